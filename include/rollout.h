@@ -1,0 +1,188 @@
+/*
+ * rollout.h -- C ABI of the MI355X rollout library (librollout.so).
+ *
+ * The library implements the data-parallel hot path of a PPO-RLHF step as the
+ * NeMo-Aligner paper states it: response generation for a batch of prompts,
+ * one token per forward pass per sequence over a KV cache held next to the
+ * weights (Section 3.2), then log-probabilities of every rollout under the
+ * actor and under the frozen reference policy -- the same network with other
+ * weights (Section 3.1) -- and the per-token KL penalty term between the two
+ * (Section 2.2 step 3; coefficient 0.003 in Section 3.3).
+ *
+ * Conventions for every call
+ *  - Return value 0 (RL_OK) on success, a negative RL_E* code otherwise.  No
+ *    call throws or aborts; rollout_last_error() returns thread-local text for
+ *    the last failure on the calling thread.
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device,
+ *    "host" pointers are ordinary host memory.  The caller owns ALL device
+ *    memory: weights, KV pool, workspace, inputs and outputs.  The library only
+ *    borrows those pointers (they must outlive the context) and owns nothing
+ *    but a small host-side state object.  It never allocates device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *    GPU work of a call is queued on it; calls return without waiting and the
+ *    caller synchronises.  Calls on one context must not overlap.
+ *  - Model: Llama-style decoder (pre-norm RMSNorm, rotary embedding with
+ *    half-split pairing (j, j + head_dim/2), grouped-query attention, SwiGLU
+ *    FFN, untied embedding / LM head, no biases).  Weight matrices are row-major
+ *    [out_features, in_features] and are applied as y = x * W^T.
+ *  - Token ids are int32; log-probs and KL are fp32 whatever the weight dtype.
+ */
+#ifndef ROLLOUT_H
+#define ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RL_OK = 0,
+    RL_EINVAL = -1,        /* bad argument or unsupported configuration */
+    RL_ENOMEM_PAGES = -2,  /* KV page pool exhausted */
+    RL_ESTATE = -3,        /* call not valid in the context's current state */
+    RL_EHIP = -4,          /* a HIP runtime call failed */
+    RL_ENOSPACE = -5       /* workspace / pool buffer smaller than required */
+};
+
+enum { RL_FP32 = 0, RL_BF16 = 1 };
+
+typedef struct rl_ctx rl_ctx; /* opaque */
+
+typedef struct rl_model_cfg {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rope_base;          /* theta_j = rope_base^(-2j/head_dim) */
+    float rms_eps;
+    int32_t dtype;            /* RL_FP32 or RL_BF16: dtype of weights, KV cache and GEMM inputs */
+    int32_t max_batch;        /* most sequences alive at once */
+    int32_t max_seq;          /* longest sequence, prompt + generated tokens */
+    int32_t page_tokens;      /* tokens per KV page (16) */
+    int32_t max_chunk_tokens; /* most tokens one prefill / scoring pass holds at once; >= max_seq */
+    int64_t n_pages;          /* pages in the KV pool (shared by all layers: page p of every layer
+                                 belongs to the same sequence) */
+} rl_model_cfg;
+
+/* One weight set.  Every pointer is dev unless location says otherwise.  The six
+ * per-layer members are HOST arrays of n_layers dev pointers. */
+typedef struct rl_weights {
+    const void* tok_embed;          /* [vocab, d_model] */
+    const void* final_norm;         /* [d_model] */
+    const void* lm_head;            /* [vocab, d_model] */
+    const void* const* attn_norm;   /* [d_model] */
+    const void* const* wqkv;        /* [(n_q_heads + 2 n_kv_heads) head_dim, d_model]: q heads, k heads, v heads */
+    const void* const* wo;          /* [d_model, n_q_heads head_dim] */
+    const void* const* ffn_norm;    /* [d_model] */
+    const void* const* w_gate_up;   /* [2 d_ffn, d_model]: gate rows then up rows */
+    const void* const* w_down;      /* [d_model, d_ffn] */
+    int32_t location;               /* 0 = device resident.  Other values are rejected (RL_EINVAL). */
+} rl_weights;
+
+typedef struct rl_sample_cfg {
+    uint64_t seed;
+    float temperature;   /* 0 = greedy arg-max (lowest id on ties); > 0 = inverse-CDF sampling of
+                            softmax(z / temperature) in vocabulary order */
+    int32_t eos_id;      /* -1 = never stop */
+    int64_t seq_id_base; /* sequence b draws uniform U(seed, seq_id_base + b, n) for its n-th token */
+} rl_sample_cfg;
+
+/* Bytes the caller must provide as `workspace` / `kv_pool` for this configuration
+ * (0 if cfg is NULL or invalid). */
+size_t rollout_workspace_bytes(const rl_model_cfg* cfg);
+size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg);
+
+/* Create a context that generates with `policy` (Section 3.2: the engine keeps
+ * weights, KV cache and activations resident).  workspace and kv_pool are dev
+ * buffers of at least the sizes above, 256-byte aligned; their contents are
+ * scratch owned by the context until rollout_destroy.  Blocks until the
+ * context's tables are initialised.  Errors: RL_EINVAL (NULL, n_q_heads %
+ * n_kv_heads != 0, head_dim not 64/128, d_model or d_ffn not a multiple of 64,
+ * page_tokens != 16, max_chunk_tokens < max_seq, ...), RL_ENOSPACE, RL_EHIP. */
+int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy,
+                 void* workspace, size_t workspace_bytes,
+                 void* kv_pool, size_t kv_pool_bytes, rl_ctx** out);
+
+/* Start B new sequences (dropping any earlier ones): cache tokens [0, P_b - 1)
+ * of every prompt in the paged KV cache and remember the prompt's last token as
+ * the next decode input, so that every generated token -- the first included --
+ * comes out of one forward pass in rollout_decode_step (Section 3.2).
+ * prompt_ids: dev int32 [B, Pmax] row-major, entries at or beyond prompt_len[b]
+ * ignored.  prompt_len: host int32 [B], 1 <= P_b <= Pmax.  Errors: RL_EINVAL
+ * (B > max_batch, P_b out of range), RL_ENOMEM_PAGES.  Token ids outside
+ * [0, vocab) are reported by the next rollout_check. */
+int rollout_prefill(rl_ctx* ctx, const int32_t* prompt_ids, const int32_t* prompt_len,
+                    int32_t B, int32_t Pmax, void* stream);
+
+/* One forward pass for every live sequence: feed tok_in[b] (dev int32 [B]) or,
+ * if tok_in is NULL, the token remembered from the previous step / prefill;
+ * append its K/V to the cache; sample the next token into tok_out[b] (dev int32
+ * [B], may be NULL) and its temperature-1 log-probability into logp_out[b] (dev
+ * fp32 [B], may be NULL).  A sequence that has emitted eos_id keeps emitting
+ * eos_id with log-prob 0.  Errors: RL_ESTATE (no prefill yet), RL_EINVAL
+ * (sequence would exceed max_seq), RL_ENOMEM_PAGES. */
+int rollout_decode_step(rl_ctx* ctx, const rl_sample_cfg* sample, const int32_t* tok_in,
+                        int32_t* tok_out, float* logp_out, void* stream);
+
+/* rollout_prefill followed by G decode steps.  out_ids: dev int32 [B, G];
+ * out_len: dev int32 [B] or NULL, tokens generated up to and including the first
+ * eos_id (G if none); out_logp: dev fp32 [B, G] or NULL. */
+int rollout_generate(rl_ctx* ctx, const rl_sample_cfg* sample,
+                     const int32_t* prompt_ids, const int32_t* prompt_len,
+                     int32_t B, int32_t Pmax, int32_t G,
+                     int32_t* out_ids, int32_t* out_len, float* out_logp, void* stream);
+
+/* Teacher-forced scoring (the "log-probs calculation" stage, Section 3.1 and the
+ * stage tables of Section 3.3).  For every sequence b of length L_b and every
+ * t in [1, L_b):  logp[b,t] = log softmax(z_{t-1})[ids[b,t]]  under `policy`
+ * and under `reference`;  kl[b,t] = logp_policy - logp_ref on response
+ * positions t in [prompt_len[b], L_b), and kl_penalty = kl_coef * kl.  Every
+ * other entry of the [B, Lmax] outputs is written as 0.  No [tokens, vocab]
+ * array is ever written to memory.
+ * ids: dev int32 [B, Lmax]; seq_len, prompt_len: host int32 [B], 1 <= L_b <=
+ * min(Lmax, max_seq), 0 <= prompt_len[b] <= L_b.  Outputs: dev fp32 [B, Lmax],
+ * any may be NULL.  reference may be NULL (policy pass only; logp_ref, kl and
+ * kl_penalty must then be NULL).  Does not touch the KV cache of live sequences.
+ * Errors: RL_EINVAL. */
+int score_logprobs_kl(rl_ctx* ctx, const rl_weights* policy, const rl_weights* reference,
+                      const int32_t* ids, const int32_t* seq_len, const int32_t* prompt_len,
+                      int32_t B, int32_t Lmax, float kl_coef,
+                      float* logp_policy, float* logp_ref, float* kl, float* kl_penalty,
+                      void* stream);
+
+/* Wait for `stream` and report device-side findings since the last check:
+ * RL_EINVAL if a token id outside [0, vocab) was seen (it was clamped), RL_EHIP
+ * if the stream is in error. */
+int rollout_check(rl_ctx* ctx, void* stream);
+
+/* Forget all sequences and return every page to the pool. */
+int rollout_reset(rl_ctx* ctx);
+void rollout_destroy(rl_ctx* ctx);
+const char* rollout_last_error(void);
+
+/* ---- implementation switches and measurement hooks (not part of the method) ---- */
+
+/* impl 0 = plain reference kernels for every step (any dtype);
+ * impl 1 = tuned gfx950 kernels where they exist (bf16 MFMA GEMMs, MFMA
+ * attention, fused LM-head log-sum-exp).  Default 1 for bf16, 0 for fp32. */
+int rollout_set_impl(rl_ctx* ctx, int32_t impl);
+
+/* Kernel classes for timing. */
+enum {
+    RL_K_GEMM_DECODE = 0,   /* weight-streaming GEMMs of a decode step */
+    RL_K_ATTN_DECODE = 1,   /* paged GQA decode attention */
+    RL_K_GEMM_PREFILL = 2,  /* large-M GEMMs of prefill / scoring */
+    RL_K_ATTN_PREFILL = 3,  /* causal prefill attention */
+    RL_K_LMHEAD_SCORE = 4,  /* fused LM head + log-sum-exp + gather */
+    RL_K_COUNT = 5
+};
+/* When on, every launch of that class is bracketed by HIP events on the launch
+ * stream (up to an internal cap; later launches go untimed). */
+int rollout_profile_enable(rl_ctx* ctx, int32_t kernel_class, int32_t on);
+/* Waits for the recorded events; returns summed milliseconds and launch count,
+ * then clears the records.  total_ms / launches: host. */
+int rollout_profile_read(rl_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLLOUT_H */

@@ -1,0 +1,547 @@
+// Plain reference kernels for every step of the rollout path (any dtype) plus the
+// small bookkeeping kernels (packing, paging, sampling, log-sum-exp, KL).
+// The formulas are the standard Llama-style decoder ones; the paper (Sections 3.1-3.2)
+// only names the stages.
+#include "rl_common.h"
+
+// ---------------------------------------------------------------- fills / tables
+__global__ void fill_i32_kernel(int* p, int v, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ void fill_f32_kernel(float* p, float v, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+void k_fill_i32(int* p, int v, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(p, v, n);
+}
+void k_fill_f32(float* p, float v, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    fill_f32_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(p, v, n);
+}
+
+// cos/sin of pos * base^(-2j/hd), evaluated in fp64 and rounded once to fp32.
+__global__ void rope_table_kernel(float2* tab, int max_seq, int half, double log_base, int hd) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= max_seq * half) return;
+    int pos = i / half, j = i % half;
+    double theta = exp(-2.0 * (double)j / (double)hd * log_base);
+    double ang = (double)pos * theta;
+    tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+void k_rope_table(float2* tab, int max_seq, int hd, float base, hipStream_t s) {
+    int n = max_seq * (hd / 2);
+    rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(tab, max_seq, hd / 2, log((double)base), hd);
+}
+
+// block_table[slot][idx] = page for up to 64 (slot, idx, page) triples passed by value.
+struct PageTriples { int v[192]; };
+__global__ void set_pages_kernel(int* bt, int mpps, PageTriples t, int n) {
+    int i = threadIdx.x;
+    if (i < n) bt[(int64_t)t.v[3 * i] * mpps + t.v[3 * i + 1]] = t.v[3 * i + 2];
+}
+void k_set_pages(int* block_table, int mpps, const int* triples_host, int n_triples, hipStream_t s) {
+    for (int o = 0; o < n_triples; o += 64) {
+        PageTriples t;
+        int n = n_triples - o < 64 ? n_triples - o : 64;
+        for (int i = 0; i < 3 * n; ++i) t.v[i] = triples_host[3 * o + i];
+        set_pages_kernel<<<1, 64, 0, s>>>(block_table, mpps, t, n);
+    }
+}
+
+// ---------------------------------------------------------------- token bookkeeping
+__global__ void step_begin_kernel(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok,
+                                  int* tok_pos, int* tok_slot, int B) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    cur_tok[b] = tok_in ? tok_in[b] : last_tok[b];
+    tok_pos[b] = seq_len[b];
+    tok_slot[b] = b;
+}
+void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok, int* tok_pos,
+                  int* tok_slot, int B, hipStream_t s) {
+    step_begin_kernel<<<(B + 255) / 256, 256, 0, s>>>(tok_in, last_tok, seq_len, cur_tok, tok_pos, tok_slot, B);
+}
+
+// Pack rows of a padded [*, ld_ids] id matrix into a flat token list.
+// Row r of the chunk is batch row seq_first[r]; its row_len[r] tokens go to
+// [row_start[r], row_start[r] + row_len[r]).  tok_tgt (optional) = next token id of the
+// same row, or -1 when there is none inside full_len[r].
+__global__ void pack_tokens_kernel(const int* ids, int ld_ids, const int* seq_first, const int* row_start,
+                                   const int* row_len, const int* full_len, int* tok_ids, int* tok_pos,
+                                   int* tok_slot, int* tok_tgt) {
+    int r = blockIdx.x;
+    int b = seq_first[r], st = row_start[r], len = row_len[r];
+    const int* src = ids + (int64_t)b * ld_ids;
+    for (int t = threadIdx.x; t < len; t += blockDim.x) {
+        tok_ids[st + t] = src[t];
+        tok_pos[st + t] = t;
+        tok_slot[st + t] = b;
+        if (tok_tgt) tok_tgt[st + t] = (t + 1 < full_len[r]) ? src[t + 1] : -1;
+    }
+}
+void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_start, const int* row_len,
+                   const int* full_len, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
+                   hipStream_t s) {
+    if (nrows <= 0) return;
+    pack_tokens_kernel<<<nrows, 256, 0, s>>>(ids, ld_ids, seq_first, row_start, row_len, full_len, tok_ids, tok_pos,
+                                             tok_slot, tok_tgt);
+}
+
+// After prefill of the first P-1 prompt tokens: remember the last prompt token, lengths, counters.
+__global__ void prefill_state_kernel(const int* ids, int ld_ids, const int* prompt_len, int* last_tok, int* seq_len,
+                                     int* gen_count, int* finished, int B) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int P = prompt_len[b];
+    last_tok[b] = ids[(int64_t)b * ld_ids + P - 1];
+    seq_len[b] = P - 1;
+    gen_count[b] = 0;
+    finished[b] = 0;
+}
+void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_tok, int* seq_len, int* gen_count,
+                     int* finished, int B, hipStream_t s) {
+    prefill_state_kernel<<<(B + 255) / 256, 256, 0, s>>>(ids, ld_ids, row_len, last_tok, seq_len, gen_count,
+                                                         finished, B);
+}
+
+__global__ void out_len_kernel(const int* gen_count, int* out_len, int B) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) out_len[b] = gen_count[b];
+}
+void k_out_len(const int* gen_count, int* out_len, int B, hipStream_t s) {
+    out_len_kernel<<<(B + 255) / 256, 256, 0, s>>>(gen_count, out_len, B);
+}
+
+// ---------------------------------------------------------------- embedding gather
+template <typename T>
+__global__ void embed_kernel(const int* ids, const T* E, int d, int V, float* x, int* errflag) {
+    int n = blockIdx.x;
+    int id = ids[n];
+    if (id < 0 || id >= V) {
+        if (threadIdx.x == 0) atomicOr(errflag, 1);
+        id = id < 0 ? 0 : V - 1;
+    }
+    const T* row = E + (int64_t)id * d;
+    float* xo = x + (int64_t)n * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) xo[j] = to_f(row[j]);
+}
+void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, float* x, int* errflag, hipStream_t s) {
+    if (n <= 0) return;
+    if (dtype == 0) embed_kernel<float><<<n, 256, 0, s>>>(ids, (const float*)E, d, V, x, errflag);
+    else embed_kernel<bf16_t><<<n, 256, 0, s>>>(ids, (const bf16_t*)E, d, V, x, errflag);
+}
+
+// ---------------------------------------------------------------- RMSNorm: out = x * rsqrt(mean(x^2) + eps) * g
+template <typename T, typename TW>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* g, T* out, int d, float eps) {
+    __shared__ float red[16];
+    int n = blockIdx.x;
+    const float* xr = x + (int64_t)n * d;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) { float v = xr[j]; ss += v * v; }
+    ss = block_sum(ss, red);
+    float rs = 1.0f / sqrtf(ss / (float)d + eps);
+    T* o = out + (int64_t)n * d;
+    for (int j = threadIdx.x; j < d; j += 256) o[j] = from_f<T>(xr[j] * rs * to_f(g[j]));
+}
+void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s) {
+    if (n <= 0) return;
+    if (dtype == 0) rmsnorm_kernel<float, float><<<n, 256, 0, s>>>(x, (const float*)g, (float*)out, d, eps);
+    else rmsnorm_kernel<f16_t, bf16_t><<<n, 256, 0, s>>>(x, (const bf16_t*)g, (f16_t*)out, d, eps);
+}
+
+// ---------------------------------------------------------------- plain tiled GEMM  C = A[M,K] * W[N,K]^T
+// 64x64 output tile, 16-wide k slab, 256 threads each 4x4, fp32 FMA accumulation.
+template <typename T, typename TW, int EPI>
+__global__ __launch_bounds__(256) void gemm_simple_kernel(const T* __restrict__ A, int lda, const TW* __restrict__ W,
+                                                          const TW* __restrict__ W2, int M, int N, int K,
+                                                          float* outF, T* outT, int ldc) {
+    __shared__ float As[16][65];
+    __shared__ float Ws[16][65];
+    __shared__ float W2s[EPI == EPI_SWIGLU ? 16 : 1][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4] = {}, acc2[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int idx = tid + i * 256, r = idx >> 4, kk = idx & 15;
+            int k = k0 + kk;
+            As[kk][r] = (m0 + r < M && k < K) ? to_f(A[(int64_t)(m0 + r) * lda + k]) : 0.f;
+            Ws[kk][r] = (n0 + r < N && k < K) ? to_f(W[(int64_t)(n0 + r) * K + k]) : 0.f;
+            if (EPI == EPI_SWIGLU) W2s[kk][r] = (n0 + r < N && k < K) ? to_f(W2[(int64_t)(n0 + r) * K + k]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4], b2[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+            if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) b2[i] = W2s[kk][tx * 4 + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] += a[i] * b[j];
+                    if (EPI == EPI_SWIGLU) acc2[i][j] += a[i] * b2[j];
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            int64_t o = (int64_t)m * ldc + n;
+            float v = acc[i][j];
+            if (EPI == EPI_STORE_F32) outF[o] = v;
+            else if (EPI == EPI_STORE_T) outT[o] = from_f<T>(v);
+            else if (EPI == EPI_RESID) outF[o] += v;
+            else { float u = acc2[i][j]; outT[o] = from_f<T>(v / (1.0f + __expf(-v)) * u); }
+        }
+    }
+}
+template <typename T, typename TW>
+static void gemm_simple_t(int epi, const T* A, int lda, const TW* W, const TW* W2, int M, int N, int K, float* outF,
+                          T* outT, int ldc, hipStream_t s) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    switch (epi) {
+        case EPI_STORE_F32: gemm_simple_kernel<T, TW, EPI_STORE_F32><<<grid, 256, 0, s>>>(A, lda, W, W2, M, N, K, outF, outT, ldc); break;
+        case EPI_STORE_T: gemm_simple_kernel<T, TW, EPI_STORE_T><<<grid, 256, 0, s>>>(A, lda, W, W2, M, N, K, outF, outT, ldc); break;
+        case EPI_RESID: gemm_simple_kernel<T, TW, EPI_RESID><<<grid, 256, 0, s>>>(A, lda, W, W2, M, N, K, outF, outT, ldc); break;
+        default: gemm_simple_kernel<T, TW, EPI_SWIGLU><<<grid, 256, 0, s>>>(A, lda, W, W2, M, N, K, outF, outT, ldc); break;
+    }
+}
+void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,
+                   float* outF, void* outT, int ldc, hipStream_t s) {
+    if (M <= 0 || N <= 0) return;
+    if (dtype == 0) gemm_simple_t<float, float>(epi, (const float*)A, lda, (const float*)W, (const float*)W2, M, N, K, outF, (float*)outT, ldc, s);
+    else gemm_simple_t<f16_t, bf16_t>(epi, (const f16_t*)A, lda, (const bf16_t*)W, (const bf16_t*)W2, M, N, K, outF, (f16_t*)outT, ldc, s);
+}
+
+// ---------------------------------------------------------------- RoPE + split + KV append
+// qkv fp32 [n, (Hq+2Hkv) hd] -> rotated q (T) [n, Hq hd]; rotated k and plain v to the
+// contiguous buffers (optional) and to the page slot of (slot, pos) (optional).
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* qkv, const int* tok_pos, const int* tok_slot,
+                                                          const float2* rope, T* q_out, T* k_out, T* v_out, T* pool,
+                                                          int layer, KvGeom geo, const int* bt, int mpps, int Hq) {
+    const int n = blockIdx.x, hd = geo.hd, half = hd / 2, Hkv = geo.Hkv;
+    const int pos = tok_pos[n];
+    const float* row = qkv + (int64_t)n * (Hq + 2 * Hkv) * hd;
+    const float2* rt = rope + (int64_t)pos * half;
+    int64_t page = 0;
+    int slot_tok = 0;
+    if (pool) {
+        page = bt[(int64_t)tok_slot[n] * mpps + pos / geo.PT];
+        slot_tok = pos % geo.PT;
+    }
+    // q heads
+    for (int i = threadIdx.x; i < Hq * half; i += 256) {
+        int h = i / half, j = i % half;
+        float a = row[h * hd + j], b = row[h * hd + j + half];
+        float2 cs = rt[j];
+        T* o = q_out + (int64_t)n * Hq * hd + h * hd;
+        o[j] = from_f<T>(a * cs.x - b * cs.y);
+        o[j + half] = from_f<T>(b * cs.x + a * cs.y);
+    }
+    // k heads
+    const float* krow = row + Hq * hd;
+    for (int i = threadIdx.x; i < Hkv * half; i += 256) {
+        int g = i / half, j = i % half;
+        float a = krow[g * hd + j], b = krow[g * hd + j + half];
+        float2 cs = rt[j];
+        T r0 = from_f<T>(a * cs.x - b * cs.y), r1 = from_f<T>(b * cs.x + a * cs.y);
+        if (k_out) {
+            T* o = k_out + (int64_t)n * Hkv * hd + g * hd;
+            o[j] = r0; o[j + half] = r1;
+        }
+        if (pool) {
+            pool[geo.k_off(layer, page, g, slot_tok, j)] = r0;
+            pool[geo.k_off(layer, page, g, slot_tok, j + half)] = r1;
+        }
+    }
+    // v heads
+    const float* vrow = row + (Hq + Hkv) * hd;
+    for (int i = threadIdx.x; i < Hkv * hd; i += 256) {
+        int g = i / hd, dd = i % hd;
+        T v = from_f<T>(vrow[i]);
+        if (v_out) v_out[(int64_t)n * Hkv * hd + i] = v;
+        if (pool) pool[geo.v_off(layer, page, g, slot_tok, dd)] = v;
+    }
+}
+void k_rope_append(int dtype, const float* qkv, int n, const int* tok_pos, const int* tok_slot, const float2* rope,
+                   void* q_out, void* k_out, void* v_out, void* pool, int layer, KvGeom geo, const int* block_table,
+                   int mpps, int Hq, hipStream_t s) {
+    if (n <= 0) return;
+    if (dtype == 0)
+        rope_append_kernel<float><<<n, 256, 0, s>>>(qkv, tok_pos, tok_slot, rope, (float*)q_out, (float*)k_out,
+                                                    (float*)v_out, (float*)pool, layer, geo, block_table, mpps, Hq);
+    else
+        rope_append_kernel<f16_t><<<n, 256, 0, s>>>(qkv, tok_pos, tok_slot, rope, (f16_t*)q_out, (f16_t*)k_out,
+                                                    (f16_t*)v_out, (f16_t*)pool, layer, geo, block_table, mpps, Hq);
+}
+
+// ---------------------------------------------------------------- plain attention
+// One block per (query token, query head).  Keys 0..pos of the query's own sequence,
+// read either from contiguous [tokens, Hkv, hd] buffers (the sequence's tokens are
+// consecutive, so key m sits at row n - pos + m) or from the paged pool.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_simple_kernel(const T* q, const T* kc, const T* vc, const T* pool,
+                                                          int layer, KvGeom geo, const int* bt, int mpps,
+                                                          const int* tok_pos, const int* tok_slot, T* out, int Hq) {
+    extern __shared__ float sm[];
+    const int hd = geo.hd, Hkv = geo.Hkv;
+    const int n = blockIdx.x, h = blockIdx.y, g = h / (Hq / Hkv);
+    const int pos = tok_pos[n], ctx = pos + 1;
+    float* qs = sm;            // [hd]
+    float* red = sm + hd;      // [16]
+    float* part = red + 16;    // [256]
+    float* sc = part + 256;    // [ctx]
+    const int* btr = pool ? bt + (int64_t)tok_slot[n] * mpps : nullptr;
+    for (int j = threadIdx.x; j < hd; j += 256) qs[j] = to_f(q[((int64_t)n * Hq + h) * hd + j]);
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)hd);
+    float lmax = -INFINITY;
+    for (int m = threadIdx.x; m < ctx; m += 256) {
+        float dot = 0.f;
+        if (pool) {
+            int64_t base = geo.k_off(layer, btr[m / geo.PT], g, m % geo.PT, 0);
+            for (int j = 0; j < hd; ++j) dot += qs[j] * to_f(pool[base + j]);
+        } else {
+            const T* kr = kc + ((int64_t)(n - pos + m) * Hkv + g) * hd;
+            for (int j = 0; j < hd; ++j) dot += qs[j] * to_f(kr[j]);
+        }
+        dot *= scale;
+        sc[m] = dot;
+        lmax = fmaxf(lmax, dot);
+    }
+    float mx = block_max(lmax, red);
+    float ls = 0.f;
+    for (int m = threadIdx.x; m < ctx; m += 256) { float e = __expf(sc[m] - mx); sc[m] = e; ls += e; }
+    float tot = block_sum(ls, red);   // has barriers: sc[] visible afterwards
+    const int dd = threadIdx.x % hd, grp = threadIdx.x / hd, ngrp = 256 / hd;
+    float acc = 0.f;
+    for (int m = grp; m < ctx; m += ngrp) {
+        float v;
+        if (pool) v = to_f(pool[geo.v_off(layer, btr[m / geo.PT], g, m % geo.PT, dd)]);
+        else v = to_f(vc[((int64_t)(n - pos + m) * Hkv + g) * hd + dd]);
+        acc += sc[m] * v;
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < hd) {
+        float o = 0.f;
+        for (int i = 0; i < ngrp; ++i) o += part[i * hd + threadIdx.x];
+        out[((int64_t)n * Hq + h) * hd + threadIdx.x] = from_f<T>(o / tot);
+    }
+}
+void k_attn_simple(int dtype, const void* q, const void* kc, const void* vc, const void* pool, int layer, KvGeom geo,
+                   const int* block_table, int mpps, const int* tok_pos, const int* tok_slot, void* out, int n,
+                   int Hq, int max_ctx, hipStream_t s) {
+    if (n <= 0) return;
+    size_t lds = (size_t)(geo.hd + 16 + 256 + max_ctx) * sizeof(float);
+    dim3 grid(n, Hq);
+    if (dtype == 0)
+        attn_simple_kernel<float><<<grid, 256, lds, s>>>((const float*)q, (const float*)kc, (const float*)vc,
+                                                         (const float*)pool, layer, geo, block_table, mpps, tok_pos,
+                                                         tok_slot, (float*)out, Hq);
+    else
+        attn_simple_kernel<f16_t><<<grid, 256, lds, s>>>((const f16_t*)q, (const f16_t*)kc, (const f16_t*)vc,
+                                                         (const f16_t*)pool, layer, geo, block_table, mpps, tok_pos,
+                                                         tok_slot, (f16_t*)out, Hq);
+}
+
+// ---------------------------------------------------------------- sampling
+// Counter-based uniform: two rounds of the splitmix64 output function over
+// (seed, sequence id, step); top 24 bits -> [0,1).  Integer-only, so the CPU
+// checker reproduces it bit for bit.
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ float hash_uniform(uint64_t seed, uint64_t seq, uint64_t step) {
+    const uint64_t G = 0x9E3779B97F4A7C15ull;
+    uint64_t h = mix64(seed + G * (seq + 1));
+    h = mix64(h + G * (step + 1));
+    return (float)(h >> 40) * (1.0f / 16777216.0f);
+}
+
+// Row statistics shared by sampling and scoring: max, arg-max (lowest index on ties).
+struct ArgMax { float v; int i; };
+__device__ __forceinline__ ArgMax argmax_combine(ArgMax a, ArgMax b) {
+    if (b.v > a.v || (b.v == a.v && b.i < a.i)) return b;
+    return a;
+}
+__device__ ArgMax block_argmax(const float* z, int V, ArgMax* red) {
+    ArgMax a{-INFINITY, 0x7fffffff};
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+        float v = z[i];
+        if (v > a.v) { a.v = v; a.i = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ArgMax b{__shfl_xor(a.v, o, RL_WAVE), __shfl_xor(a.i, o, RL_WAVE)};
+        a = argmax_combine(a, b);
+    }
+    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = a;
+    __syncthreads();
+    ArgMax r = red[0];
+    for (int i = 1; i < nw; ++i) r = argmax_combine(r, red[i]);
+    __syncthreads();
+    return r;
+}
+
+// One block of 1024 threads per sequence.  Wave w owns the contiguous vocabulary
+// segment [w*seg, (w+1)*seg); sums are formed lane-column-wise then reduced, in a
+// fixed order, so results are reproducible run to run.
+__global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int ldz, int V, SampleArgs a, int* last_tok,
+                                                      int* seq_len, int* gen_count, int* finished, int* tok_out,
+                                                      float* logp_out, int* out_ids, float* out_logp,
+                                                      int out_stride) {
+    __shared__ ArgMax ared[16];
+    __shared__ float ws1[16], wsT[16];
+    __shared__ int s_tok;
+    const int b = blockIdx.x;
+    const float* z = logits + (int64_t)b * ldz;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    ArgMax am = block_argmax(z, V, ared);
+    const float mx = am.v;
+    const bool greedy = !(a.temperature > 0.f);
+    const float invT = greedy ? 1.0f : 1.0f / a.temperature;
+    int seg = (V + 15) / 16;
+    seg = (seg + 63) / 64 * 64;
+    const int s0 = w * seg, s1 = min(V, s0 + seg);
+    float c1 = 0.f, cT = 0.f;
+    for (int i = s0 + lane; i < s1; i += 64) {
+        float dz = z[i] - mx;
+        c1 += __expf(dz);
+        cT += __expf(dz * invT);
+    }
+    c1 = wave_sum(c1);
+    cT = wave_sum(cT);
+    if (lane == 0) { ws1[w] = c1; wsT[w] = cT; }
+    if (threadIdx.x == 0) s_tok = greedy ? am.i : V - 1;
+    __syncthreads();
+    float tot1 = 0.f, totT = 0.f;
+    for (int i = 0; i < 16; ++i) { tot1 += ws1[i]; totT += wsT[i]; }
+    const int n_gen = gen_count[b];
+    if (!greedy) {
+        float u = hash_uniform(a.seed, (uint64_t)(a.seq_base + b), (uint64_t)n_gen);
+        float target = u * totT;
+        float cum = 0.f;
+        int wsel = -1;
+        float before = 0.f;
+        for (int i = 0; i < 16; ++i) {
+            float nc = cum + wsT[i];
+            if (wsel < 0 && nc > target) { wsel = i; before = cum; }
+            cum = nc;
+        }
+        if (w == wsel) {
+            float run = before;
+            int found = -1;
+            for (int r0 = s0; r0 < s1 && found < 0; r0 += 64) {
+                int i = r0 + lane;
+                float e = (i < s1) ? __expf((z[i] - mx) * invT) : 0.f;
+                float rowsum = wave_sum(e);
+                if (run + rowsum > target) {
+                    float pe = e;   // inclusive prefix over lanes
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        float t = __shfl_up(pe, o, RL_WAVE);
+                        if (lane >= o) pe += t;
+                    }
+                    unsigned long long m = __ballot((run + pe > target) && (i < s1));
+                    if (m) found = r0 + __ffsll((long long)m) - 1;
+                    else run += rowsum;
+                } else {
+                    run += rowsum;
+                }
+            }
+            if (found < 0) found = s1 - 1;   // crossing falls on the segment end within rounding
+            if (lane == 0) s_tok = found;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tok = s_tok;
+        float lp = z[tok] - mx - logf(tot1);
+        const bool fin = finished[b] != 0;
+        if (fin) { tok = a.eos_id; lp = 0.f; }
+        else {
+            gen_count[b] = n_gen + 1;
+            if (a.eos_id >= 0 && tok == a.eos_id) finished[b] = 1;
+        }
+        last_tok[b] = tok;
+        seq_len[b] = seq_len[b] + 1;
+        if (tok_out) tok_out[b] = tok;
+        if (logp_out) logp_out[b] = lp;
+        if (out_ids) out_ids[(int64_t)b * out_stride] = tok;
+        if (out_logp) out_logp[(int64_t)b * out_stride] = lp;
+    }
+}
+void k_sample(const float* logits, int ldz, int V, int B, SampleArgs a, int* last_tok, int* seq_len, int* gen_count,
+              int* finished, int* tok_out, float* logp_out, int* out_ids, float* out_logp, int out_stride,
+              hipStream_t s) {
+    if (B <= 0) return;
+    sample_kernel<<<B, 1024, 0, s>>>(logits, ldz, V, a, last_tok, seq_len, gen_count, finished, tok_out, logp_out,
+                                     out_ids, out_logp, out_stride);
+}
+
+// ---------------------------------------------------------------- log-sum-exp + gather over materialised logits
+// logp_out[slot, pos + 1] = z[target] - log sum_v exp(z_v) for rows with a target.
+__global__ __launch_bounds__(1024) void lse_gather_kernel(const float* logits, int ldz, int V, const int* tok_tgt,
+                                                          const int* tok_slot, const int* tok_pos, float* logp_out,
+                                                          int ld_out) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    const int tgt = tok_tgt[r];
+    if (tgt < 0) return;
+    const float* z = logits + (int64_t)r * ldz;
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += 1024) m = fmaxf(m, z[i]);
+    m = block_max(m, red);
+    float su = 0.f;
+    for (int i = threadIdx.x; i < V; i += 1024) su += __expf(z[i] - m);
+    su = block_sum(su, red);
+    if (threadIdx.x == 0) {
+        int t = min(max(tgt, 0), V - 1);
+        logp_out[(int64_t)tok_slot[r] * ld_out + tok_pos[r] + 1] = z[t] - m - logf(su);
+    }
+}
+void k_lse_gather(const float* logits, int ldz, int V, int nrows, const int* tok_tgt, const int* tok_slot,
+                  const int* tok_pos, float* logp_out, int ld_out, hipStream_t s) {
+    if (nrows <= 0) return;
+    lse_gather_kernel<<<nrows, 1024, 0, s>>>(logits, ldz, V, tok_tgt, tok_slot, tok_pos, logp_out, ld_out);
+}
+
+// ---------------------------------------------------------------- KL term on response positions
+__global__ void kl_kernel(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int Lmax,
+                          float coef, float* kl, float* pen) {
+    int b = blockIdx.y;
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= Lmax) return;
+    int64_t o = (int64_t)b * Lmax + t;
+    int lo = max(prompt_len[b], 1);
+    float v = (t >= lo && t < seq_len[b]) ? lp[o] - lr[o] : 0.f;
+    if (kl) kl[o] = v;
+    if (pen) pen[o] = coef * v;
+}
+void k_kl(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int B, int Lmax, float coef,
+          float* kl, float* pen, hipStream_t s) {
+    if (B <= 0 || Lmax <= 0) return;
+    dim3 grid((Lmax + 255) / 256, B);
+    kl_kernel<<<grid, 256, 0, s>>>(lp, lr, seq_len, prompt_len, Lmax, coef, kl, pen);
+}

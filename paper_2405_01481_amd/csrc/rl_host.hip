@@ -1,0 +1,620 @@
+// Host side of librollout: context, workspace layout, page allocator, the
+// generation / scoring step sequences, and the C ABI declared in include/rollout.h.
+#include "rl_common.h"
+#include "../../include/rollout.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+// ---------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+#define HIP_TRY(expr)                                                                            \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) return fail(RL_EHIP, "%s: %s", #expr, hipGetErrorString(e_));      \
+    } while (0)
+
+// ---------------------------------------------------------------- workspace layout
+struct Layout {
+    size_t x, h, qkv, q, kbuf, vbuf, attn, ffn, logits, rope, block_table;
+    size_t last_tok, seq_len, gen_count, finished, cur_tok;
+    size_t tok_ids, tok_pos, tok_slot, tok_tgt;
+    size_t seq_first, row_start, row_len, full_len, d_seq_len, d_prompt_len, errflag;
+    size_t splitk, attn_part, attn_ml, lse_part;
+    size_t total;
+    int rows, logit_rows, mpps, nqkv;
+};
+
+static size_t esz_of(int dtype) { return dtype == RL_FP32 ? 4 : 2; }
+
+static const int kLogitRowsScore = 512;    // rows of logits materialised at a time by the plain scoring path
+static const int kMaxSplitK = 16;
+static const int kMaxAttnSplits = 16;
+
+static Layout make_layout(const rl_model_cfg& c) {
+    Layout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += (bytes + 255) / 256 * 256;
+        return o;
+    };
+    const size_t e = esz_of(c.dtype);
+    const int rows = std::max(c.max_chunk_tokens, c.max_batch);
+    const int nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim;
+    L.rows = rows;
+    L.nqkv = nqkv;
+    L.mpps = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
+    L.logit_rows = std::max(c.max_batch, std::min(rows, kLogitRowsScore));
+    L.x = take((size_t)rows * c.d_model * 4);
+    L.h = take((size_t)rows * c.d_model * e);
+    L.qkv = take((size_t)rows * nqkv * 4);
+    L.q = take((size_t)rows * qd * e);
+    L.kbuf = take((size_t)rows * kd * e);
+    L.vbuf = take((size_t)(rows + 64) * kd * e);
+    L.attn = take((size_t)rows * qd * e);
+    L.ffn = take((size_t)rows * c.d_ffn * e);
+    L.logits = take((size_t)L.logit_rows * c.vocab * 4);
+    L.rope = take((size_t)c.max_seq * (c.head_dim / 2) * sizeof(float2));
+    L.block_table = take((size_t)c.max_batch * L.mpps * 4);
+    L.last_tok = take((size_t)c.max_batch * 4);
+    L.seq_len = take((size_t)c.max_batch * 4);
+    L.gen_count = take((size_t)c.max_batch * 4);
+    L.finished = take((size_t)c.max_batch * 4);
+    L.cur_tok = take((size_t)c.max_batch * 4);
+    L.tok_ids = take((size_t)rows * 4);
+    L.tok_pos = take((size_t)rows * 4);
+    L.tok_slot = take((size_t)rows * 4);
+    L.tok_tgt = take((size_t)rows * 4);
+    L.seq_first = take((size_t)c.max_batch * 4);
+    L.row_start = take((size_t)c.max_batch * 4);
+    L.row_len = take((size_t)c.max_batch * 4);
+    L.full_len = take((size_t)c.max_batch * 4);
+    L.d_seq_len = take((size_t)c.max_batch * 4);
+    L.d_prompt_len = take((size_t)c.max_batch * 4);
+    L.errflag = take(256);
+    // decode-path partial buffers: split-K partial sums and split-KV attention partials
+    const int maxn = std::max(std::max(nqkv, c.d_model), 1);
+    L.splitk = take((size_t)kMaxSplitK * 128 * ((c.max_batch + 127) / 128) * maxn * 4);
+    L.attn_part = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * c.head_dim * 4);
+    L.attn_ml = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * 2 * 4);
+    L.lse_part = take((size_t)rows * ((c.vocab + 127) / 128) * 2 * 4);
+    L.total = off;
+    return L;
+}
+
+static int validate_cfg(const rl_model_cfg* c) {
+    if (!c) return fail(RL_EINVAL, "cfg is NULL");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 || c->vocab < 2)
+        return fail(RL_EINVAL, "non-positive model dimension");
+    if (c->n_q_heads % c->n_kv_heads != 0) return fail(RL_EINVAL, "n_q_heads %% n_kv_heads != 0");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(RL_EINVAL, "head_dim must be 64 or 128");
+    if (c->d_model % 64 != 0 || c->d_ffn % 64 != 0) return fail(RL_EINVAL, "d_model and d_ffn must be multiples of 64");
+    if (c->dtype != RL_FP32 && c->dtype != RL_BF16) return fail(RL_EINVAL, "dtype must be RL_FP32 or RL_BF16");
+    if (c->page_tokens != 16) return fail(RL_EINVAL, "page_tokens must be 16");
+    if (c->max_batch < 1 || c->max_batch > 4096) return fail(RL_EINVAL, "max_batch out of range [1, 4096]");
+    if (c->max_seq < 2 || c->max_seq > 65536) return fail(RL_EINVAL, "max_seq out of range [2, 65536]");
+    if (c->max_chunk_tokens < c->max_seq) return fail(RL_EINVAL, "max_chunk_tokens < max_seq");
+    if (c->n_pages < 1) return fail(RL_EINVAL, "n_pages < 1");
+    if (!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f)) return fail(RL_EINVAL, "bad rope_base / rms_eps");
+    return RL_OK;
+}
+
+// ---------------------------------------------------------------- context
+struct WeightsHost {
+    const void *tok_embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+    std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+};
+
+static int copy_weights(const rl_model_cfg& c, const rl_weights* w, WeightsHost& out, const char* what) {
+    if (!w) return fail(RL_EINVAL, "%s weights are NULL", what);
+    if (w->location != 0) return fail(RL_EINVAL, "%s weights: only device-resident weights (location 0) are supported", what);
+    if (!w->tok_embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+        !w->w_gate_up || !w->w_down)
+        return fail(RL_EINVAL, "%s weights: NULL member", what);
+    out.tok_embed = w->tok_embed;
+    out.final_norm = w->final_norm;
+    out.lm_head = w->lm_head;
+    auto cp = [&](std::vector<const void*>& v, const void* const* src) {
+        v.assign(src, src + c.n_layers);
+        for (auto p : v)
+            if (!p) return false;
+        return true;
+    };
+    if (!cp(out.attn_norm, w->attn_norm) || !cp(out.wqkv, w->wqkv) || !cp(out.wo, w->wo) ||
+        !cp(out.ffn_norm, w->ffn_norm) || !cp(out.w_gate_up, w->w_gate_up) || !cp(out.w_down, w->w_down))
+        return fail(RL_EINVAL, "%s weights: NULL layer pointer", what);
+    return RL_OK;
+}
+
+struct ProfRec { hipEvent_t a, b; };
+static const size_t kProfCap = 8192;
+
+struct rl_ctx {
+    rl_model_cfg cfg;
+    Layout L;
+    char* ws = nullptr;
+    void* pool = nullptr;
+    WeightsHost policy;
+    KvGeom geo;
+    int impl = 0;
+    // sequences
+    int B = 0;                       // live sequences (0 = no prefill yet)
+    std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len)
+    std::vector<std::vector<int>> pages;
+    std::vector<int> free_pages;
+    // profiling
+    bool prof_on[RL_K_COUNT] = {};
+    std::vector<ProfRec> prof[RL_K_COUNT];
+    size_t prof_used[RL_K_COUNT] = {};
+
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+struct ProfScope {
+    rl_ctx* c; int k; hipStream_t s; ProfRec* r = nullptr;
+    ProfScope(rl_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
+        if (!c->prof_on[k] || c->prof_used[k] >= kProfCap) return;
+        if (c->prof_used[k] >= c->prof[k].size()) {
+            ProfRec nr;
+            if (hipEventCreate(&nr.a) != hipSuccess) return;
+            if (hipEventCreate(&nr.b) != hipSuccess) { (void)hipEventDestroy(nr.a); return; }
+            c->prof[k].push_back(nr);
+        }
+        r = &c->prof[k][c->prof_used[k]++];
+        (void)hipEventRecord(r->a, s);
+    }
+    ~ProfScope() { if (r) (void)hipEventRecord(r->b, s); }
+};
+
+// ---------------------------------------------------------------- page allocator (host)
+static void release_all_pages(rl_ctx* c) {
+    c->free_pages.clear();
+    for (int64_t p = c->cfg.n_pages - 1; p >= 0; --p) c->free_pages.push_back((int)p);
+    for (auto& v : c->pages) v.clear();
+    std::fill(c->cached.begin(), c->cached.end(), 0);
+}
+
+// Make sure every live slot b can hold need[b] tokens; new block-table entries are pushed to the device.
+static int ensure_pages(rl_ctx* c, const std::vector<int>& need, hipStream_t s) {
+    const int PT = c->cfg.page_tokens;
+    size_t want = 0;
+    for (int b = 0; b < (int)need.size(); ++b) {
+        size_t np = (size_t)(need[b] + PT - 1) / PT;
+        if (np > c->pages[b].size()) want += np - c->pages[b].size();
+    }
+    if (want == 0) return RL_OK;
+    if (want > c->free_pages.size())
+        return fail(RL_ENOMEM_PAGES, "KV page pool exhausted: need %zu more pages, %zu free", want, c->free_pages.size());
+    std::vector<int> triples;
+    triples.reserve(want * 3);
+    for (int b = 0; b < (int)need.size(); ++b) {
+        size_t np = (size_t)(need[b] + PT - 1) / PT;
+        while (c->pages[b].size() < np) {
+            int p = c->free_pages.back();
+            c->free_pages.pop_back();
+            triples.push_back(b);
+            triples.push_back((int)c->pages[b].size());
+            triples.push_back(p);
+            c->pages[b].push_back(p);
+        }
+    }
+    k_set_pages(c->at<int>(c->L.block_table), c->L.mpps, triples.data(), (int)triples.size() / 3, s);
+    return RL_OK;
+}
+
+// ---------------------------------------------------------------- GEMM dispatch
+static void gemm(rl_ctx* c, int cls, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,
+                 float* outF, void* outT, int ldc, hipStream_t s) {
+    ProfScope ps(c, cls, s);
+    k_gemm_simple(c->cfg.dtype, epi, A, lda, W, W2, M, N, K, outF, outT, ldc, s);
+}
+
+// ---------------------------------------------------------------- decoder layers on n packed tokens
+// Inputs: x (fp32 residual stream) filled by the embedding, tok_pos / tok_slot descriptors.
+// paged = attention reads the paged cache (decode); else the chunk's own contiguous K/V.
+// write_pages = append K/V of these tokens to the paged cache.
+static void run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
+                       hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    const int dt = m.dtype;
+    const size_t e = esz_of(dt);
+    const int qd = m.n_q_heads * m.head_dim;
+    float* x = c->at<float>(L.x);
+    void* h = c->at<char>(L.h);
+    float* qkv = c->at<float>(L.qkv);
+    void* q = c->at<char>(L.q);
+    void* kb = c->at<char>(L.kbuf);
+    void* vb = c->at<char>(L.vbuf);
+    void* att = c->at<char>(L.attn);
+    void* ffn = c->at<char>(L.ffn);
+    const int* tpos = c->at<int>(L.tok_pos);
+    const int* tslot = c->at<int>(L.tok_slot);
+    const int* bt = c->at<int>(L.block_table);
+    const float2* rope = c->at<float2>(L.rope);
+    const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
+    const int acls = paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL;
+    for (int l = 0; l < m.n_layers; ++l) {
+        k_rmsnorm(dt, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s);
+        gemm(c, gcls, EPI_STORE_F32, h, m.d_model, W.wqkv[l], nullptr, n, L.nqkv, m.d_model, qkv, nullptr, L.nqkv, s);
+        k_rope_append(dt, qkv, n, tpos, tslot, rope, q, paged ? nullptr : kb, paged ? nullptr : vb,
+                      write_pages ? c->pool : nullptr, l, c->geo, bt, L.mpps, m.n_q_heads, s);
+        {
+            ProfScope ps(c, acls, s);
+            k_attn_simple(dt, q, paged ? nullptr : kb, paged ? nullptr : vb, paged ? c->pool : nullptr, l, c->geo, bt,
+                          L.mpps, tpos, tslot, att, n, m.n_q_heads, max_ctx, s);
+        }
+        gemm(c, gcls, EPI_RESID, att, qd, W.wo[l], nullptr, n, m.d_model, qd, x, nullptr, m.d_model, s);
+        k_rmsnorm(dt, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
+        const char* wg = (const char*)W.w_gate_up[l];
+        gemm(c, gcls, EPI_SWIGLU, h, m.d_model, wg, wg + (size_t)m.d_ffn * m.d_model * e, n, m.d_ffn, m.d_model,
+             nullptr, ffn, m.d_ffn, s);
+        gemm(c, gcls, EPI_RESID, ffn, m.d_ffn, W.w_down[l], nullptr, n, m.d_model, m.d_ffn, x, nullptr, m.d_model, s);
+    }
+}
+
+// Upload a chunk's row descriptors and build the packed token arrays on the device.
+static int pack_chunk(rl_ctx* c, const int* ids, int ld_ids, const std::vector<int>& rows_b,
+                      const std::vector<int>& starts, const std::vector<int>& lens, const std::vector<int>& full,
+                      bool targets, hipStream_t s) {
+    const Layout& L = c->L;
+    const size_t nb = rows_b.size() * sizeof(int);
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.seq_first), rows_b.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_start), starts.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_len), lens.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.full_len), full.data(), nb, hipMemcpyHostToDevice, s));
+    // the host vectors may be reused by the caller right after this returns
+    HIP_TRY(hipStreamSynchronize(s));
+    k_pack_tokens(ids, ld_ids, c->at<int>(L.seq_first), c->at<int>(L.row_start), c->at<int>(L.row_len),
+                  c->at<int>(L.full_len), c->at<int>(L.tok_ids), c->at<int>(L.tok_pos), c->at<int>(L.tok_slot),
+                  targets ? c->at<int>(L.tok_tgt) : nullptr, (int)rows_b.size(), s);
+    return RL_OK;
+}
+
+// ---------------------------------------------------------------- C ABI
+extern "C" {
+
+const char* rollout_last_error(void) { return g_err; }
+
+size_t rollout_workspace_bytes(const rl_model_cfg* cfg) {
+    if (validate_cfg(cfg) != RL_OK) return 0;
+    return make_layout(*cfg).total;
+}
+
+size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg) {
+    if (validate_cfg(cfg) != RL_OK) return 0;
+    return (size_t)cfg->n_layers * 2 * (size_t)cfg->n_pages * cfg->n_kv_heads * cfg->page_tokens * cfg->head_dim *
+           esz_of(cfg->dtype);
+}
+
+int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* workspace, size_t workspace_bytes,
+                 void* kv_pool, size_t kv_pool_bytes, rl_ctx** out) {
+    if (!out) return fail(RL_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = validate_cfg(cfg);
+    if (rc) return rc;
+    if (!workspace || !kv_pool) return fail(RL_EINVAL, "workspace / kv_pool is NULL");
+    if (((uintptr_t)workspace & 255) || ((uintptr_t)kv_pool & 255))
+        return fail(RL_EINVAL, "workspace / kv_pool must be 256-byte aligned");
+    Layout L = make_layout(*cfg);
+    if (workspace_bytes < L.total)
+        return fail(RL_ENOSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
+    if (kv_pool_bytes < rollout_kv_pool_bytes(cfg))
+        return fail(RL_ENOSPACE, "kv_pool too small: %zu < %zu bytes", kv_pool_bytes, rollout_kv_pool_bytes(cfg));
+    rl_ctx* c = new (std::nothrow) rl_ctx();
+    if (!c) return fail(RL_EINVAL, "out of host memory");
+    c->cfg = *cfg;
+    c->L = L;
+    c->ws = (char*)workspace;
+    c->pool = kv_pool;
+    rc = copy_weights(*cfg, policy, c->policy, "policy");
+    if (rc) { delete c; return rc; }
+    c->geo = KvGeom{cfg->n_kv_heads, cfg->head_dim, cfg->page_tokens, cfg->n_pages};
+    c->impl = cfg->dtype == RL_BF16 ? 1 : 0;
+    c->cached.assign(cfg->max_batch, 0);
+    c->pages.assign(cfg->max_batch, {});
+    release_all_pages(c);
+    hipStream_t s = nullptr;
+    k_rope_table(c->at<float2>(L.rope), cfg->max_seq, cfg->head_dim, cfg->rope_base, s);
+    k_fill_i32(c->at<int>(L.block_table), 0, (int64_t)cfg->max_batch * L.mpps, s);
+    k_fill_i32(c->at<int>(L.errflag), 0, 64, s);
+    k_fill_i32(c->at<int>(L.seq_len), 0, cfg->max_batch, s);
+    k_fill_i32(c->at<int>(L.last_tok), 0, cfg->max_batch, s);
+    k_fill_i32(c->at<int>(L.gen_count), 0, cfg->max_batch, s);
+    k_fill_i32(c->at<int>(L.finished), 0, cfg->max_batch, s);
+    hipError_t e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete c;
+        return fail(RL_EHIP, "rollout_init: %s", hipGetErrorString(e));
+    }
+    *out = c;
+    return RL_OK;
+}
+
+void rollout_destroy(rl_ctx* c) {
+    if (!c) return;
+    for (int k = 0; k < RL_K_COUNT; ++k)
+        for (auto& r : c->prof[k]) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    delete c;
+}
+
+int rollout_reset(rl_ctx* c) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    c->B = 0;
+    release_all_pages(c);
+    return RL_OK;
+}
+
+int rollout_set_impl(rl_ctx* c, int32_t impl) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    if (impl != 0 && impl != 1) return fail(RL_EINVAL, "impl must be 0 or 1");
+    if (impl == 1 && c->cfg.dtype != RL_BF16) return fail(RL_EINVAL, "impl 1 needs bf16");
+    c->impl = impl;
+    return RL_OK;
+}
+
+int rollout_check(rl_ctx* c, void* stream) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    hipStream_t s = (hipStream_t)stream;
+    int flag = 0;
+    HIP_TRY(hipMemcpyAsync(&flag, c->at<int>(c->L.errflag), sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    if (flag) {
+        k_fill_i32(c->at<int>(c->L.errflag), 0, 1, s);
+        return fail(RL_EINVAL, "token id outside [0, vocab) was seen (clamped)");
+    }
+    return RL_OK;
+}
+
+int rollout_prefill(rl_ctx* c, const int32_t* prompt_ids, const int32_t* prompt_len, int32_t B, int32_t Pmax,
+                    void* stream) {
+    if (!c || !prompt_ids || !prompt_len) return fail(RL_EINVAL, "NULL argument");
+    const rl_model_cfg& m = c->cfg;
+    if (B < 1 || B > m.max_batch) return fail(RL_EINVAL, "B=%d outside [1, max_batch=%d]", B, m.max_batch);
+    if (Pmax < 1) return fail(RL_EINVAL, "Pmax < 1");
+    for (int b = 0; b < B; ++b)
+        if (prompt_len[b] < 1 || prompt_len[b] > Pmax || prompt_len[b] > m.max_seq)
+            return fail(RL_EINVAL, "prompt_len[%d]=%d outside [1, min(Pmax, max_seq)]", b, prompt_len[b]);
+    hipStream_t s = (hipStream_t)stream;
+    const Layout& L = c->L;
+    c->B = 0;
+    release_all_pages(c);
+    std::vector<int> need(B);
+    for (int b = 0; b < B; ++b) need[b] = prompt_len[b] - 1;
+    int rc = ensure_pages(c, need, s);
+    if (rc) { release_all_pages(c); return rc; }
+    // chunks of whole sequences, at most max_chunk_tokens tokens each
+    int b0 = 0;
+    while (b0 < B) {
+        std::vector<int> rows, starts, lens, full;
+        int n = 0, max_ctx = 1;
+        int b1 = b0;
+        while (b1 < B && n + need[b1] <= m.max_chunk_tokens) {
+            rows.push_back(b1);
+            starts.push_back(n);
+            lens.push_back(need[b1]);
+            full.push_back(need[b1]);
+            n += need[b1];
+            max_ctx = std::max(max_ctx, need[b1]);
+            ++b1;
+        }
+        if (n > 0) {
+            rc = pack_chunk(c, prompt_ids, Pmax, rows, starts, lens, full, false, s);
+            if (rc) return rc;
+            k_embed(m.dtype, c->at<int>(L.tok_ids), n, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+                    c->at<int>(L.errflag), s);
+            run_layers(c, c->policy, n, false, true, max_ctx, s);
+        }
+        b0 = b1;
+    }
+    // prompt lengths to the device for the state kernel
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    k_prefill_state(prompt_ids, Pmax, c->at<int>(L.d_prompt_len), c->at<int>(L.last_tok), c->at<int>(L.seq_len),
+                    c->at<int>(L.gen_count), c->at<int>(L.finished), B, s);
+    for (int b = 0; b < B; ++b) c->cached[b] = need[b];
+    c->B = B;
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* tok_in, int32_t* tok_out,
+                            float* logp_out, int32_t* out_ids, float* out_logp, int out_stride, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    const int B = c->B;
+    std::vector<int> need(B);
+    int max_ctx = 1;
+    for (int b = 0; b < B; ++b) {
+        if (c->cached[b] + 1 > m.max_seq) return fail(RL_EINVAL, "sequence %d would exceed max_seq=%d", b, m.max_seq);
+        need[b] = c->cached[b] + 1;
+        max_ctx = std::max(max_ctx, need[b]);
+    }
+    int rc = ensure_pages(c, need, s);
+    if (rc) return rc;
+    k_step_begin(tok_in, c->at<int>(L.last_tok), c->at<int>(L.seq_len), c->at<int>(L.cur_tok), c->at<int>(L.tok_pos),
+                 c->at<int>(L.tok_slot), B, s);
+    k_embed(m.dtype, c->at<int>(L.cur_tok), B, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+            c->at<int>(L.errflag), s);
+    run_layers(c, c->policy, B, true, true, max_ctx, s);
+    k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
+    gemm(c, RL_K_GEMM_DECODE, EPI_STORE_F32, c->at<char>(L.h), m.d_model, c->policy.lm_head, nullptr, B, m.vocab,
+         m.d_model, c->at<float>(L.logits), nullptr, m.vocab, s);
+    SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
+    k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
+             c->at<int>(L.gen_count), c->at<int>(L.finished), tok_out, logp_out, out_ids, out_logp, out_stride, s);
+    for (int b = 0; b < B; ++b) c->cached[b] += 1;
+    return RL_OK;
+}
+
+static int check_sample(const rl_sample_cfg* sample) {
+    if (!sample) return fail(RL_EINVAL, "sample cfg is NULL");
+    if (!(sample->temperature >= 0.0f)) return fail(RL_EINVAL, "temperature must be >= 0");
+    return RL_OK;
+}
+
+int rollout_decode_step(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* tok_in, int32_t* tok_out,
+                        float* logp_out, void* stream) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    int rc = check_sample(sample);
+    if (rc) return rc;
+    if (c->B < 1) return fail(RL_ESTATE, "rollout_decode_step before rollout_prefill");
+    rc = decode_step_impl(c, sample, tok_in, tok_out, logp_out, nullptr, nullptr, 0, (hipStream_t)stream);
+    if (rc) return rc;
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+int rollout_generate(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prompt_ids, const int32_t* prompt_len,
+                     int32_t B, int32_t Pmax, int32_t G, int32_t* out_ids, int32_t* out_len, float* out_logp,
+                     void* stream) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    int rc = check_sample(sample);
+    if (rc) return rc;
+    if (!out_ids) return fail(RL_EINVAL, "out_ids is NULL");
+    if (G < 1) return fail(RL_EINVAL, "G < 1");
+    if (!prompt_len) return fail(RL_EINVAL, "NULL argument");
+    for (int b = 0; b < B && b < c->cfg.max_batch; ++b)
+        if (prompt_len[b] >= 1 && prompt_len[b] - 1 + G > c->cfg.max_seq)
+            return fail(RL_EINVAL, "prompt_len[%d] - 1 + G = %d exceeds max_seq=%d", b, prompt_len[b] - 1 + G,
+                        c->cfg.max_seq);
+    hipStream_t s = (hipStream_t)stream;
+    rc = rollout_prefill(c, prompt_ids, prompt_len, B, Pmax, stream);
+    if (rc) return rc;
+    // reserve every page the rollout will need up front: no allocation inside the loop
+    std::vector<int> need(B);
+    for (int b = 0; b < B; ++b) need[b] = prompt_len[b] - 1 + G;
+    rc = ensure_pages(c, need, s);
+    if (rc) return rc;
+    for (int n = 0; n < G; ++n) {
+        rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids + n, out_logp ? out_logp + n : nullptr, G, s);
+        if (rc) return rc;
+    }
+    if (out_len) k_out_len(c->at<int>(c->L.gen_count), out_len, B, s);
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+// One teacher-forced pass of one weight set over all sequences; writes logp_out [B, Lmax].
+static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const int32_t* seq_len, int B, int Lmax,
+                      float* logp_out, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    k_fill_f32(logp_out, 0.f, (int64_t)B * Lmax, s);
+    int b0 = 0;
+    while (b0 < B) {
+        std::vector<int> rows, starts, lens, full;
+        int n = 0, max_ctx = 1, b1 = b0;
+        while (b1 < B && n + seq_len[b1] <= m.max_chunk_tokens) {
+            rows.push_back(b1);
+            starts.push_back(n);
+            lens.push_back(seq_len[b1]);
+            full.push_back(seq_len[b1]);
+            n += seq_len[b1];
+            max_ctx = std::max(max_ctx, seq_len[b1]);
+            ++b1;
+        }
+        int rc = pack_chunk(c, ids, Lmax, rows, starts, lens, full, true, s);
+        if (rc) return rc;
+        k_embed(m.dtype, c->at<int>(L.tok_ids), n, W.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+                c->at<int>(L.errflag), s);
+        run_layers(c, W, n, false, false, max_ctx, s);
+        k_rmsnorm(m.dtype, c->at<float>(L.x), W.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
+        const size_t e = esz_of(m.dtype);
+        for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
+            int nr = std::min(L.logit_rows, n - r0);
+            ProfScope ps(c, RL_K_LMHEAD_SCORE, s);
+            k_gemm_simple(m.dtype, EPI_STORE_F32, c->at<char>(L.h) + (size_t)r0 * m.d_model * e, m.d_model, W.lm_head,
+                          nullptr, nr, m.vocab, m.d_model, c->at<float>(L.logits), nullptr, m.vocab, s);
+            k_lse_gather(c->at<float>(L.logits), m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0,
+                         c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, logp_out, Lmax, s);
+        }
+        b0 = b1;
+    }
+    return RL_OK;
+}
+
+int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* reference, const int32_t* ids,
+                      const int32_t* seq_len, const int32_t* prompt_len, int32_t B, int32_t Lmax, float kl_coef,
+                      float* logp_policy, float* logp_ref, float* kl, float* kl_penalty, void* stream) {
+    if (!c || !ids || !seq_len || !prompt_len) return fail(RL_EINVAL, "NULL argument");
+    const rl_model_cfg& m = c->cfg;
+    if (B < 1 || B > m.max_batch) return fail(RL_EINVAL, "B=%d outside [1, max_batch=%d]", B, m.max_batch);
+    if (Lmax < 1) return fail(RL_EINVAL, "Lmax < 1");
+    for (int b = 0; b < B; ++b) {
+        if (seq_len[b] < 1 || seq_len[b] > Lmax || seq_len[b] > m.max_seq)
+            return fail(RL_EINVAL, "seq_len[%d]=%d outside [1, min(Lmax, max_seq)]", b, seq_len[b]);
+        if (prompt_len[b] < 0 || prompt_len[b] > seq_len[b])
+            return fail(RL_EINVAL, "prompt_len[%d]=%d outside [0, seq_len]", b, prompt_len[b]);
+    }
+    if (!reference && (logp_ref || kl || kl_penalty))
+        return fail(RL_EINVAL, "reference is NULL but a reference-dependent output was requested");
+    if ((kl || kl_penalty) && (!logp_policy || !logp_ref))
+        return fail(RL_EINVAL, "kl outputs need logp_policy and logp_ref buffers");
+    hipStream_t s = (hipStream_t)stream;
+    WeightsHost wp, wr;
+    int rc = copy_weights(m, policy, wp, "policy");
+    if (rc) return rc;
+    if (reference) {
+        rc = copy_weights(m, reference, wr, "reference");
+        if (rc) return rc;
+    }
+    if (logp_policy) {
+        rc = score_pass(c, wp, ids, seq_len, B, Lmax, logp_policy, s);
+        if (rc) return rc;
+    }
+    if (reference && logp_ref) {
+        rc = score_pass(c, wr, ids, seq_len, B, Lmax, logp_ref, s);
+        if (rc) return rc;
+    }
+    if (kl || kl_penalty) {
+        const Layout& L = c->L;
+        HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_seq_len), seq_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+        HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        k_kl(logp_policy, logp_ref, c->at<int>(L.d_seq_len), c->at<int>(L.d_prompt_len), B, Lmax, kl_coef, kl,
+             kl_penalty, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+int rollout_profile_enable(rl_ctx* c, int32_t k, int32_t on) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    if (k < 0 || k >= RL_K_COUNT) return fail(RL_EINVAL, "kernel_class out of range");
+    c->prof_on[k] = on != 0;
+    return RL_OK;
+}
+
+int rollout_profile_read(rl_ctx* c, int32_t k, double* total_ms, int64_t* launches) {
+    if (!c || !total_ms || !launches) return fail(RL_EINVAL, "NULL argument");
+    if (k < 0 || k >= RL_K_COUNT) return fail(RL_EINVAL, "kernel_class out of range");
+    double tot = 0.0;
+    for (size_t i = 0; i < c->prof_used[k]; ++i) {
+        HIP_TRY(hipEventSynchronize(c->prof[k][i].b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->prof[k][i].a, c->prof[k][i].b));
+        tot += ms;
+    }
+    *total_ms = tot;
+    *launches = (int64_t)c->prof_used[k];
+    c->prof_used[k] = 0;
+    return RL_OK;
+}
+
+}  // extern "C"
