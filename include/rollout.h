@@ -175,8 +175,9 @@ enum {
     RL_K_LMHEAD_SCORE = 4,  /* fused LM head + log-sum-exp + gather */
     RL_K_COUNT = 5
 };
-/* When on, every launch of that class is bracketed by HIP events on the launch
- * stream (up to an internal cap; later launches go untimed). */
+/* on = 0: off.  on = n >= 1: every n-th launch of that class is bracketed by HIP
+ * events on the launch stream (up to an internal cap of 8192 timed launches
+ * between reads; later launches go untimed). */
 int rollout_profile_enable(rl_ctx* ctx, int32_t kernel_class, int32_t on);
 /* Waits for the recorded events; returns summed milliseconds and launch count,
  * then clears the records.  total_ms / launches: host. */

@@ -232,13 +232,26 @@ void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, co
 // ---------------------------------------------------------------- RoPE + split + KV append
 // qkv fp32 [n, (Hq+2Hkv) hd] -> rotated q (T) [n, Hq hd]; rotated k and plain v to the
 // contiguous buffers (optional) and to the page slot of (slot, pos) (optional).
+// With nsplit > 1 the row is the sum, in split order, of nsplit partial rows split_stride apart.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float* qkv, const int* tok_pos, const int* tok_slot,
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* qkv, int nsplit, int64_t split_stride,
+                                                          const int* tok_pos, const int* tok_slot,
                                                           const float2* rope, T* q_out, T* k_out, T* v_out, T* pool,
                                                           int layer, KvGeom geo, const int* bt, int mpps, int Hq) {
+    extern __shared__ float rowbuf[];
     const int n = blockIdx.x, hd = geo.hd, half = hd / 2, Hkv = geo.Hkv;
     const int pos = tok_pos[n];
-    const float* row = qkv + (int64_t)n * (Hq + 2 * Hkv) * hd;
+    const int width = (Hq + 2 * Hkv) * hd;
+    const float* row = qkv + (int64_t)n * width;
+    if (nsplit > 1) {
+        for (int i = threadIdx.x; i < width; i += 256) {
+            float v = row[i];
+            for (int sp = 1; sp < nsplit; ++sp) v += row[sp * split_stride + i];
+            rowbuf[i] = v;
+        }
+        __syncthreads();
+        row = rowbuf;
+    }
     const float2* rt = rope + (int64_t)pos * half;
     int64_t page = 0;
     int slot_tok = 0;
@@ -280,16 +293,52 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* qkv, cons
         if (pool) pool[geo.v_off(layer, page, g, slot_tok, dd)] = v;
     }
 }
-void k_rope_append(int dtype, const float* qkv, int n, const int* tok_pos, const int* tok_slot, const float2* rope,
-                   void* q_out, void* k_out, void* v_out, void* pool, int layer, KvGeom geo, const int* block_table,
-                   int mpps, int Hq, hipStream_t s) {
+void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride, int n, const int* tok_pos,
+                   const int* tok_slot, const float2* rope, void* q_out, void* k_out, void* v_out, void* pool,
+                   int layer, KvGeom geo, const int* block_table, int mpps, int Hq, hipStream_t s) {
     if (n <= 0) return;
+    size_t lds = nsplit > 1 ? (size_t)(Hq + 2 * geo.Hkv) * geo.hd * sizeof(float) : 0;
     if (dtype == 0)
-        rope_append_kernel<float><<<n, 256, 0, s>>>(qkv, tok_pos, tok_slot, rope, (float*)q_out, (float*)k_out,
-                                                    (float*)v_out, (float*)pool, layer, geo, block_table, mpps, Hq);
+        rope_append_kernel<float><<<n, 256, lds, s>>>(qkv, nsplit, split_stride, tok_pos, tok_slot, rope,
+                                                      (float*)q_out, (float*)k_out, (float*)v_out, (float*)pool,
+                                                      layer, geo, block_table, mpps, Hq);
     else
-        rope_append_kernel<f16_t><<<n, 256, 0, s>>>(qkv, tok_pos, tok_slot, rope, (f16_t*)q_out, (f16_t*)k_out,
-                                                    (f16_t*)v_out, (f16_t*)pool, layer, geo, block_table, mpps, Hq);
+        rope_append_kernel<f16_t><<<n, 256, lds, s>>>(qkv, nsplit, split_stride, tok_pos, tok_slot, rope,
+                                                      (f16_t*)q_out, (f16_t*)k_out, (f16_t*)v_out, (f16_t*)pool,
+                                                      layer, geo, block_table, mpps, Hq);
+}
+
+// ---------------------------------------------------------------- split-K reduce + residual add + RMSNorm
+// x[n,:] += sum_s part[s][n,:] (split order);  out[n,:] = RMSNorm(x[n,:]; g).  One block per row.
+template <typename T, typename TW>
+__global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* part, int nsplit, int64_t split_stride,
+                                                         const TW* g, T* out, int d, float eps) {
+    __shared__ float red[16];
+    extern __shared__ float xrow[];
+    const int n = blockIdx.x;
+    float* xr = x + (int64_t)n * d;
+    const float* pr = part + (int64_t)n * d;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        float v = xr[j];
+        for (int sp = 0; sp < nsplit; ++sp) v += pr[sp * split_stride + j];
+        xr[j] = v;
+        xrow[j] = v;
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    float rs = 1.0f / sqrtf(ss / (float)d + eps);
+    T* o = out + (int64_t)n * d;
+    for (int j = threadIdx.x; j < d; j += 256) o[j] = from_f<T>(xrow[j] * rs * to_f(g[j]));
+}
+void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
+                  int n, int d, float eps, hipStream_t s) {
+    if (n <= 0) return;
+    size_t lds = (size_t)d * sizeof(float);
+    if (dtype == 0)
+        resid_norm_kernel<float, float><<<n, 256, lds, s>>>(x, part, nsplit, split_stride, (const float*)g, (float*)out, d, eps);
+    else
+        resid_norm_kernel<f16_t, bf16_t><<<n, 256, lds, s>>>(x, part, nsplit, split_stride, (const bf16_t*)g, (f16_t*)out, d, eps);
 }
 
 // ---------------------------------------------------------------- plain attention

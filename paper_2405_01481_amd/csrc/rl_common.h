@@ -98,9 +98,11 @@ void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, floa
 void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s);
 void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,
                    float* outF, void* outT, int ldc, hipStream_t s);
-void k_rope_append(int dtype, const float* qkv, int n, const int* tok_pos, const int* tok_slot, const float2* rope,
-                   void* q_out, void* k_out, void* v_out, void* pool, int layer, KvGeom geo, const int* block_table,
-                   int mpps, int Hq, hipStream_t s);
+void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride, int n, const int* tok_pos,
+                   const int* tok_slot, const float2* rope, void* q_out, void* k_out, void* v_out, void* pool,
+                   int layer, KvGeom geo, const int* block_table, int mpps, int Hq, hipStream_t s);
+void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
+                  int n, int d, float eps, hipStream_t s);
 void k_attn_simple(int dtype, const void* q, const void* kc, const void* vc, const void* pool, int layer, KvGeom geo,
                    const int* block_table, int mpps, const int* tok_pos, const int* tok_slot, void* out, int n,
                    int Hq, int max_ctx, hipStream_t s);

@@ -1,0 +1,35 @@
+// Interface of the MFMA GEMM launcher (rl_gemm.hip).
+#pragma once
+#include "rl_common.h"
+
+enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4 };
+
+struct GemmArgs {
+    const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
+    int lda = 0;
+    const bf16_t* W = nullptr;  // [Wrows, K] row-major
+    int M = 0, N = 0, K = 0;    // N = output columns (MG_SWIGLU: d_ffn)
+    int Wrows = 0;              // filled by the launcher
+    int k_per_split = 0;        // filled by the launcher
+    int up_offset = 0;          // MG_SWIGLU: row of W where the up projection starts
+    float* outF = nullptr;      // MG_STORE_F32 (+ split * split_stride) / MG_RESID
+    f16_t* outH = nullptr;      // MG_STORE_F16 / MG_SWIGLU
+    int ldc = 0;
+    int64_t split_stride = 0;
+    // MG_QKV
+    const int* tok_pos = nullptr;
+    const int* tok_slot = nullptr;
+    const float2* rope = nullptr;
+    f16_t* q_out = nullptr;
+    f16_t* k_out = nullptr;
+    f16_t* v_out = nullptr;
+    f16_t* pool = nullptr;
+    const int* block_table = nullptr;
+    int mpps = 0, layer = 0, Hq = 0, Hkv = 0, hd = 0;
+    KvGeom geo{};
+};
+
+bool k_gemm_mfma_supported(int epi, int N, int K, int hd);
+// splits > 1 only with MG_STORE_F32: partial sums of split s go to outF + s * split_stride.
+void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
+int k_gemm_mfma_splits_used(int K, int splits);

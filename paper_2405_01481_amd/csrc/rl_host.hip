@@ -1,6 +1,7 @@
 // Host side of librollout: context, workspace layout, page allocator, the
 // generation / scoring step sequences, and the C ABI declared in include/rollout.h.
 #include "rl_common.h"
+#include "rl_gemm.h"
 #include "../../include/rollout.h"
 
 #include <algorithm>
@@ -156,7 +157,8 @@ struct rl_ctx {
     std::vector<std::vector<int>> pages;
     std::vector<int> free_pages;
     // profiling
-    bool prof_on[RL_K_COUNT] = {};
+    int prof_on[RL_K_COUNT] = {};       // 0 off, n >= 1: time every n-th launch
+    uint64_t prof_seen[RL_K_COUNT] = {};
     std::vector<ProfRec> prof[RL_K_COUNT];
     size_t prof_used[RL_K_COUNT] = {};
 
@@ -166,7 +168,8 @@ struct rl_ctx {
 struct ProfScope {
     rl_ctx* c; int k; hipStream_t s; ProfRec* r = nullptr;
     ProfScope(rl_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
-        if (!c->prof_on[k] || c->prof_used[k] >= kProfCap) return;
+        if (!c->prof_on[k]) return;
+        if ((c->prof_seen[k]++ % (uint64_t)c->prof_on[k]) != 0 || c->prof_used[k] >= kProfCap) return;
         if (c->prof_used[k] >= c->prof[k].size()) {
             ProfRec nr;
             if (hipEventCreate(&nr.a) != hipSuccess) return;
@@ -226,8 +229,18 @@ static void gemm(rl_ctx* c, int cls, int epi, const void* A, int lda, const void
 // Inputs: x (fp32 residual stream) filled by the embedding, tok_pos / tok_slot descriptors.
 // paged = attention reads the paged cache (decode); else the chunk's own contiguous K/V.
 // write_pages = append K/V of these tokens to the paged cache.
-static void run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                       hipStream_t s) {
+// Returns true when h already holds RMSNorm(x; final_norm) (the tuned decode path fuses it).
+static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    ProfScope ps(c, paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL, s);
+    k_attn_simple(m.dtype, c->at<char>(L.q), paged ? nullptr : c->at<char>(L.kbuf), paged ? nullptr : c->at<char>(L.vbuf),
+                  paged ? c->pool : nullptr, l, c->geo, c->at<int>(L.block_table), L.mpps, c->at<int>(L.tok_pos),
+                  c->at<int>(L.tok_slot), c->at<char>(L.attn), n, m.n_q_heads, max_ctx, s);
+}
+
+static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
+                             hipStream_t s) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int dt = m.dtype;
@@ -246,17 +259,12 @@ static void run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool 
     const int* bt = c->at<int>(L.block_table);
     const float2* rope = c->at<float2>(L.rope);
     const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
-    const int acls = paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL;
     for (int l = 0; l < m.n_layers; ++l) {
         k_rmsnorm(dt, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s);
         gemm(c, gcls, EPI_STORE_F32, h, m.d_model, W.wqkv[l], nullptr, n, L.nqkv, m.d_model, qkv, nullptr, L.nqkv, s);
-        k_rope_append(dt, qkv, n, tpos, tslot, rope, q, paged ? nullptr : kb, paged ? nullptr : vb,
+        k_rope_append(dt, qkv, 1, 0, n, tpos, tslot, rope, q, paged ? nullptr : kb, paged ? nullptr : vb,
                       write_pages ? c->pool : nullptr, l, c->geo, bt, L.mpps, m.n_q_heads, s);
-        {
-            ProfScope ps(c, acls, s);
-            k_attn_simple(dt, q, paged ? nullptr : kb, paged ? nullptr : vb, paged ? c->pool : nullptr, l, c->geo, bt,
-                          L.mpps, tpos, tslot, att, n, m.n_q_heads, max_ctx, s);
-        }
+        attention(c, l, n, paged, max_ctx, s);
         gemm(c, gcls, EPI_RESID, att, qd, W.wo[l], nullptr, n, m.d_model, qd, x, nullptr, m.d_model, s);
         k_rmsnorm(dt, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
         const char* wg = (const char*)W.w_gate_up[l];
@@ -264,6 +272,127 @@ static void run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool 
              nullptr, ffn, m.d_ffn, s);
         gemm(c, gcls, EPI_RESID, ffn, m.d_ffn, W.w_down[l], nullptr, n, m.d_model, m.d_ffn, x, nullptr, m.d_model, s);
     }
+    return false;
+}
+
+static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a, int splits, hipStream_t s) {
+    ProfScope ps(c, cls, s);
+    k_gemm_mfma(epi, a, splits, s);
+}
+
+// Split count for a weight-streaming GEMM with n_tiles column tiles and K/64 k-tiles:
+// enough workgroups to cover the 256 CUs about twice, at least 4 k-tiles each.
+static int decode_splits(int n_tiles, int K) {
+    int want = (512 + n_tiles - 1) / n_tiles;
+    int kt = K / 64;
+    want = std::min(want, std::max(1, kt / 4));
+    want = std::min(want, kMaxSplitK);
+    return k_gemm_mfma_splits_used(K, std::max(1, want));
+}
+
+// bf16 weights / fp16 activations on the MFMA kernels.
+static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
+                            hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    const int qd = m.n_q_heads * m.head_dim;
+    float* x = c->at<float>(L.x);
+    f16_t* h = c->at<f16_t>(L.h);
+    f16_t* q = c->at<f16_t>(L.q);
+    f16_t* kb = c->at<f16_t>(L.kbuf);
+    f16_t* vb = c->at<f16_t>(L.vbuf);
+    f16_t* att = c->at<f16_t>(L.attn);
+    f16_t* ffn = c->at<f16_t>(L.ffn);
+    float* part = c->at<float>(L.splitk);
+    const int* tpos = c->at<int>(L.tok_pos);
+    const int* tslot = c->at<int>(L.tok_slot);
+    const int* bt = c->at<int>(L.block_table);
+    const float2* rope = c->at<float2>(L.rope);
+    const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
+    if (paged) k_rmsnorm(1, x, W.attn_norm[0], h, n, m.d_model, m.rms_eps, s);
+    for (int l = 0; l < m.n_layers; ++l) {
+        GemmArgs g;
+        g.M = n;
+        if (paged) {
+            // weight-streaming GEMMs, split over K; consumers reduce the partial sums
+            g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
+            g.outF = part; g.ldc = L.nqkv; g.split_stride = (int64_t)n * L.nqkv;
+            int sp = decode_splits(L.nqkv / 128, m.d_model);
+            mfma(c, gcls, MG_STORE_F32, g, sp, s);
+            k_rope_append(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, nullptr, nullptr,
+                          write_pages ? c->pool : nullptr, l, c->geo, bt, L.mpps, m.n_q_heads, s);
+            attention(c, l, n, true, max_ctx, s);
+            g = GemmArgs();
+            g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
+            g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
+            sp = decode_splits(m.d_model / 128, qd);
+            mfma(c, gcls, MG_STORE_F32, g, sp, s);
+            k_resid_norm(1, x, part, sp, g.split_stride, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
+            g = GemmArgs();
+            g.M = n; g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn; g.K = m.d_model;
+            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = m.d_ffn;
+            mfma(c, gcls, MG_SWIGLU, g, 1, s);
+            g = GemmArgs();
+            g.M = n; g.A = ffn; g.lda = m.d_ffn; g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model; g.K = m.d_ffn;
+            g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
+            sp = decode_splits(m.d_model / 128, m.d_ffn);
+            mfma(c, gcls, MG_STORE_F32, g, sp, s);
+            const void* next = (l + 1 < m.n_layers) ? W.attn_norm[l + 1] : W.final_norm;
+            k_resid_norm(1, x, part, sp, g.split_stride, next, h, n, m.d_model, m.rms_eps, s);
+        } else {
+            k_rmsnorm(1, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s);
+            g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
+            g.tok_pos = tpos; g.tok_slot = tslot; g.rope = rope; g.q_out = q; g.k_out = kb; g.v_out = vb;
+            g.pool = write_pages ? (f16_t*)c->pool : nullptr; g.block_table = bt; g.mpps = L.mpps; g.layer = l;
+            g.Hq = m.n_q_heads; g.Hkv = m.n_kv_heads; g.hd = m.head_dim; g.geo = c->geo;
+            mfma(c, gcls, MG_QKV, g, 1, s);
+            attention(c, l, n, false, max_ctx, s);
+            g = GemmArgs();
+            g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
+            g.outF = x; g.ldc = m.d_model;
+            mfma(c, gcls, MG_RESID, g, 1, s);
+            k_rmsnorm(1, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
+            g = GemmArgs();
+            g.M = n; g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn; g.K = m.d_model;
+            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = m.d_ffn;
+            mfma(c, gcls, MG_SWIGLU, g, 1, s);
+            g = GemmArgs();
+            g.M = n; g.A = ffn; g.lda = m.d_ffn; g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model; g.K = m.d_ffn;
+            g.outF = x; g.ldc = m.d_model;
+            mfma(c, gcls, MG_RESID, g, 1, s);
+        }
+    }
+    return paged;
+}
+
+static bool run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
+                       hipStream_t s) {
+    if (c->impl == 1) return run_layers_fast(c, W, n, paged, write_pages, max_ctx, s);
+    return run_layers_plain(c, W, n, paged, write_pages, max_ctx, s);
+}
+
+// LM head on rows [0, nr) of h: logits fp32 [nr, V]
+static void lm_head_logits(rl_ctx* c, int cls, const WeightsHost& W, const void* hrows, int nr, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    if (c->impl == 1) {
+        GemmArgs g;
+        g.M = nr; g.A = (const f16_t*)hrows; g.lda = m.d_model; g.W = (const bf16_t*)W.lm_head; g.N = m.vocab;
+        g.K = m.d_model; g.outF = c->at<float>(c->L.logits); g.ldc = m.vocab;
+        mfma(c, cls, MG_STORE_F32, g, 1, s);
+    } else {
+        gemm(c, cls, EPI_STORE_F32, hrows, m.d_model, W.lm_head, nullptr, nr, m.vocab, m.d_model,
+             c->at<float>(c->L.logits), nullptr, m.vocab, s);
+    }
+}
+
+static bool fast_path_supported(const rl_model_cfg& m) {
+    if (m.dtype != RL_BF16) return false;
+    const int nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, qd = m.n_q_heads * m.head_dim;
+    return k_gemm_mfma_supported(MG_QKV, nqkv, m.d_model, m.head_dim) &&
+           k_gemm_mfma_supported(MG_STORE_F32, m.d_model, qd, m.head_dim) &&
+           k_gemm_mfma_supported(MG_SWIGLU, m.d_ffn, m.d_model, m.head_dim) &&
+           k_gemm_mfma_supported(MG_STORE_F32, m.d_model, m.d_ffn, m.head_dim) &&
+           k_gemm_mfma_supported(MG_STORE_F32, m.vocab, m.d_model, m.head_dim);
 }
 
 // Upload a chunk's row descriptors and build the packed token arrays on the device.
@@ -323,7 +452,7 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
     rc = copy_weights(*cfg, policy, c->policy, "policy");
     if (rc) { delete c; return rc; }
     c->geo = KvGeom{cfg->n_kv_heads, cfg->head_dim, cfg->page_tokens, cfg->n_pages};
-    c->impl = cfg->dtype == RL_BF16 ? 1 : 0;
+    c->impl = fast_path_supported(*cfg) ? 1 : 0;
     c->cached.assign(cfg->max_batch, 0);
     c->pages.assign(cfg->max_batch, {});
     release_all_pages(c);
@@ -362,7 +491,8 @@ int rollout_reset(rl_ctx* c) {
 int rollout_set_impl(rl_ctx* c, int32_t impl) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     if (impl != 0 && impl != 1) return fail(RL_EINVAL, "impl must be 0 or 1");
-    if (impl == 1 && c->cfg.dtype != RL_BF16) return fail(RL_EINVAL, "impl 1 needs bf16");
+    if (impl == 1 && !fast_path_supported(c->cfg))
+        return fail(RL_EINVAL, "impl 1 needs bf16 weights and GEMM widths that are multiples of 128 (K of 64)");
     c->impl = impl;
     return RL_OK;
 }
@@ -451,10 +581,9 @@ static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_
                  c->at<int>(L.tok_slot), B, s);
     k_embed(m.dtype, c->at<int>(L.cur_tok), B, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
             c->at<int>(L.errflag), s);
-    run_layers(c, c->policy, B, true, true, max_ctx, s);
-    k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
-    gemm(c, RL_K_GEMM_DECODE, EPI_STORE_F32, c->at<char>(L.h), m.d_model, c->policy.lm_head, nullptr, B, m.vocab,
-         m.d_model, c->at<float>(L.logits), nullptr, m.vocab, s);
+    if (!run_layers(c, c->policy, B, true, true, max_ctx, s))
+        k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
+    lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
     SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
     k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
              c->at<int>(L.gen_count), c->at<int>(L.finished), tok_out, logp_out, out_ids, out_logp, out_stride, s);
@@ -538,9 +667,7 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
         const size_t e = esz_of(m.dtype);
         for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
             int nr = std::min(L.logit_rows, n - r0);
-            ProfScope ps(c, RL_K_LMHEAD_SCORE, s);
-            k_gemm_simple(m.dtype, EPI_STORE_F32, c->at<char>(L.h) + (size_t)r0 * m.d_model * e, m.d_model, W.lm_head,
-                          nullptr, nr, m.vocab, m.d_model, c->at<float>(L.logits), nullptr, m.vocab, s);
+            lm_head_logits(c, RL_K_LMHEAD_SCORE, W, c->at<char>(L.h) + (size_t)r0 * m.d_model * e, nr, s);
             k_lse_gather(c->at<float>(L.logits), m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0,
                          c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, logp_out, Lmax, s);
         }
@@ -597,7 +724,8 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
 int rollout_profile_enable(rl_ctx* c, int32_t k, int32_t on) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     if (k < 0 || k >= RL_K_COUNT) return fail(RL_EINVAL, "kernel_class out of range");
-    c->prof_on[k] = on != 0;
+    c->prof_on[k] = on < 0 ? 0 : on;
+    c->prof_seen[k] = 0;
     return RL_OK;
 }
 

@@ -207,8 +207,8 @@ class Rollout:
     def rollout_set_impl(self, impl: int):
         _chk(lib().rollout_set_impl(self.h, impl))
 
-    def rollout_profile_enable(self, kernel_class: int, on: bool):
-        _chk(lib().rollout_profile_enable(self.h, kernel_class, 1 if on else 0))
+    def rollout_profile_enable(self, kernel_class: int, every: int):
+        _chk(lib().rollout_profile_enable(self.h, kernel_class, int(every)))
 
     def rollout_profile_read(self, kernel_class: int):
         ms, n = C.c_double(), C.c_int64()
