@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: rollout_generate
+(prompt prefill + G decode steps over the paged KV cache) followed by
+score_logprobs_kl (teacher-forced log-probs under policy and reference + KL).
+Prints ONE JSON line.  `value` = generated tokens per second over the whole step,
+inputs resident in HBM.  Extra keys give the decode-only and scoring-only rates,
+the roofline of the dominant kernel class (HIP events on the launch stream, live in
+the timed region) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2405_01481_amd import rollout as R   # noqa: E402
+from paper_2405_01481_amd import synth          # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0     # dense bf16 / fp16 MFMA
+
+
+def decode_bytes(shape, plens, G):
+    """Algorithmic HBM bytes of the G decode steps: weights once per step, plus per sequence the
+    KV of every attended key read and the new token's KV written."""
+    w = 2 * (shape.body_params() + shape.head_params())
+    kvt = shape.kv_bytes_per_token()
+    total = G * w
+    for p in plens:
+        for n in range(G):
+            ctx = int(p) + n                       # keys attended at step n (prompt + n generated so far)
+            total += (ctx + 1) * kvt               # read ctx keys/values, write one
+    return total
+
+
+def gemm_decode_bytes_per_step(shape, B):
+    """Algorithmic bytes of the weight-streaming GEMMs of one decode step (weights + fp16 A rows in,
+    fp16 / fp32 results out at their final width; split-K partials are overhead, not counted)."""
+    d, F, V = shape.d_model, shape.d_ffn, shape.vocab
+    qd = shape.n_q_heads * shape.head_dim
+    per_layer_w = 2 * (shape.qkv_rows * d + d * qd + 2 * F * d + d * F)
+    per_layer_act = 2 * B * (d + qd + d + F) + 2 * B * (shape.qkv_rows + F) + 4 * B * 2 * d
+    return shape.n_layers * (per_layer_w + per_layer_act) + 2 * V * d + 2 * B * d + 4 * B * V
+
+
+def attn_decode_bytes(shape, plens, G):
+    kvt = shape.kv_bytes_per_token()
+    return sum((int(p) + n) * kvt for p in plens for n in range(G))
+
+
+def score_flops(shape, lens):
+    """Algorithmic FLOP of one teacher-forced pass: 2*params per token (LM head only on scored
+    positions) + causal attention (lower triangle only)."""
+    f = 0.0
+    for L in lens:
+        L = int(L)
+        f += 2.0 * shape.body_params() * L + 2.0 * shape.head_params() * max(L - 1, 0)
+        f += shape.n_layers * 4.0 * shape.n_q_heads * shape.head_dim * (L * (L + 1) / 2.0)
+    return f
+
+
+def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperature):
+    """The CPU oracle, as it stands, on a bounded sample: row 0, its first sample_P prompt
+    tokens, sample_G generated tokens (with KV cache).  Weights are handed over as float64
+    arrays (same values) so the timed region holds the oracle's arithmetic only."""
+    from oracle import rollout_oracle as O
+    try:
+        import threadpoolctl
+        threads = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) or 1
+    except Exception:
+        threads = os.cpu_count() or 1
+    w = {k: synth.to_numpy_f32(v).astype(np.float64) for k, v in wp.items() if k != "layers"}
+    w["layers"] = [{k: synth.to_numpy_f32(v).astype(np.float64) for k, v in lw.items()} for lw in wp["layers"]]
+    m = O.Model(shape, w)
+    prompt = ids[0, :min(sample_P, int(prompt_len[0]))]
+    t0 = time.perf_counter()
+    O.generate(m, [prompt], sample_G, temperature, seed=seed)
+    dt = time.perf_counter() - t0
+    return {"value": sample_G / dt, "unit": "generated tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"row 0, first {len(prompt)} prompt tokens, {sample_G} generated tokens, "
+                      f"float64 numpy oracle with KV cache, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="8b", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (marks the line reduced)")
+    ap.add_argument("--batch", type=int, default=0, help="debug override")
+    ap.add_argument("--prompt", type=int, default=0, help="debug override")
+    ap.add_argument("--gen", type=int, default=0, help="debug override")
+    ap.add_argument("--no-score", action="store_true", help="debug: skip scoring (marks the line reduced)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--impl", type=int, default=-1)
+    ap.add_argument("--chunk", type=int, default=16384)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+
+    wl = synth.WORKLOADS[args.workload]
+    shape = wl.shape
+    reduced = False
+    if args.layers:
+        shape = synth.scaled_shape(shape, shape.name, n_layers=args.layers)
+        reduced = True
+    B = args.batch or wl.batch
+    Pmax = args.prompt or wl.prompt_max
+    Pmin = min(wl.prompt_min, Pmax) if not args.prompt else Pmax
+    G = args.gen or wl.gen
+    reduced = reduced or (B, Pmax, G) != (wl.batch, wl.prompt_max, wl.gen) or args.no_score
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wp = synth.make_weights(shape, wl.policy_seed, dev)
+    wr = synth.make_weights(shape, wl.ref_seed, dev)
+    Wp, Wr = R.Weights(wp), R.Weights(wr)
+    Lmax = Pmax + G
+    cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=max(Lmax, args.chunk))
+    ro = R.Rollout(cfg, Wp, dev)
+    if args.impl >= 0:
+        ro.rollout_set_impl(args.impl)
+    ids_np, plen = synth.make_prompts(shape.vocab, B, Pmax, Pmin, wl.prompt_seed)
+    ids = torch.tensor(ids_np, device=dev)
+    out_ids = torch.zeros(B, G, dtype=torch.int32, device=dev)
+    out_lp = torch.zeros(B, G, dtype=torch.float32, device=dev)
+    full = torch.zeros(B, Lmax, dtype=torch.int32, device=dev)
+    seq_len = (plen + G).astype(np.int32)
+    outs = [torch.zeros(B, Lmax, dtype=torch.float32, device=dev) for _ in range(4)]
+    sc = R.sample_cfg(wl.sample_seed, wl.temperature)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def assemble():
+        # [prompt | generated] rows, ragged prompts packed to the left (device-side copies only)
+        if Pmin == Pmax:
+            full[:, :Pmax] = ids
+            full[:, Pmax:] = out_ids
+        else:
+            for b in range(B):
+                p = int(plen[b])
+                full[b, :p] = ids[b, :p]
+                full[b, p:p + G] = out_ids[b]
+
+    def one_step(timed):
+        ev[0].record()
+        ro.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)
+        ev[1].record()
+        if not args.no_score:
+            assemble()
+            ro.score_logprobs_kl(Wp, Wr, full, seq_len, plen, 0.003, *outs)
+        ev[2].record()
+
+    # a non-default stream: rollout_generate then replays its decode step as a captured HIP graph
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(stream)
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    ro.rollout_check()
+
+    gen_ms, score_ms = [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+        ev[2].synchronize()
+        gen_ms.append(ev[0].elapsed_time(ev[1]))
+        score_ms.append(ev[1].elapsed_time(ev[2]))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ro.rollout_check()
+
+    # One more step of the same work with HIP events bracketing sampled kernel launches on the
+    # launch stream (per-class average launch durations for the roofline).  With events on, the
+    # decode step is launched kernel by kernel instead of as a captured graph, so this step is
+    # kept out of `value`.
+    prof_classes = {"gemm_decode": R.RL_K_GEMM_DECODE, "attn_decode": R.RL_K_ATTN_DECODE,
+                    "gemm_prefill": R.RL_K_GEMM_PREFILL, "attn_prefill": R.RL_K_ATTN_PREFILL,
+                    "lmhead_score": R.RL_K_LMHEAD_SCORE}
+    launches_per_step = {"gemm_decode": G * (4 * shape.n_layers + 1), "attn_decode": G * shape.n_layers}
+    for name, k in prof_classes.items():
+        n = launches_per_step.get(name, 0)
+        ro.rollout_profile_enable(k, max(1, -(-n // 6000)))      # sample evenly, stay under the event cap
+    one_step(False)
+    torch.cuda.synchronize()
+    prof = {}
+    for name, k in prof_classes.items():
+        ms, n = ro.rollout_profile_read(k)
+        prof[name] = {"ms_timed": ms, "launches_timed": n}
+        ro.rollout_profile_enable(k, 0)
+
+    # prompt prefill alone, to split generation time into prefill + decode loop
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ro.rollout_prefill(ids, plen)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t1
+
+    ms_per_step = dt * 1e3 / args.steps
+    gen_s = float(np.mean(gen_ms)) / 1e3
+    score_s = float(np.mean(score_ms)) / 1e3
+    decode_s = max(gen_s - prefill_s, 1e-9)
+    dbytes = decode_bytes(shape, plen, G)
+    decode_gbps = dbytes / decode_s / 1e9
+    sflops = 2 * score_flops(shape, seq_len)
+    score_tflops = sflops / score_s / 1e12 if not args.no_score else None
+
+    # roofline of the dominant decode kernel class
+    def avg_ms(name):
+        p = prof[name]
+        return p["ms_timed"] / p["launches_timed"] if p["launches_timed"] else None
+    g_avg, a_avg = avg_ms("gemm_decode"), avg_ms("attn_decode")
+    g_tot = (g_avg or 0) * launches_per_step["gemm_decode"]
+    a_tot = (a_avg or 0) * launches_per_step["attn_decode"]
+    if g_tot >= a_tot:
+        name = "gemm_decode (weight-streaming MFMA GEMM)"
+        per_launch = gemm_decode_bytes_per_step(shape, B) / (4 * shape.n_layers + 1)
+        achieved = per_launch / (g_avg * 1e-3) / 1e9 if g_avg else None
+    else:
+        name = "attn_decode (paged GQA decode attention)"
+        per_launch = attn_decode_bytes(shape, plen, G) / launches_per_step["attn_decode"]
+        achieved = per_launch / (a_avg * 1e-3) / 1e9 if a_avg else None
+    roofline = {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": (achieved / HBM_PEAK_GBPS) if achieved else None, "traffic": None,
+                "avg_launch_ms": g_avg if g_tot >= a_tot else a_avg, "bytes_per_launch": per_launch}
+
+    line = {
+        "metric": "rollout gen tokens/s + decode HBM GB/s % peak, 8B shape batch 128 (1 GPU)",
+        "value": B * G / (ms_per_step / 1e3),
+        "unit": "generated tokens/s (whole step: generate + policy/reference scoring + KL)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, fp16 activations/KV, fp32 accumulate" if shape.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "shape": shape.name, "layers": shape.n_layers, "batch": B,
+                   "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
+                   "temperature": wl.temperature, "reduced": reduced, "impl": args.impl},
+        "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
+        "decode_tok_s": B * G / decode_s, "generate_tok_s": B * G / gen_s,
+        "decode_hbm_gbps": decode_gbps, "decode_hbm_frac": decode_gbps / HBM_PEAK_GBPS,
+        "scored_tok_s": (2 * float(seq_len.sum()) / score_s) if not args.no_score else None,
+        "score_tflops": score_tflops,
+        "score_mfma_frac": (score_tflops / MFMA_PEAK_TFLOPS) if score_tflops else None,
+        "kernel_classes": prof,
+        "roofline": roofline,
+        "host_cores": os.cpu_count(),
+    }
+    if not args.no_cpu:
+        small = shape.body_params() < 5e9
+        line["cpu_baseline"] = cpu_baseline(shape, wp, ids_np, plen, wl.sample_seed,
+                                            32 if not small else 64, 4 if not small else 16, wl.temperature)
+    else:
+        line["cpu_baseline"] = None
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

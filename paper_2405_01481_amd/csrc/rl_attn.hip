@@ -1,0 +1,182 @@
+// MFMA attention kernels for gfx950 (fp16 K/V, fp32 softmax and accumulation).
+//
+// Both kernels compute the transposed problem so that nothing has to be shuffled
+// between the two contractions:
+//     S^T = K * Q^T        (rows = keys,  cols = queries / query heads)
+//     O^T = V^T * P^T      (rows = dims,  cols = queries / query heads)
+// In the MFMA C layout a lane owns one column, i.e. one query (head): its softmax
+// statistics are lane-local, and the four S^T values a lane holds per 16-key block
+// are exactly the four k-values the B operand of the 16x16x16 MFMA wants from that
+// lane for P^T.  K is read token-major, V dim-major (the paged pool stores V pages
+// as [kv head][dim][token] for this reason), both straight from global memory in
+// operand layout -- a (page, kv head) tile is one contiguous 4 KB block.
+#include "rl_common.h"
+#include "rl_attn.h"
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+#define LOG2E 1.4426950408889634f
+
+// ------------------------------------------------------------------ decode: one new query per sequence
+// Workgroup = (sequence b, kv head g, split).  Its 4 waves take page pairs round-robin
+// from the split's page range; query heads g*G .. g*G+G-1 are the MFMA columns 0..G-1
+// (columns >= G are zero padding).  Per-wave results are merged through LDS; with more
+// than one split the workgroup writes an unnormalised partial (o, m, l) per head.
+template <int HD, int PT>
+__global__ __launch_bounds__(256) void attn_decode_kernel(DecodeAttnArgs a) {
+    static_assert(PT == 16, "page tile is one 16-row MFMA block");
+    constexpr int KS = HD / 32;    // k-steps of the 16x16x32 S^T MFMAs
+    constexpr int DB = HD / 16;    // 16-dim blocks of O^T
+    __shared__ float sm_m[4][16], sm_l[4][16];
+    __shared__ float sm_o[4][16][HD + 4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, g4 = lane >> 4;
+    const int b = blockIdx.x, g = blockIdx.y, split = blockIdx.z;
+    const int G = a.Hq / a.Hkv;
+    const int ctx = a.tok_pos[b] + 1;
+    const int npages = (ctx + PT - 1) / PT;
+    const int chunk = (npages + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int pbeg = split * chunk, pend = min(npages, pbeg + chunk);
+    const int* bt = a.block_table + (int64_t)b * a.mpps;
+    const f16_t* kbase = a.pool + a.geo.k_off(a.layer, 0, g, 0, 0);
+    const f16_t* vbase = a.pool + a.geo.v_off(a.layer, 0, g, 0, 0);
+    const int64_t page_stride = a.geo.page_elems();
+
+    // Q^T operand: lane (head col, k-group g4) holds q[head][s*32 + g4*8 .. +8)
+    half8 qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        if (col < G) qf[s] = *reinterpret_cast<const half8*>(a.q + ((int64_t)b * a.Hq + g * G + col) * HD + s * 32 + g4 * 8);
+        else qf[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    const float scale = a.scale * LOG2E;       // softmax in base 2
+    float m_run = -INFINITY, l_run = 0.f;
+    floatx4 acc[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) acc[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    for (int p0 = pbeg + wave * 2; p0 < pend; p0 += 8) {
+        const bool two = p0 + 1 < pend;
+        const int64_t pg0 = bt[p0];
+        const int64_t pg1 = two ? bt[p0 + 1] : pg0;
+        const f16_t* k0 = kbase + pg0 * page_stride + col * HD + g4 * 8;
+        const f16_t* k1 = kbase + pg1 * page_stride + col * HD + g4 * 8;
+        const f16_t* v0 = vbase + pg0 * page_stride + col * PT + g4 * 4;
+        const f16_t* v1 = vbase + pg1 * page_stride + col * PT + g4 * 4;
+        half8 kf0[KS], kf1[KS];
+        half4 vf0[DB], vf1[DB];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            kf0[s] = *reinterpret_cast<const half8*>(k0 + s * 32);
+            kf1[s] = *reinterpret_cast<const half8*>(k1 + s * 32);
+        }
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+            vf0[d] = *reinterpret_cast<const half4*>(v0 + d * 16 * PT);
+            vf1[d] = *reinterpret_cast<const half4*>(v1 + d * 16 * PT);
+        }
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf0[s], qf[s], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf1[s], qf[s], s1, 0, 0, 0);
+        }
+        // lane holds keys p*16 + g4*4 + i of head `col`
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int t0 = p0 * PT + g4 * 4 + i;
+            s0[i] = (t0 < ctx) ? s0[i] * scale : -INFINITY;
+            s1[i] = (two && t0 + PT < ctx) ? s1[i] * scale : -INFINITY;
+            mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, RL_WAVE));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
+        const float m_new = fmaxf(m_run, mx);       // finite: the first key of page p0 is always valid
+        const float alpha = exp2f(m_run - m_new);
+        half4 pf0, pf1;
+        float ps = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float e0 = exp2f(s0[i] - m_new), e1 = exp2f(s1[i] - m_new);
+            ps += e0 + e1;
+            pf0[i] = (f16_t)e0;
+            pf1[i] = (f16_t)e1;
+        }
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+            acc[d] *= alpha;
+            acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf0[d], pf0, acc[d], 0, 0, 0);
+            acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf1[d], pf1, acc[d], 0, 0, 0);
+        }
+    }
+    // wave totals: l over the four key groups
+    l_run += __shfl_xor(l_run, 16, RL_WAVE);
+    l_run += __shfl_xor(l_run, 32, RL_WAVE);
+    if (col < G) {
+        if (g4 == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sm_o[wave][col][d * 16 + g4 * 4 + i] = acc[d][i];
+    }
+    __syncthreads();
+    const int nsplit = gridDim.z;
+    for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
+        const int hh = idx / HD, d = idx % HD;
+        float mt = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
+        float o = 0.f, l = 0.f;
+        if (mt > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float wt = exp2f(sm_m[w][hh] - mt);
+                o += wt * sm_o[w][hh][d];
+                l += wt * sm_l[w][hh];
+            }
+        }
+        const int64_t head = (int64_t)b * a.Hq + g * G + hh;
+        if (nsplit == 1) {
+            a.out[head * HD + d] = (f16_t)(o / l);
+        } else {
+            a.part_o[(head * nsplit + split) * HD + d] = o;
+            if (d == 0) {
+                a.part_ml[(head * nsplit + split) * 2 + 0] = mt;
+                a.part_ml[(head * nsplit + split) * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// Merge of split partials: out = sum_s w_s o_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, const float* part_ml, f16_t* out,
+                                                        int nsplit) {
+    const int64_t head = blockIdx.x;
+    const int d = threadIdx.x;
+    float mt = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mt = fmaxf(mt, part_ml[(head * nsplit + s) * 2]);
+    float o = 0.f, l = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        float m = part_ml[(head * nsplit + s) * 2];
+        if (m == -INFINITY) continue;
+        float wt = exp2f(m - mt);
+        o += wt * part_o[(head * nsplit + s) * HD + d];
+        l += wt * part_ml[(head * nsplit + s) * 2 + 1];
+    }
+    out[head * HD + d] = (f16_t)(o / l);
+}
+
+void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
+    if (B <= 0) return;
+    dim3 grid(B, a.Hkv, nsplit);
+    if (a.geo.hd == 128) attn_decode_kernel<128, 16><<<grid, 256, 0, s>>>(a);
+    else attn_decode_kernel<64, 16><<<grid, 256, 0, s>>>(a);
+    if (nsplit > 1) {
+        if (a.geo.hd == 128) attn_merge_kernel<128><<<B * a.Hq, 128, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit);
+        else attn_merge_kernel<64><<<B * a.Hq, 64, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit);
+    }
+}

@@ -92,7 +92,7 @@ void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* 
 
 // After prefill of the first P-1 prompt tokens: remember the last prompt token, lengths, counters.
 __global__ void prefill_state_kernel(const int* ids, int ld_ids, const int* prompt_len, int* last_tok, int* seq_len,
-                                     int* gen_count, int* finished, int B) {
+                                     int* gen_count, int* finished, int* step_count, int B) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int P = prompt_len[b];
@@ -100,11 +100,12 @@ __global__ void prefill_state_kernel(const int* ids, int ld_ids, const int* prom
     seq_len[b] = P - 1;
     gen_count[b] = 0;
     finished[b] = 0;
+    step_count[b] = 0;
 }
 void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_tok, int* seq_len, int* gen_count,
-                     int* finished, int B, hipStream_t s) {
+                     int* finished, int* step_count, int B, hipStream_t s) {
     prefill_state_kernel<<<(B + 255) / 256, 256, 0, s>>>(ids, ld_ids, row_len, last_tok, seq_len, gen_count,
-                                                         finished, B);
+                                                         finished, step_count, B);
 }
 
 __global__ void out_len_kernel(const int* gen_count, int* out_len, int B) {
@@ -308,37 +309,117 @@ void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride
                                                       layer, geo, block_table, mpps, Hq);
 }
 
+#define RL_MAX_SPLITS 16
+// Decode variant: the qkv row arrives as nsplit split-K partial rows.  One block of 1024 threads
+// per token; a thread owns (column j, column j + hd/2) pairs and requests every partial of a pair
+// before summing them in split order.  Writes rotated q, and k / v into the page slot.
+template <typename T>
+__global__ __launch_bounds__(1024) void rope_append_split_kernel(const float* part, int nsplit, int64_t split_stride,
+                                                                 const int* tok_pos, const int* tok_slot,
+                                                                 const float2* rope, T* q_out, T* pool, int layer,
+                                                                 KvGeom geo, const int* bt, int mpps, int Hq) {
+    const int n = blockIdx.x, hd = geo.hd, half = hd / 2, Hkv = geo.Hkv;
+    const int pos = tok_pos[n];
+    const int width = (Hq + 2 * Hkv) * hd;
+    const float* row = part + (int64_t)n * width;
+    const float2* rt = rope + (int64_t)pos * half;
+    const int64_t page = bt[(int64_t)tok_slot[n] * mpps + pos / geo.PT];
+    const int st = pos % geo.PT;
+    const int npairs = (Hq + 2 * Hkv) * half;
+    for (int i = threadIdx.x; i < npairs; i += 1024) {
+        const int head = i / half, j = i % half;
+        const int c0 = head * hd + j;
+        float p0[RL_MAX_SPLITS], p1[RL_MAX_SPLITS];
+#pragma unroll
+        for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
+            if (sp < nsplit) { p0[sp] = row[sp * split_stride + c0]; p1[sp] = row[sp * split_stride + c0 + half]; }
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
+            if (sp < nsplit) { a += p0[sp]; b += p1[sp]; }
+        if (head < Hq + Hkv) {
+            float2 cs = rt[j];
+            float r0 = a * cs.x - b * cs.y, r1 = b * cs.x + a * cs.y;
+            a = r0; b = r1;
+        }
+        if (head < Hq) {
+            T* o = q_out + (int64_t)n * Hq * hd + head * hd + j;
+            o[0] = from_f<T>(a); o[half] = from_f<T>(b);
+        } else if (head < Hq + Hkv) {
+            const int g = head - Hq;
+            pool[geo.k_off(layer, page, g, st, j)] = from_f<T>(a);
+            pool[geo.k_off(layer, page, g, st, j + half)] = from_f<T>(b);
+        } else {
+            const int g = head - Hq - Hkv;
+            pool[geo.v_off(layer, page, g, st, j)] = from_f<T>(a);
+            pool[geo.v_off(layer, page, g, st, j + half)] = from_f<T>(b);
+        }
+    }
+}
+void k_rope_append_split(int dtype, const float* part, int nsplit, int64_t split_stride, int n, const int* tok_pos,
+                         const int* tok_slot, const float2* rope, void* q_out, void* pool, int layer, KvGeom geo,
+                         const int* block_table, int mpps, int Hq, hipStream_t s) {
+    if (n <= 0) return;
+    if (dtype == 0)
+        rope_append_split_kernel<float><<<n, 1024, 0, s>>>(part, nsplit, split_stride, tok_pos, tok_slot, rope,
+                                                           (float*)q_out, (float*)pool, layer, geo, block_table, mpps, Hq);
+    else
+        rope_append_split_kernel<f16_t><<<n, 1024, 0, s>>>(part, nsplit, split_stride, tok_pos, tok_slot, rope,
+                                                           (f16_t*)q_out, (f16_t*)pool, layer, geo, block_table, mpps, Hq);
+}
+
 // ---------------------------------------------------------------- split-K reduce + residual add + RMSNorm
-// x[n,:] += sum_s part[s][n,:] (split order);  out[n,:] = RMSNorm(x[n,:]; g).  One block per row.
+// x[n,:] += sum_s part[s][n,:] (split order);  out[n,:] = RMSNorm(x[n,:]; g).  One block of 1024
+// threads per row; every thread owns float4 columns and requests all split partials of a column
+// before adding them (in split order), so the row costs about one memory round trip.
 template <typename T, typename TW>
-__global__ __launch_bounds__(256) void resid_norm_kernel(float* x, const float* part, int nsplit, int64_t split_stride,
-                                                         const TW* g, T* out, int d, float eps) {
+__global__ __launch_bounds__(1024) void resid_norm_kernel(float* x, const float* part, int nsplit, int64_t split_stride,
+                                                          const TW* g, T* out, int d, float eps) {
     __shared__ float red[16];
-    extern __shared__ float xrow[];
     const int n = blockIdx.x;
     float* xr = x + (int64_t)n * d;
     const float* pr = part + (int64_t)n * d;
+    float4 keep[2];
     float ss = 0.f;
-    for (int j = threadIdx.x; j < d; j += 256) {
-        float v = xr[j];
-        for (int sp = 0; sp < nsplit; ++sp) v += pr[sp * split_stride + j];
-        xr[j] = v;
-        xrow[j] = v;
-        ss += v * v;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int j = (it * 1024 + threadIdx.x) * 4;
+        if (j < d) {
+            float4 v = *reinterpret_cast<const float4*>(xr + j);
+            float4 p[RL_MAX_SPLITS];
+#pragma unroll
+            for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
+                if (sp < nsplit) p[sp] = *reinterpret_cast<const float4*>(pr + sp * split_stride + j);
+#pragma unroll
+            for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
+                if (sp < nsplit) { v.x += p[sp].x; v.y += p[sp].y; v.z += p[sp].z; v.w += p[sp].w; }
+            *reinterpret_cast<float4*>(xr + j) = v;
+            keep[it] = v;
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
     }
     ss = block_sum(ss, red);
-    float rs = 1.0f / sqrtf(ss / (float)d + eps);
+    const float rs = 1.0f / sqrtf(ss / (float)d + eps);
     T* o = out + (int64_t)n * d;
-    for (int j = threadIdx.x; j < d; j += 256) o[j] = from_f<T>(xrow[j] * rs * to_f(g[j]));
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int j = (it * 1024 + threadIdx.x) * 4;
+        if (j < d) {
+            o[j + 0] = from_f<T>(keep[it].x * rs * to_f(g[j + 0]));
+            o[j + 1] = from_f<T>(keep[it].y * rs * to_f(g[j + 1]));
+            o[j + 2] = from_f<T>(keep[it].z * rs * to_f(g[j + 2]));
+            o[j + 3] = from_f<T>(keep[it].w * rs * to_f(g[j + 3]));
+        }
+    }
 }
+// d must be a multiple of 4 and at most 8192; nsplit at most RL_MAX_SPLITS.
 void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
                   int n, int d, float eps, hipStream_t s) {
     if (n <= 0) return;
-    size_t lds = (size_t)d * sizeof(float);
     if (dtype == 0)
-        resid_norm_kernel<float, float><<<n, 256, lds, s>>>(x, part, nsplit, split_stride, (const float*)g, (float*)out, d, eps);
+        resid_norm_kernel<float, float><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const float*)g, (float*)out, d, eps);
     else
-        resid_norm_kernel<f16_t, bf16_t><<<n, 256, lds, s>>>(x, part, nsplit, split_stride, (const bf16_t*)g, (f16_t*)out, d, eps);
+        resid_norm_kernel<f16_t, bf16_t><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const bf16_t*)g, (f16_t*)out, d, eps);
 }
 
 // ---------------------------------------------------------------- plain attention
@@ -456,9 +537,11 @@ __device__ ArgMax block_argmax(const float* z, int V, ArgMax* red) {
 // One block of 1024 threads per sequence.  Wave w owns the contiguous vocabulary
 // segment [w*seg, (w+1)*seg); sums are formed lane-column-wise then reduced, in a
 // fixed order, so results are reproducible run to run.
+// out_ids / out_logp (optional) are [B, out_stride]; the column is the sequence's decode-step
+// counter, kept on the device so that a captured step can be replayed unchanged.
 __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int ldz, int V, SampleArgs a, int* last_tok,
-                                                      int* seq_len, int* gen_count, int* finished, int* tok_out,
-                                                      float* logp_out, int* out_ids, float* out_logp,
+                                                      int* seq_len, int* gen_count, int* finished, int* step_count,
+                                                      int* tok_out, float* logp_out, int* out_ids, float* out_logp,
                                                       int out_stride) {
     __shared__ ArgMax ared[16];
     __shared__ float ws1[16], wsT[16];
@@ -537,16 +620,20 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
         seq_len[b] = seq_len[b] + 1;
         if (tok_out) tok_out[b] = tok;
         if (logp_out) logp_out[b] = lp;
-        if (out_ids) out_ids[(int64_t)b * out_stride] = tok;
-        if (out_logp) out_logp[(int64_t)b * out_stride] = lp;
+        const int st = step_count[b];
+        step_count[b] = st + 1;
+        if (st < out_stride) {
+            if (out_ids) out_ids[(int64_t)b * out_stride + st] = tok;
+            if (out_logp) out_logp[(int64_t)b * out_stride + st] = lp;
+        }
     }
 }
 void k_sample(const float* logits, int ldz, int V, int B, SampleArgs a, int* last_tok, int* seq_len, int* gen_count,
-              int* finished, int* tok_out, float* logp_out, int* out_ids, float* out_logp, int out_stride,
-              hipStream_t s) {
+              int* finished, int* step_count, int* tok_out, float* logp_out, int* out_ids, float* out_logp,
+              int out_stride, hipStream_t s) {
     if (B <= 0) return;
-    sample_kernel<<<B, 1024, 0, s>>>(logits, ldz, V, a, last_tok, seq_len, gen_count, finished, tok_out, logp_out,
-                                     out_ids, out_logp, out_stride);
+    sample_kernel<<<B, 1024, 0, s>>>(logits, ldz, V, a, last_tok, seq_len, gen_count, finished, step_count, tok_out,
+                                     logp_out, out_ids, out_logp, out_stride);
 }
 
 // ---------------------------------------------------------------- log-sum-exp + gather over materialised logits

@@ -93,7 +93,7 @@ void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* 
                    const int* full_len, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
                    hipStream_t s);
 void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_tok, int* seq_len, int* gen_count,
-                     int* finished, int B, hipStream_t s);
+                     int* finished, int* step_count, int B, hipStream_t s);
 void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, float* x, int* errflag, hipStream_t s);
 void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s);
 void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,
@@ -101,14 +101,17 @@ void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, co
 void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride, int n, const int* tok_pos,
                    const int* tok_slot, const float2* rope, void* q_out, void* k_out, void* v_out, void* pool,
                    int layer, KvGeom geo, const int* block_table, int mpps, int Hq, hipStream_t s);
+void k_rope_append_split(int dtype, const float* part, int nsplit, int64_t split_stride, int n, const int* tok_pos,
+                         const int* tok_slot, const float2* rope, void* q_out, void* pool, int layer, KvGeom geo,
+                         const int* block_table, int mpps, int Hq, hipStream_t s);
 void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
                   int n, int d, float eps, hipStream_t s);
 void k_attn_simple(int dtype, const void* q, const void* kc, const void* vc, const void* pool, int layer, KvGeom geo,
                    const int* block_table, int mpps, const int* tok_pos, const int* tok_slot, void* out, int n,
                    int Hq, int max_ctx, hipStream_t s);
 void k_sample(const float* logits, int ldz, int V, int B, SampleArgs a, int* last_tok, int* seq_len, int* gen_count,
-              int* finished, int* tok_out, float* logp_out, int* out_ids, float* out_logp, int out_stride,
-              hipStream_t s);
+              int* finished, int* step_count, int* tok_out, float* logp_out, int* out_ids, float* out_logp,
+              int out_stride, hipStream_t s);
 void k_lse_gather(const float* logits, int ldz, int V, int nrows, const int* tok_tgt, const int* tok_slot,
                   const int* tok_pos, float* logp_out, int ld_out, hipStream_t s);
 void k_kl(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int B, int Lmax, float coef,

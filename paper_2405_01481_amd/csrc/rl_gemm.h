@@ -33,3 +33,6 @@ bool k_gemm_mfma_supported(int epi, int N, int K, int hd);
 // splits > 1 only with MG_STORE_F32: partial sums of split s go to outF + s * split_stride.
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
 int k_gemm_mfma_splits_used(int K, int splits);
+// Weight-streaming variant for M <= 128 (decode): epi MG_STORE_F32 (split-K partials / plain
+// fp32 store when splits == 1) or MG_SWIGLU.  Same shape requirements as k_gemm_mfma.
+void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s);

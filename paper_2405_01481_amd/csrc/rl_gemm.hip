@@ -30,6 +30,15 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w) {
     return o.u;
 }
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ half8 bf16x8_to_half8(u32x4_t w) {
+    fp16x2 p0 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u));
+    fp16x2 p1 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[1] << 16), __uint_as_float(w[1] & 0xffff0000u));
+    fp16x2 p2 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[2] << 16), __uint_as_float(w[2] & 0xffff0000u));
+    fp16x2 p3 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[3] << 16), __uint_as_float(w[3] & 0xffff0000u));
+    return half8{(f16_t)p0[0], (f16_t)p0[1], (f16_t)p1[0], (f16_t)p1[1], (f16_t)p2[0], (f16_t)p2[1], (f16_t)p3[0], (f16_t)p3[1]};
+}
+
 // Which row of W feeds LDS row r of the B tile of column-block nb.
 //  EPI_SWIGLU: the tile holds BN/2 gate rows and the matching BN/2 up rows, interleaved in
 //              blocks of 32 so that a wave's adjacent 32-column MFMA tiles are (gate, up).
@@ -229,6 +238,160 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
                 }
             }
         }
+    }
+}
+
+// ------------------------------------------------------------------ weight-streaming GEMM (decode, M <= 128)
+// One workgroup = 128 rows x 128 columns of C over one K slice.  The four waves split the
+// columns (32 each, two 16-wide MFMA tiles) and each wave reads ITS OWN rows of W straight
+// from global memory in B-operand layout (every row contributes 64 contiguous bytes per
+// load instruction), several k-tiles ahead, so that enough bytes are in flight per CU to
+// cover HBM latency; W never touches LDS.  The activations (shared by all four waves, and
+// L2-resident) are staged through LDS.  v_mfma_f32_16x16x32_f16, fp32 accumulation.
+//   SG_PARTIAL: outF[ks][m][n] = partial sum of K slice ks
+//   SG_SWIGLU : a wave's two column tiles are (gate, up) rows of W for the same 16 outputs;
+//               the workgroup covers 64 outputs; outH[m][n] = silu(gate) * up
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+enum { SG_PARTIAL = 0, SG_SWIGLU = 1 };
+
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
+    __shared__ __attribute__((aligned(16))) f16_t As[2][128 * LDS_STRIDE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int nb = blockIdx.x, ks = blockIdx.y;
+    const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
+    const int nk = (kend - kbeg) / BK;
+
+    // this lane's two W rows
+    const bf16_t* wp[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        int row;
+        if (EPI == SG_SWIGLU) row = (j ? a.up_offset : 0) + nb * 64 + wave * 16 + c16;
+        else row = nb * 128 + wave * 32 + j * 16 + c16;
+        wp[j] = a.W + (int64_t)row * a.K + kbeg + g4 * 8;
+    }
+    // A staging: 4 chunks of 16 B per thread per k-tile.  Rows >= M are read from row M-1: a row
+    // of C depends on the same row of A only, and rows >= M are never stored.
+    const f16_t* a_src[4];
+    int a_dst[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int c = tid + i * 256, r = c >> 3, kc = c & 7;
+        a_src[i] = a.A + (int64_t)min(r, a.M - 1) * a.lda + kbeg + kc * 8;
+        a_dst[i] = r * LDS_STRIDE + kc * 8;
+    }
+    u32x4 ra[4];            // the A tile in flight (requested after the previous one was parked in LDS)
+    u32x4 wq0[4], wq1[4];   // W tiles in flight, index = k32 step * 2 + column tile
+    floatx4 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+#define SG_LOAD(sl, kt)                                                                          \
+    {                                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                         \
+            ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * BK);                     \
+        _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
+            wq##sl[s_ * 2 + j_] = *reinterpret_cast<const u32x4*>(wp[j_] + (kt) * BK + s_ * 32); \
+    }
+#define SG_STORE_A(sl)                                                                           \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) *reinterpret_cast<u32x4*>(&As[sl][a_dst[i_]]) = ra[i_];
+    // Step kt: consume A tile kt (LDS buffer kt&1) and W tile kt (register slot kt&1) while tile
+    // kt+1 is in flight; then park A tile kt+1 in the other LDS buffer and request tile kt+2 into
+    // the slot just freed.  Vector loads return in order and A is requested before W, so no wait
+    // ever covers a request younger than one step.
+#define SG_COMPUTE(sl)                                                                           \
+    _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) {                                           \
+        half8 bf_[2];                                                                            \
+        _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) bf_[j_] = bf16x8_to_half8(wq##sl[s_ * 2 + j_]); \
+        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                       \
+            half8 af_ = *reinterpret_cast<const half8*>(                                         \
+                &As[sl][(i_ * 16 + c16) * LDS_STRIDE + s_ * 32 + g4 * 8]);                       \
+            acc[i_][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[0], acc[i_][0], 0, 0, 0); \
+            acc[i_][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[1], acc[i_][1], 0, 0, 0); \
+        }                                                                                        \
+    }
+    // full step: compute tile kt, park A tile kt+1, request tile kt+2 into the freed slot
+#define SG_STEP_FULL(sl, other, kt)  { SG_COMPUTE(sl) SG_STORE_A(other) SG_LOAD(sl, (kt) + 2) __syncthreads(); }
+#define SG_STEP_NOLOAD(sl, other)    { SG_COMPUTE(sl) SG_STORE_A(other) __syncthreads(); }
+#define SG_STEP_LAST(sl)             { SG_COMPUTE(sl) }
+
+    // The steady-state path has no conditional loads anywhere between its first request and its
+    // last wait: with vector loads returning in order, a wait count is exact only when every path
+    // to it has issued the same requests.  Short K slices take a separate, simpler path.
+    if (nk >= 4) {
+        SG_LOAD(0, 0)
+        SG_STORE_A(0)
+        SG_LOAD(1, 1)
+        __syncthreads();
+        int kt = 0;
+        for (; kt + 3 < nk; kt += 2) {
+            SG_STEP_FULL(0, 1, kt)
+            SG_STEP_FULL(1, 0, kt + 1)
+        }
+        if (nk - kt == 3) {
+            SG_STEP_FULL(0, 1, kt)
+            SG_STEP_NOLOAD(1, 0)
+            SG_STEP_LAST(0)
+        } else {
+            SG_STEP_NOLOAD(0, 1)
+            SG_STEP_LAST(1)
+        }
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+            SG_LOAD(0, kt)
+            SG_STORE_A(0)
+            __syncthreads();
+            SG_COMPUTE(0)
+            __syncthreads();
+        }
+    }
+#undef SG_COMPUTE
+#undef SG_STEP_FULL
+#undef SG_STEP_NOLOAD
+#undef SG_STEP_LAST
+#undef SG_LOAD
+#undef SG_STORE_A
+
+    // epilogue: acc[i][j][r] = C(row i*16 + g4*4 + r, column tile j, col c16)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int m = i * 16 + g4 * 4 + r;
+            if (m >= a.M) continue;
+            if (EPI == SG_PARTIAL) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    int n = nb * 128 + wave * 32 + j * 16 + c16;
+                    a.outF[(int64_t)ks * a.split_stride + (int64_t)m * a.ldc + n] = acc[i][j][r];
+                }
+            } else {
+                int n = nb * 64 + wave * 16 + c16;
+                float g = acc[i][0][r], u = acc[i][1][r];
+                a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
+            }
+        }
+    }
+}
+
+void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return;
+    if (splits < 1) splits = 1;
+    int kt = a.K / BK;
+    int per = (kt + splits - 1) / splits;
+    a.k_per_split = per * BK;
+    splits = (kt + per - 1) / per;
+    if (epi == MG_SWIGLU) {
+        dim3 grid(a.N / 64, 1);
+        gemm_stream_kernel<SG_SWIGLU><<<grid, 256, 0, s>>>(a);
+    } else {
+        dim3 grid(a.N / 128, splits);
+        gemm_stream_kernel<SG_PARTIAL><<<grid, 256, 0, s>>>(a);
     }
 }
 

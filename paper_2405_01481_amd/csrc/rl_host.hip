@@ -2,6 +2,7 @@
 // generation / scoring step sequences, and the C ABI declared in include/rollout.h.
 #include "rl_common.h"
 #include "rl_gemm.h"
+#include "rl_attn.h"
 #include "../../include/rollout.h"
 
 #include <algorithm>
@@ -29,7 +30,7 @@ static int fail(int code, const char* fmt, ...) {
 // ---------------------------------------------------------------- workspace layout
 struct Layout {
     size_t x, h, qkv, q, kbuf, vbuf, attn, ffn, logits, rope, block_table;
-    size_t last_tok, seq_len, gen_count, finished, cur_tok;
+    size_t last_tok, seq_len, gen_count, finished, cur_tok, step_count;
     size_t tok_ids, tok_pos, tok_slot, tok_tgt;
     size_t seq_first, row_start, row_len, full_len, d_seq_len, d_prompt_len, errflag;
     size_t splitk, attn_part, attn_ml, lse_part;
@@ -75,6 +76,7 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.gen_count = take((size_t)c.max_batch * 4);
     L.finished = take((size_t)c.max_batch * 4);
     L.cur_tok = take((size_t)c.max_batch * 4);
+    L.step_count = take((size_t)c.max_batch * 4);
     L.tok_ids = take((size_t)rows * 4);
     L.tok_pos = take((size_t)rows * 4);
     L.tok_slot = take((size_t)rows * 4);
@@ -156,6 +158,21 @@ struct rl_ctx {
     std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len)
     std::vector<std::vector<int>> pages;
     std::vector<int> free_pages;
+    // captured decode step (rollout_generate on a non-default stream, tuned kernels)
+    struct GraphKey {
+        int B, G, impl, eos;
+        const void *out_ids, *out_logp;
+        uint64_t seed;
+        int64_t base;
+        float temp;
+        hipStream_t s;
+        bool operator==(const GraphKey& o) const {
+            return B == o.B && G == o.G && impl == o.impl && eos == o.eos && out_ids == o.out_ids &&
+                   out_logp == o.out_logp && seed == o.seed && base == o.base && temp == o.temp && s == o.s;
+        }
+    } gkey{};
+    hipGraphExec_t gexec = nullptr;
+    bool use_graph = true;
     // profiling
     int prof_on[RL_K_COUNT] = {};       // 0 off, n >= 1: time every n-th launch
     uint64_t prof_seen[RL_K_COUNT] = {};
@@ -234,6 +251,17 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, hipStrea
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     ProfScope ps(c, paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL, s);
+    if (paged && c->impl == 1) {
+        DecodeAttnArgs a;
+        a.q = c->at<f16_t>(L.q); a.pool = (const f16_t*)c->pool; a.block_table = c->at<int>(L.block_table);
+        a.tok_pos = c->at<int>(L.tok_pos); a.out = c->at<f16_t>(L.attn); a.part_o = c->at<float>(L.attn_part);
+        a.part_ml = c->at<float>(L.attn_ml); a.mpps = L.mpps; a.layer = l; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads;
+        a.scale = 1.0f / sqrtf((float)m.head_dim); a.geo = c->geo;
+        int nsplit = (1024 + n * m.n_kv_heads - 1) / (n * m.n_kv_heads);
+        nsplit = std::max(1, std::min(std::min(nsplit, kMaxAttnSplits), std::max(1, L.mpps / 8)));
+        k_attn_decode(a, n, nsplit, s);
+        return;
+    }
     k_attn_simple(m.dtype, c->at<char>(L.q), paged ? nullptr : c->at<char>(L.kbuf), paged ? nullptr : c->at<char>(L.vbuf),
                   paged ? c->pool : nullptr, l, c->geo, c->at<int>(L.block_table), L.mpps, c->at<int>(L.tok_pos),
                   c->at<int>(L.tok_slot), c->at<char>(L.attn), n, m.n_q_heads, max_ctx, s);
@@ -277,7 +305,10 @@ static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged,
 
 static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a, int splits, hipStream_t s) {
     ProfScope ps(c, cls, s);
-    k_gemm_mfma(epi, a, splits, s);
+    if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU))
+        k_gemm_stream(epi, a, splits, s);
+    else
+        k_gemm_mfma(epi, a, splits, s);
 }
 
 // Split count for a weight-streaming GEMM with n_tiles column tiles and K/64 k-tiles:
@@ -319,8 +350,8 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             g.outF = part; g.ldc = L.nqkv; g.split_stride = (int64_t)n * L.nqkv;
             int sp = decode_splits(L.nqkv / 128, m.d_model);
             mfma(c, gcls, MG_STORE_F32, g, sp, s);
-            k_rope_append(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, nullptr, nullptr,
-                          write_pages ? c->pool : nullptr, l, c->geo, bt, L.mpps, m.n_q_heads, s);
+            k_rope_append_split(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
+                                m.n_q_heads, s);
             attention(c, l, n, true, max_ctx, s);
             g = GemmArgs();
             g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
@@ -386,7 +417,7 @@ static void lm_head_logits(rl_ctx* c, int cls, const WeightsHost& W, const void*
 }
 
 static bool fast_path_supported(const rl_model_cfg& m) {
-    if (m.dtype != RL_BF16) return false;
+    if (m.dtype != RL_BF16 || m.d_model > 8192) return false;
     const int nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, qd = m.n_q_heads * m.head_dim;
     return k_gemm_mfma_supported(MG_QKV, nqkv, m.d_model, m.head_dim) &&
            k_gemm_mfma_supported(MG_STORE_F32, m.d_model, qd, m.head_dim) &&
@@ -464,6 +495,7 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
     k_fill_i32(c->at<int>(L.last_tok), 0, cfg->max_batch, s);
     k_fill_i32(c->at<int>(L.gen_count), 0, cfg->max_batch, s);
     k_fill_i32(c->at<int>(L.finished), 0, cfg->max_batch, s);
+    k_fill_i32(c->at<int>(L.step_count), 0, cfg->max_batch, s);
     hipError_t e = hipStreamSynchronize(s);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) {
@@ -476,6 +508,7 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
 
 void rollout_destroy(rl_ctx* c) {
     if (!c) return;
+    if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
     for (int k = 0; k < RL_K_COUNT; ++k)
         for (auto& r : c->prof[k]) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
@@ -556,7 +589,7 @@ int rollout_prefill(rl_ctx* c, const int32_t* prompt_ids, const int32_t* prompt_
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     k_prefill_state(prompt_ids, Pmax, c->at<int>(L.d_prompt_len), c->at<int>(L.last_tok), c->at<int>(L.seq_len),
-                    c->at<int>(L.gen_count), c->at<int>(L.finished), B, s);
+                    c->at<int>(L.gen_count), c->at<int>(L.finished), c->at<int>(L.step_count), B, s);
     for (int b = 0; b < B; ++b) c->cached[b] = need[b];
     c->B = B;
     HIP_TRY(hipGetLastError());
@@ -586,7 +619,8 @@ static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_
     lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
     SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
     k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
-             c->at<int>(L.gen_count), c->at<int>(L.finished), tok_out, logp_out, out_ids, out_logp, out_stride, s);
+             c->at<int>(L.gen_count), c->at<int>(L.finished), c->at<int>(L.step_count), tok_out, logp_out, out_ids,
+             out_logp, out_stride, s);
     for (int b = 0; b < B; ++b) c->cached[b] += 1;
     return RL_OK;
 }
@@ -630,9 +664,35 @@ int rollout_generate(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prom
     for (int b = 0; b < B; ++b) need[b] = prompt_len[b] - 1 + G;
     rc = ensure_pages(c, need, s);
     if (rc) return rc;
-    for (int n = 0; n < G; ++n) {
-        rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids + n, out_logp ? out_logp + n : nullptr, G, s);
-        if (rc) return rc;
+    bool profiling = false;
+    for (int k = 0; k < RL_K_COUNT; ++k) profiling = profiling || c->prof_on[k] != 0;
+    if (c->impl == 1 && s != nullptr && c->use_graph && !profiling) {
+        // The step is identical from one token to the next (positions, step counters and page
+        // tables live on the device), so it is captured once and replayed G times.
+        rl_ctx::GraphKey key{B, G, c->impl, sample->eos_id, out_ids, out_logp, sample->seed, sample->seq_id_base,
+                             sample->temperature, s};
+        if (!c->gexec || !(key == c->gkey)) {
+            if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+            std::vector<int> saved = c->cached;
+            HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+            rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids, out_logp, G, s);
+            hipGraph_t graph = nullptr;
+            hipError_t e = hipStreamEndCapture(s, &graph);
+            c->cached = saved;
+            if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+            if (e != hipSuccess) return fail(RL_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+            e = hipGraphInstantiate(&c->gexec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) { c->gexec = nullptr; return fail(RL_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+            c->gkey = key;
+        }
+        for (int n = 0; n < G; ++n) HIP_TRY(hipGraphLaunch(c->gexec, s));
+        for (int b = 0; b < B; ++b) c->cached[b] += G;
+    } else {
+        for (int n = 0; n < G; ++n) {
+            rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids, out_logp, G, s);
+            if (rc) return rc;
+        }
     }
     if (out_len) k_out_len(c->at<int>(c->L.gen_count), out_len, B, s);
     HIP_TRY(hipGetLastError());

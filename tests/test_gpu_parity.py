@@ -242,3 +242,44 @@ def test_tuned_and_plain_kernels_agree(shape):
     for a, b in zip(s1, s0):
         assert np.abs(a - b).max() < 5e-3
     ro.close()
+
+
+def test_long_context_decode_uses_split_kv():
+    """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
+    (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
+    shape = MINI128
+    B, G = 3, 6
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 320)
+    ids, lens = synth.make_prompts(shape.vocab, B, 300, 180, 51)
+    lens[0] = 17
+    g_ids, _, g_lp = _generate(ro, ids, lens, G, 1.0, seed=13)
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    st = verify_rollout(mp, prompts, g_ids, g_lp, 1.0, 13, 0, 1e-3, 2e-2)
+    print("long ctx", st)
+    ro.rollout_set_impl(0)
+    p_ids, _, p_lp = _generate(ro, ids, lens, G, 1.0, seed=13)
+    assert np.abs(p_lp[:, 0] - g_lp[:, 0]).max() < 5e-3
+    ro.close()
+
+
+def test_captured_decode_graph_replays_match_eager():
+    """On a non-default stream rollout_generate captures one decode step as a HIP graph and
+    replays it; on the default stream it launches eagerly.  Same bits either way, also when
+    the graph is reused for new prompts and after other work ran in between."""
+    shape = MINI128
+    B, G = 4, 14
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 64)
+    side = torch.cuda.Stream()
+    results = []
+    for seed in (61, 62, 63):
+        ids, lens = synth.make_prompts(shape.vocab, B, 40, 21, seed)
+        eager = _generate(ro, ids, lens, G, 1.0, seed=9)
+        with torch.cuda.stream(side):
+            graph = _generate(ro, ids, lens, G, 1.0, seed=9)
+            side.synchronize()
+        assert np.array_equal(eager[0], graph[0]) and np.array_equal(eager[2], graph[2])
+        seqs, slens, plens = synth.make_sequences(shape.vocab, B, 64, 30, 0.5, seed)
+        results.append(_score(ro, Wp, Wr, seqs, slens, plens))      # unrelated work between replays
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    verify_rollout(mp, prompts, graph[0], graph[2], 1.0, 9, 0, 1e-3, 2e-2)
+    ro.close()
