@@ -15,3 +15,16 @@ struct DecodeAttnArgs {
     KvGeom geo{};
 };
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s);
+
+// Causal attention over a packed token list.  Sequences start at rows that are multiples of 32
+// and every row up to the next multiple of 32 past a sequence's end holds finite values.
+struct PrefillAttnArgs {
+    const f16_t* q = nullptr;    // [rows, Hq, hd]
+    const f16_t* k = nullptr;    // [rows, Hkv, hd]
+    const f16_t* vT = nullptr;   // [Hkv, hd, vt_cap]  (dim-major)
+    f16_t* out = nullptr;        // [rows, Hq * hd]
+    const int4* blocks = nullptr;  // per workgroup: (first row of the sequence, its length, query block, 0)
+    int Hq = 0, Hkv = 0, hd = 0, vt_cap = 0;
+    float scale = 0.f;
+};
+void k_attn_prefill(const PrefillAttnArgs& a, int nblocks, hipStream_t s);

@@ -180,3 +180,108 @@ void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
         else attn_merge_kernel<64><<<B * a.Hq, 64, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit);
     }
 }
+
+// ------------------------------------------------------------------ prefill / scoring: causal attention over packed sequences
+// Workgroup = (32-query block of one sequence, kv head g); wave w handles query head g*G + w,
+// so the waves of a workgroup stream the SAME keys and values (one trip through L2 for the
+// whole GQA group).  Per 32-key block: S^T (32 keys x 32 queries) by 32x32x16 MFMAs with K
+// rows as A and Q^T as B; base-2 online softmax per query (a lane owns one query column);
+// O^T += V^T P^T where the lane's own S^T registers, rounded to fp16, are the B operand and
+// V^T comes from the dim-major value buffer (two 8-byte loads per MFMA).
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int HD>
+__global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
+    constexpr int KSTEPS = HD / 16, DB = HD / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    const int4 blk = a.blocks[blockIdx.x];          // (row start, length, query block, -)
+    const int start = blk.x, len = blk.y, qb = blk.z;
+    const int g = blockIdx.y, G = a.Hq / a.Hkv, h = g * G + wave;
+    const int qi = qb * 32 + col;                   // this lane's query (position in the sequence)
+    const int qrow = start + min(qi, len - 1);
+    const int kvw = a.Hkv * HD;
+
+    half8 qf[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+        qf[s] = *reinterpret_cast<const half8*>(a.q + ((int64_t)qrow * a.Hq + h) * HD + s * 16 + g2 * 8);
+    floatx16 o[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float scale = a.scale * LOG2E;
+
+    for (int kb = 0; kb <= qb; ++kb) {
+        const int krow0 = start + kb * 32;
+        // S^T = K Q^T
+        floatx16 st;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = 0.f;
+        const f16_t* kp = a.k + (int64_t)(krow0 + col) * kvw + g * HD + g2 * 8;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            half8 kf = *reinterpret_cast<const half8*>(kp + s * 16);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], st, 0, 0, 0);
+        }
+        // register r of this lane is key kb*32 + 8*(r/4) + 4*g2 + r%4 for query qi
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
+            st[r] = (key <= qi) ? st[r] * scale : -INFINITY;
+            mx = fmaxf(mx, st[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
+        const float m_new = fmaxf(m_run, mx);        // finite: key kb*32 <= qi for every kb <= qb
+        const float alpha = exp2f(m_run - m_new);
+        half8 pf[2];
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float e = exp2f(st[r] - m_new);
+            ps += e;
+            pf[r >> 3][r & 7] = (f16_t)e;
+        }
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+        // O^T += V^T P^T
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+            const f16_t* vp = a.vT + ((int64_t)g * HD + d * 32 + col) * a.vt_cap + krow0 + 4 * g2;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                half4 lo = *reinterpret_cast<const half4*>(vp + kk * 16);
+                half4 hi = *reinterpret_cast<const half4*>(vp + kk * 16 + 8);
+                half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kk], o[d], 0, 0, 0);
+            }
+        }
+    }
+    l_run += __shfl_xor(l_run, 32, RL_WAVE);
+    if (qi < len) {
+        const float inv = 1.0f / l_run;
+        f16_t* op = a.out + ((int64_t)(start + qi) * a.Hq + h) * HD;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                half4 w4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w4[i] = (f16_t)(o[d][4 * j + i] * inv);
+                *reinterpret_cast<half4*>(op + d * 32 + 8 * j + 4 * g2) = w4;
+            }
+    }
+}
+
+void k_attn_prefill(const PrefillAttnArgs& a, int nblocks, hipStream_t s) {
+    if (nblocks <= 0) return;
+    dim3 grid(nblocks, a.Hkv);
+    const int threads = 64 * (a.Hq / a.Hkv);
+    if (a.hd == 128) attn_prefill_kernel<128><<<grid, threads, 0, s>>>(a);
+    else attn_prefill_kernel<64><<<grid, threads, 0, s>>>(a);
+}

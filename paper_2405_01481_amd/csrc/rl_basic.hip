@@ -69,25 +69,29 @@ void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, in
 // Row r of the chunk is batch row seq_first[r]; its row_len[r] tokens go to
 // [row_start[r], row_start[r] + row_len[r]).  tok_tgt (optional) = next token id of the
 // same row, or -1 when there is none inside full_len[r].
+// With align > 1 every row is padded to a multiple of align tokens; padding entries carry
+// token id 0, position -1 and no target.
 __global__ void pack_tokens_kernel(const int* ids, int ld_ids, const int* seq_first, const int* row_start,
-                                   const int* row_len, const int* full_len, int* tok_ids, int* tok_pos,
+                                   const int* row_len, const int* full_len, int align, int* tok_ids, int* tok_pos,
                                    int* tok_slot, int* tok_tgt) {
     int r = blockIdx.x;
     int b = seq_first[r], st = row_start[r], len = row_len[r];
+    const int alen = (len + align - 1) / align * align;
     const int* src = ids + (int64_t)b * ld_ids;
-    for (int t = threadIdx.x; t < len; t += blockDim.x) {
-        tok_ids[st + t] = src[t];
-        tok_pos[st + t] = t;
+    for (int t = threadIdx.x; t < alen; t += blockDim.x) {
+        const bool real = t < len;
+        tok_ids[st + t] = real ? src[t] : 0;
+        tok_pos[st + t] = real ? t : -1;
         tok_slot[st + t] = b;
-        if (tok_tgt) tok_tgt[st + t] = (t + 1 < full_len[r]) ? src[t + 1] : -1;
+        if (tok_tgt) tok_tgt[st + t] = (real && t + 1 < full_len[r]) ? src[t + 1] : -1;
     }
 }
 void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_start, const int* row_len,
-                   const int* full_len, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
+                   const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
                    hipStream_t s) {
     if (nrows <= 0) return;
-    pack_tokens_kernel<<<nrows, 256, 0, s>>>(ids, ld_ids, seq_first, row_start, row_len, full_len, tok_ids, tok_pos,
-                                             tok_slot, tok_tgt);
+    pack_tokens_kernel<<<nrows, 256, 0, s>>>(ids, ld_ids, seq_first, row_start, row_len, full_len, align, tok_ids,
+                                             tok_pos, tok_slot, tok_tgt);
 }
 
 // After prefill of the first P-1 prompt tokens: remember the last prompt token, lengths, counters.

@@ -90,7 +90,7 @@ void k_set_pages(int* block_table, int mpps, const int* triples_host, int n_trip
 void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok, int* tok_pos,
                   int* tok_slot, int B, hipStream_t s);
 void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_start, const int* row_len,
-                   const int* full_len, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
+                   const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
                    hipStream_t s);
 void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_tok, int* seq_len, int* gen_count,
                      int* finished, int* step_count, int B, hipStream_t s);

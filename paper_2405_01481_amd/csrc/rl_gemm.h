@@ -26,6 +26,7 @@ struct GemmArgs {
     f16_t* pool = nullptr;
     const int* block_table = nullptr;
     int mpps = 0, layer = 0, Hq = 0, Hkv = 0, hd = 0;
+    int vt_cap = 0;             // > 0: v_out is dim-major [Hkv][hd][vt_cap tokens]; 0: token-major [M][Hkv][hd]
     KvGeom geo{};
 };
 
@@ -36,3 +37,5 @@ int k_gemm_mfma_splits_used(int K, int splits);
 // Weight-streaming variant for M <= 128 (decode): epi MG_STORE_F32 (split-K partials / plain
 // fp32 store when splits == 1) or MG_SWIGLU.  Same shape requirements as k_gemm_mfma.
 void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s);
+bool k_gemm_stream_supported(int N, int K);       // K multiple of 128, N multiple of 128
+int k_gemm_stream_splits_used(int K, int splits);

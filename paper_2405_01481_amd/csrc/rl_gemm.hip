@@ -186,7 +186,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
             } else if (EPI == MG_QKV) {
                 // columns of this tile belong to one head (hd 128) or two (hd 64); pairs (j, j + hd/2)
                 // sit in adjacent 32-column MFMA tiles of this lane.
-                const int pos = a.tok_pos[m];
+                // pos < 0 marks a padding row of the packed token list: it gets zeros (so that
+                // nothing non-finite is ever read back as a key or value) and no cache slot
+                const int pos_raw = a.tok_pos[m];
+                const bool pad = pos_raw < 0;
+                const int pos = pad ? 0 : pos_raw;
                 const int hd = a.hd, half = hd >> 1;
 #pragma unroll
                 for (int j = 0; j < TN; j += 2) {
@@ -199,7 +203,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
                     } else {
                         col0 = nb * BN + c0;
                     }
-                    float v0 = acc[i][j][r], v1 = acc[i][j + 1][r];
+                    float v0 = pad ? 0.f : acc[i][j][r], v1 = pad ? 0.f : acc[i][j + 1][r];
                     const int head = col0 / hd, jj = col0 % hd;      // jj < half
                     const int Hq = a.Hq, Hkv = a.Hkv;
                     if (head < Hq + Hkv) {
@@ -216,7 +220,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
                             f16_t* o = a.k_out + ((int64_t)m * Hkv + g) * hd + jj;
                             o[0] = (f16_t)v0; o[half] = (f16_t)v1;
                         }
-                        if (a.pool) {
+                        if (a.pool && !pad) {
                             int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
                             int st = pos % a.geo.PT;
                             a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = (f16_t)v0;
@@ -225,10 +229,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
                     } else {
                         int g = head - Hq - Hkv;
                         if (a.v_out) {
-                            f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
-                            o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                            if (a.vt_cap > 0) {   // dim-major: vT[kv head][dim][token]
+                                a.v_out[((int64_t)g * hd + jj) * a.vt_cap + m] = (f16_t)v0;
+                                a.v_out[((int64_t)g * hd + jj + half) * a.vt_cap + m] = (f16_t)v1;
+                            } else {
+                                f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
+                                o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                            }
                         }
-                        if (a.pool) {
+                        if (a.pool && !pad) {
                             int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
                             int st = pos % a.geo.PT;
                             a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = (f16_t)v0;
@@ -242,27 +251,38 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 }
 
 // ------------------------------------------------------------------ weight-streaming GEMM (decode, M <= 128)
-// One workgroup = 128 rows x 128 columns of C over one K slice.  The four waves split the
-// columns (32 each, two 16-wide MFMA tiles) and each wave reads ITS OWN rows of W straight
-// from global memory in B-operand layout (every row contributes 64 contiguous bytes per
-// load instruction), several k-tiles ahead, so that enough bytes are in flight per CU to
-// cover HBM latency; W never touches LDS.  The activations (shared by all four waves, and
-// L2-resident) are staged through LDS.  v_mfma_f32_16x16x32_f16, fp32 accumulation.
+// One workgroup = 128 rows x 128 columns of C over one K slice, computed by two teams of
+// four waves: team t takes the k-tiles t, t+2, t+4, ... of the slice (a split over K inside
+// the workgroup, reduced through LDS at the end), so every SIMD hosts two waves that hide
+// each other's LDS / MFMA-issue latencies.  Inside a team the four waves split the columns
+// (32 each, two 16-wide MFMA tiles) and each wave reads ITS OWN rows of W straight from
+// global memory in B-operand layout (every row contributes 64 contiguous bytes per load
+// instruction), one k-tile ahead of the one being consumed; W never touches LDS.  The
+// activations (shared by a team's waves, and L2-resident) are staged through LDS.
+// v_mfma_f32_16x16x32_f16, fp32 accumulation.
 //   SG_PARTIAL: outF[ks][m][n] = partial sum of K slice ks
 //   SG_SWIGLU : a wave's two column tiles are (gate, up) rows of W for the same 16 outputs;
 //               the workgroup covers 64 outputs; outH[m][n] = silu(gate) * up
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 enum { SG_PARTIAL = 0, SG_SWIGLU = 1 };
+#define SG_TILE_HALFS (128 * LDS_STRIDE)
 
 template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
-    __shared__ __attribute__((aligned(16))) f16_t As[2][128 * LDS_STRIDE];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
+    // [team][buffer][128 rows x LDS_STRIDE]; reused as a 128 x 128 fp32 tile for the team reduction
+    __shared__ __attribute__((aligned(16))) f16_t As[2 * 2 * SG_TILE_HALFS];
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6, team = threadIdx.x >> 8;
     const int c16 = lane & 15, g4 = lane >> 4;
     const int nb = blockIdx.x, ks = blockIdx.y;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
-    const int nk = (kend - kbeg) / BK;
+    // k-tiles of the slice: (kend - kbeg) / BK, an even number (the launcher guarantees it);
+    // this team's tiles start at kbeg + team * BK and are 2 * BK apart
+    const int nk = (kend - kbeg) / (2 * BK);
+    const int k0 = kbeg + team * BK;
+    constexpr int KS = 2 * BK;
+    f16_t* As0 = As + team * 2 * SG_TILE_HALFS;
+    f16_t* As1 = As0 + SG_TILE_HALFS;
 
     // this lane's two W rows
     const bf16_t* wp[2];
@@ -271,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
         int row;
         if (EPI == SG_SWIGLU) row = (j ? a.up_offset : 0) + nb * 64 + wave * 16 + c16;
         else row = nb * 128 + wave * 32 + j * 16 + c16;
-        wp[j] = a.W + (int64_t)row * a.K + kbeg + g4 * 8;
+        wp[j] = a.W + (int64_t)row * a.K + k0 + g4 * 8;
     }
     // A staging: 4 chunks of 16 B per thread per k-tile.  Rows >= M are read from row M-1: a row
     // of C depends on the same row of A only, and rows >= M are never stored.
@@ -280,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int c = tid + i * 256, r = c >> 3, kc = c & 7;
-        a_src[i] = a.A + (int64_t)min(r, a.M - 1) * a.lda + kbeg + kc * 8;
+        a_src[i] = a.A + (int64_t)min(r, a.M - 1) * a.lda + k0 + kc * 8;
         a_dst[i] = r * LDS_STRIDE + kc * 8;
     }
     u32x4 ra[4];            // the A tile in flight (requested after the previous one was parked in LDS)
@@ -291,26 +311,27 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+#ifdef SGV_NO_W
+#define SG_WLOAD(ptr, kt) (u32x4{(unsigned)(kt), 0x3c003c00u, 0x3c003c00u, 0x3c003c00u})
+#else
+#define SG_WLOAD(ptr, kt) (*reinterpret_cast<const u32x4*>(ptr))
+#endif
 #define SG_LOAD(sl, kt)                                                                          \
     {                                                                                            \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                         \
-            ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * BK);                     \
+            ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * KS);                     \
         _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
-            wq##sl[s_ * 2 + j_] = *reinterpret_cast<const u32x4*>(wp[j_] + (kt) * BK + s_ * 32); \
+            wq##sl[s_ * 2 + j_] = SG_WLOAD(wp[j_] + (kt) * KS + s_ * 32, kt);                    \
     }
 #define SG_STORE_A(sl)                                                                           \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) *reinterpret_cast<u32x4*>(&As[sl][a_dst[i_]]) = ra[i_];
-    // Step kt: consume A tile kt (LDS buffer kt&1) and W tile kt (register slot kt&1) while tile
-    // kt+1 is in flight; then park A tile kt+1 in the other LDS buffer and request tile kt+2 into
-    // the slot just freed.  Vector loads return in order and A is requested before W, so no wait
-    // ever covers a request younger than one step.
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) *reinterpret_cast<u32x4*>(&As##sl[a_dst[i_]]) = ra[i_];
 #define SG_COMPUTE(sl)                                                                           \
     _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) {                                           \
         half8 bf_[2];                                                                            \
         _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) bf_[j_] = bf16x8_to_half8(wq##sl[s_ * 2 + j_]); \
         _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                       \
             half8 af_ = *reinterpret_cast<const half8*>(                                         \
-                &As[sl][(i_ * 16 + c16) * LDS_STRIDE + s_ * 32 + g4 * 8]);                       \
+                &As##sl[(i_ * 16 + c16) * LDS_STRIDE + s_ * 32 + g4 * 8]);                       \
             acc[i_][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[0], acc[i_][0], 0, 0, 0); \
             acc[i_][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[1], acc[i_][1], 0, 0, 0); \
         }                                                                                        \
@@ -357,6 +378,29 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
 #undef SG_LOAD
 #undef SG_STORE_A
 
+    // team reduction: team 1 parks its accumulators in LDS as a 128 x 128 fp32 tile (row m,
+    // tile-local column), team 0 adds them to its own, in this fixed order
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(As);
+    if (team == 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    red[(i * 16 + g4 * 4 + r) * 128 + wave * 32 + j * 16 + c16] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (team == 1) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[i][j][r] += red[(i * 16 + g4 * 4 + r) * 128 + wave * 32 + j * 16 + c16];
+
     // epilogue: acc[i][j][r] = C(row i*16 + g4*4 + r, column tile j, col c16)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -379,19 +423,33 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(GemmArgs a) {
     }
 }
 
+// K slices hold an even number of 64-wide k-tiles (two teams per workgroup).
+static void stream_split(GemmArgs& a, int& splits) {
+    if (splits < 1) splits = 1;
+    int kt2 = a.K / (2 * BK);                     // pairs of k-tiles
+    int per = (kt2 + splits - 1) / splits;
+    a.k_per_split = per * 2 * BK;
+    splits = (kt2 + per - 1) / per;
+}
+
+bool k_gemm_stream_supported(int N, int K) { return K % (2 * BK) == 0 && N % 128 == 0; }
+
+int k_gemm_stream_splits_used(int K, int splits) {
+    GemmArgs a;
+    a.K = K;
+    stream_split(a, splits);
+    return splits;
+}
+
 void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return;
-    if (splits < 1) splits = 1;
-    int kt = a.K / BK;
-    int per = (kt + splits - 1) / splits;
-    a.k_per_split = per * BK;
-    splits = (kt + per - 1) / per;
+    stream_split(a, splits);
     if (epi == MG_SWIGLU) {
         dim3 grid(a.N / 64, 1);
-        gemm_stream_kernel<SG_SWIGLU><<<grid, 256, 0, s>>>(a);
+        gemm_stream_kernel<SG_SWIGLU><<<grid, 512, 0, s>>>(a);
     } else {
         dim3 grid(a.N / 128, splits);
-        gemm_stream_kernel<SG_PARTIAL><<<grid, 256, 0, s>>>(a);
+        gemm_stream_kernel<SG_PARTIAL><<<grid, 512, 0, s>>>(a);
     }
 }
 

@@ -33,9 +33,9 @@ struct Layout {
     size_t last_tok, seq_len, gen_count, finished, cur_tok, step_count;
     size_t tok_ids, tok_pos, tok_slot, tok_tgt;
     size_t seq_first, row_start, row_len, full_len, d_seq_len, d_prompt_len, errflag;
-    size_t splitk, attn_part, attn_ml, lse_part;
+    size_t splitk, attn_part, attn_ml, lse_part, blocks;
     size_t total;
-    int rows, logit_rows, mpps, nqkv;
+    int rows, logit_rows, mpps, nqkv, vt_cap, max_blocks;
 };
 
 static size_t esz_of(int dtype) { return dtype == RL_FP32 ? 4 : 2; }
@@ -53,7 +53,8 @@ static Layout make_layout(const rl_model_cfg& c) {
         return o;
     };
     const size_t e = esz_of(c.dtype);
-    const int rows = std::max(c.max_chunk_tokens, c.max_batch);
+    // token rows of one pass; sequences are packed at multiples of 32 rows on the tuned path
+    const int rows = (std::max(c.max_chunk_tokens, c.max_batch) + 31) / 32 * 32 + 32;
     const int nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim;
     L.rows = rows;
@@ -65,7 +66,8 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.qkv = take((size_t)rows * nqkv * 4);
     L.q = take((size_t)rows * qd * e);
     L.kbuf = take((size_t)rows * kd * e);
-    L.vbuf = take((size_t)(rows + 64) * kd * e);
+    L.vt_cap = rows;
+    L.vbuf = take((size_t)rows * kd * e);
     L.attn = take((size_t)rows * qd * e);
     L.ffn = take((size_t)rows * c.d_ffn * e);
     L.logits = take((size_t)L.logit_rows * c.vocab * 4);
@@ -94,6 +96,8 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.attn_part = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * c.head_dim * 4);
     L.attn_ml = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * 2 * 4);
     L.lse_part = take((size_t)rows * ((c.vocab + 127) / 128) * 2 * 4);
+    L.max_blocks = rows / 32 + c.max_batch;
+    L.blocks = take((size_t)L.max_blocks * sizeof(int4));
     L.total = off;
     return L;
 }
@@ -247,7 +251,7 @@ static void gemm(rl_ctx* c, int cls, int epi, const void* A, int lda, const void
 // paged = attention reads the paged cache (decode); else the chunk's own contiguous K/V.
 // write_pages = append K/V of these tokens to the paged cache.
 // Returns true when h already holds RMSNorm(x; final_norm) (the tuned decode path fuses it).
-static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, hipStream_t s) {
+static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblocks, hipStream_t s) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     ProfScope ps(c, paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL, s);
@@ -262,13 +266,21 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, hipStrea
         k_attn_decode(a, n, nsplit, s);
         return;
     }
+    if (!paged && c->impl == 1) {
+        PrefillAttnArgs a;
+        a.q = c->at<f16_t>(L.q); a.k = c->at<f16_t>(L.kbuf); a.vT = c->at<f16_t>(L.vbuf); a.out = c->at<f16_t>(L.attn);
+        a.blocks = c->at<int4>(L.blocks); a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim;
+        a.vt_cap = L.vt_cap; a.scale = 1.0f / sqrtf((float)m.head_dim);
+        k_attn_prefill(a, nblocks, s);
+        return;
+    }
     k_attn_simple(m.dtype, c->at<char>(L.q), paged ? nullptr : c->at<char>(L.kbuf), paged ? nullptr : c->at<char>(L.vbuf),
                   paged ? c->pool : nullptr, l, c->geo, c->at<int>(L.block_table), L.mpps, c->at<int>(L.tok_pos),
                   c->at<int>(L.tok_slot), c->at<char>(L.attn), n, m.n_q_heads, max_ctx, s);
 }
 
 static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                             hipStream_t s) {
+                             int nblocks, hipStream_t s) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int dt = m.dtype;
@@ -292,7 +304,7 @@ static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged,
         gemm(c, gcls, EPI_STORE_F32, h, m.d_model, W.wqkv[l], nullptr, n, L.nqkv, m.d_model, qkv, nullptr, L.nqkv, s);
         k_rope_append(dt, qkv, 1, 0, n, tpos, tslot, rope, q, paged ? nullptr : kb, paged ? nullptr : vb,
                       write_pages ? c->pool : nullptr, l, c->geo, bt, L.mpps, m.n_q_heads, s);
-        attention(c, l, n, paged, max_ctx, s);
+        attention(c, l, n, paged, max_ctx, nblocks, s);
         gemm(c, gcls, EPI_RESID, att, qd, W.wo[l], nullptr, n, m.d_model, qd, x, nullptr, m.d_model, s);
         k_rmsnorm(dt, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
         const char* wg = (const char*)W.w_gate_up[l];
@@ -305,25 +317,24 @@ static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged,
 
 static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a, int splits, hipStream_t s) {
     ProfScope ps(c, cls, s);
-    if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU))
+    if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU) &&
+        k_gemm_stream_supported(a.N, a.K))
         k_gemm_stream(epi, a, splits, s);
     else
         k_gemm_mfma(epi, a, splits, s);
 }
 
-// Split count for a weight-streaming GEMM with n_tiles column tiles and K/64 k-tiles:
-// enough workgroups to cover the 256 CUs about twice, at least 4 k-tiles each.
+// Split count for a weight-streaming GEMM with n_tiles column tiles: the streaming kernel keeps
+// one 8-wave workgroup per CU, so aim for as many workgroups as fit in one round of 256 CUs.
 static int decode_splits(int n_tiles, int K) {
-    int want = (512 + n_tiles - 1) / n_tiles;
-    int kt = K / 64;
-    want = std::min(want, std::max(1, kt / 4));
+    int want = std::max(1, 256 / std::max(1, n_tiles));
     want = std::min(want, kMaxSplitK);
-    return k_gemm_mfma_splits_used(K, std::max(1, want));
+    return k_gemm_stream_splits_used(K, want);
 }
 
 // bf16 weights / fp16 activations on the MFMA kernels.
 static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                            hipStream_t s) {
+                            int nblocks, hipStream_t s) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int qd = m.n_q_heads * m.head_dim;
@@ -352,7 +363,7 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             mfma(c, gcls, MG_STORE_F32, g, sp, s);
             k_rope_append_split(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
                                 m.n_q_heads, s);
-            attention(c, l, n, true, max_ctx, s);
+            attention(c, l, n, true, max_ctx, 0, s);
             g = GemmArgs();
             g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
@@ -375,9 +386,9 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
             g.tok_pos = tpos; g.tok_slot = tslot; g.rope = rope; g.q_out = q; g.k_out = kb; g.v_out = vb;
             g.pool = write_pages ? (f16_t*)c->pool : nullptr; g.block_table = bt; g.mpps = L.mpps; g.layer = l;
-            g.Hq = m.n_q_heads; g.Hkv = m.n_kv_heads; g.hd = m.head_dim; g.geo = c->geo;
+            g.Hq = m.n_q_heads; g.Hkv = m.n_kv_heads; g.hd = m.head_dim; g.geo = c->geo; g.vt_cap = L.vt_cap;
             mfma(c, gcls, MG_QKV, g, 1, s);
-            attention(c, l, n, false, max_ctx, s);
+            attention(c, l, n, false, max_ctx, nblocks, s);
             g = GemmArgs();
             g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
             g.outF = x; g.ldc = m.d_model;
@@ -397,9 +408,9 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
 }
 
 static bool run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                       hipStream_t s) {
-    if (c->impl == 1) return run_layers_fast(c, W, n, paged, write_pages, max_ctx, s);
-    return run_layers_plain(c, W, n, paged, write_pages, max_ctx, s);
+                       int nblocks, hipStream_t s) {
+    if (c->impl == 1) return run_layers_fast(c, W, n, paged, write_pages, max_ctx, nblocks, s);
+    return run_layers_plain(c, W, n, paged, write_pages, max_ctx, nblocks, s);
 }
 
 // LM head on rows [0, nr) of h: logits fp32 [nr, V]
@@ -426,21 +437,62 @@ static bool fast_path_supported(const rl_model_cfg& m) {
            k_gemm_mfma_supported(MG_STORE_F32, m.vocab, m.d_model, m.head_dim);
 }
 
+// A pass works on whole sequences packed into one token list.  On the tuned path every sequence
+// starts at a multiple of 32 rows (the MFMA attention walks 32-key blocks) and the padding rows
+// are marked; the plain path packs densely.
+struct Chunk {
+    std::vector<int> rows_b, starts, lens, full;
+    int n = 0;          // rows in the list, padding included
+    int max_ctx = 1;
+    int nblocks = 0;    // 32-query blocks (tuned path)
+};
+static int pack_align(const rl_ctx* c) { return c->impl == 1 ? 32 : 1; }
+
+// Take sequences b0.. while they fit; returns the first sequence not taken.
+static int chunk_take(const rl_ctx* c, const std::vector<int>& len_of, int b0, int B, Chunk& ch) {
+    const int al = pack_align(c);
+    int b1 = b0;
+    while (b1 < B) {
+        int alen = (len_of[b1] + al - 1) / al * al;
+        if (ch.n + alen > c->cfg.max_chunk_tokens && ch.n > 0) break;
+        ch.rows_b.push_back(b1);
+        ch.starts.push_back(ch.n);
+        ch.lens.push_back(len_of[b1]);
+        ch.full.push_back(len_of[b1]);
+        ch.n += alen;
+        ch.max_ctx = std::max(ch.max_ctx, len_of[b1]);
+        ++b1;
+    }
+    return b1;
+}
+
 // Upload a chunk's row descriptors and build the packed token arrays on the device.
-static int pack_chunk(rl_ctx* c, const int* ids, int ld_ids, const std::vector<int>& rows_b,
-                      const std::vector<int>& starts, const std::vector<int>& lens, const std::vector<int>& full,
-                      bool targets, hipStream_t s) {
+static int pack_chunk(rl_ctx* c, const int* ids, int ld_ids, Chunk& ch, bool targets, hipStream_t s) {
     const Layout& L = c->L;
-    const size_t nb = rows_b.size() * sizeof(int);
-    HIP_TRY(hipMemcpyAsync(c->at<int>(L.seq_first), rows_b.data(), nb, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_start), starts.data(), nb, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_len), lens.data(), nb, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(c->at<int>(L.full_len), full.data(), nb, hipMemcpyHostToDevice, s));
+    const size_t nb = ch.rows_b.size() * sizeof(int);
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.seq_first), ch.rows_b.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_start), ch.starts.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_len), ch.lens.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.full_len), ch.full.data(), nb, hipMemcpyHostToDevice, s));
+    std::vector<int4> blocks;
+    if (c->impl == 1) {
+        // one workgroup per 32-query block; long (late) blocks first so the tail of the grid is short work
+        int maxqb = 0;
+        for (int len : ch.lens) maxqb = std::max(maxqb, (len + 31) / 32);
+        for (int qb = maxqb - 1; qb >= 0; --qb)
+            for (size_t r = 0; r < ch.lens.size(); ++r)
+                if (qb < (ch.lens[r] + 31) / 32) blocks.push_back(make_int4(ch.starts[r], ch.lens[r], qb, 0));
+        ch.nblocks = (int)blocks.size();
+        if (ch.nblocks > L.max_blocks) return fail(RL_EINVAL, "internal: attention block list overflow");
+        if (ch.nblocks)
+            HIP_TRY(hipMemcpyAsync(c->at<int4>(L.blocks), blocks.data(), blocks.size() * sizeof(int4),
+                                   hipMemcpyHostToDevice, s));
+    }
     // the host vectors may be reused by the caller right after this returns
     HIP_TRY(hipStreamSynchronize(s));
     k_pack_tokens(ids, ld_ids, c->at<int>(L.seq_first), c->at<int>(L.row_start), c->at<int>(L.row_len),
-                  c->at<int>(L.full_len), c->at<int>(L.tok_ids), c->at<int>(L.tok_pos), c->at<int>(L.tok_slot),
-                  targets ? c->at<int>(L.tok_tgt) : nullptr, (int)rows_b.size(), s);
+                  c->at<int>(L.full_len), pack_align(c), c->at<int>(L.tok_ids), c->at<int>(L.tok_pos),
+                  c->at<int>(L.tok_slot), targets ? c->at<int>(L.tok_tgt) : nullptr, (int)ch.rows_b.size(), s);
     return RL_OK;
 }
 
@@ -564,26 +616,15 @@ int rollout_prefill(rl_ctx* c, const int32_t* prompt_ids, const int32_t* prompt_
     // chunks of whole sequences, at most max_chunk_tokens tokens each
     int b0 = 0;
     while (b0 < B) {
-        std::vector<int> rows, starts, lens, full;
-        int n = 0, max_ctx = 1;
-        int b1 = b0;
-        while (b1 < B && n + need[b1] <= m.max_chunk_tokens) {
-            rows.push_back(b1);
-            starts.push_back(n);
-            lens.push_back(need[b1]);
-            full.push_back(need[b1]);
-            n += need[b1];
-            max_ctx = std::max(max_ctx, need[b1]);
-            ++b1;
-        }
-        if (n > 0) {
-            rc = pack_chunk(c, prompt_ids, Pmax, rows, starts, lens, full, false, s);
+        Chunk ch;
+        b0 = chunk_take(c, need, b0, B, ch);
+        if (ch.n > 0) {
+            rc = pack_chunk(c, prompt_ids, Pmax, ch, false, s);
             if (rc) return rc;
-            k_embed(m.dtype, c->at<int>(L.tok_ids), n, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+            k_embed(m.dtype, c->at<int>(L.tok_ids), ch.n, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
                     c->at<int>(L.errflag), s);
-            run_layers(c, c->policy, n, false, true, max_ctx, s);
+            run_layers(c, c->policy, ch.n, false, true, ch.max_ctx, ch.nblocks, s);
         }
-        b0 = b1;
     }
     // prompt lengths to the device for the state kernel
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
@@ -614,7 +655,7 @@ static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_
                  c->at<int>(L.tok_slot), B, s);
     k_embed(m.dtype, c->at<int>(L.cur_tok), B, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
             c->at<int>(L.errflag), s);
-    if (!run_layers(c, c->policy, B, true, true, max_ctx, s))
+    if (!run_layers(c, c->policy, B, true, true, max_ctx, 0, s))
         k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
     lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
     SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
@@ -705,24 +746,17 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     k_fill_f32(logp_out, 0.f, (int64_t)B * Lmax, s);
+    std::vector<int> len_of(seq_len, seq_len + B);
     int b0 = 0;
     while (b0 < B) {
-        std::vector<int> rows, starts, lens, full;
-        int n = 0, max_ctx = 1, b1 = b0;
-        while (b1 < B && n + seq_len[b1] <= m.max_chunk_tokens) {
-            rows.push_back(b1);
-            starts.push_back(n);
-            lens.push_back(seq_len[b1]);
-            full.push_back(seq_len[b1]);
-            n += seq_len[b1];
-            max_ctx = std::max(max_ctx, seq_len[b1]);
-            ++b1;
-        }
-        int rc = pack_chunk(c, ids, Lmax, rows, starts, lens, full, true, s);
+        Chunk ch;
+        b0 = chunk_take(c, len_of, b0, B, ch);
+        const int n = ch.n;
+        int rc = pack_chunk(c, ids, Lmax, ch, true, s);
         if (rc) return rc;
         k_embed(m.dtype, c->at<int>(L.tok_ids), n, W.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
                 c->at<int>(L.errflag), s);
-        run_layers(c, W, n, false, false, max_ctx, s);
+        run_layers(c, W, n, false, false, ch.max_ctx, ch.nblocks, s);
         k_rmsnorm(m.dtype, c->at<float>(L.x), W.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
         const size_t e = esz_of(m.dtype);
         for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
@@ -731,7 +765,6 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
             k_lse_gather(c->at<float>(L.logits), m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0,
                          c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, logp_out, Lmax, s);
         }
-        b0 = b1;
     }
     return RL_OK;
 }
