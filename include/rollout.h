@@ -46,7 +46,7 @@ enum {
     RL_ENOSPACE = -5       /* workspace / pool buffer smaller than required */
 };
 
-enum { RL_FP32 = 0, RL_BF16 = 1 };
+enum { RL_FP32 = 0, RL_BF16 = 1 };   /* dtype of the weight tensors */
 
 typedef struct rl_ctx rl_ctx; /* opaque */
 
@@ -54,7 +54,9 @@ typedef struct rl_model_cfg {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rope_base;          /* theta_j = rope_base^(-2j/head_dim) */
     float rms_eps;
-    int32_t dtype;            /* RL_FP32 or RL_BF16: dtype of weights, KV cache and GEMM inputs */
+    int32_t dtype;            /* RL_FP32: fp32 weights, activations and KV cache.  RL_BF16: bf16 weights;
+                                 activations between kernels and the KV cache are fp16 (11-bit significand),
+                                 accumulation and the residual stream fp32 */
     int32_t max_batch;        /* most sequences alive at once */
     int32_t max_seq;          /* longest sequence, prompt + generated tokens */
     int32_t page_tokens;      /* tokens per KV page (16) */
