@@ -263,7 +263,7 @@ def main():
     if not args.no_cpu:
         small = shape.body_params() < 5e9
         line["cpu_baseline"] = cpu_baseline(shape, wp, ids_np, plen, wl.sample_seed,
-                                            32 if not small else 64, 4 if not small else 16, wl.temperature)
+                                            128 if not small else 256, 24 if not small else 64, wl.temperature)
     else:
         line["cpu_baseline"] = None
     print(json.dumps(line))

@@ -266,7 +266,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 enum { SG_PARTIAL = 0, SG_SWIGLU = 1 };
-#define SG_TILE_HALFS (128 * LDS_STRIDE)
+#define SG_BK 64                       // k extent of one team step
+#define SG_STRIDE (SG_BK + 8)           // halfs per LDS row (+16 B pad: conflict-free ds_read_b128)
+#define SG_TILE_HALFS (128 * SG_STRIDE)
+#define SG_ACH (SG_BK / 16)             // 16-byte A chunks per thread per step
+#define SG_WLD (SG_BK / 16)             // W loads per wave-lane per step (k32 steps x 2 column tiles)
 
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
@@ -276,11 +280,11 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
     const int c16 = lane & 15, g4 = lane >> 4;
     const int nb = blockIdx.x, ks = blockIdx.y;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
-    // k-tiles of the slice: (kend - kbeg) / BK, an even number (the launcher guarantees it);
-    // this team's tiles start at kbeg + team * BK and are 2 * BK apart
-    const int nk = (kend - kbeg) / (2 * BK);
-    const int k0 = kbeg + team * BK;
-    constexpr int KS = 2 * BK;
+    // team steps of the slice: (kend - kbeg) / SG_BK, an even number (the launcher guarantees it);
+    // this team's steps start at kbeg + team * SG_BK and are 2 * SG_BK apart
+    const int nk = (kend - kbeg) / (2 * SG_BK);
+    const int k0 = kbeg + team * SG_BK;
+    constexpr int KS = 2 * SG_BK;
     f16_t* As0 = As + team * 2 * SG_TILE_HALFS;
     f16_t* As1 = As0 + SG_TILE_HALFS;
 
@@ -295,59 +299,59 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
     }
     // A staging: 4 chunks of 16 B per thread per k-tile.  Rows >= M are read from row M-1: a row
     // of C depends on the same row of A only, and rows >= M are never stored.
-    const f16_t* a_src[4];
-    int a_dst[4];
+    const f16_t* a_src[SG_ACH];
+    int a_dst[SG_ACH];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int c = tid + i * 256, r = c >> 3, kc = c & 7;
+    for (int i = 0; i < SG_ACH; ++i) {
+        int c = tid + i * 256, r = c / (SG_BK / 8), kc = c % (SG_BK / 8);
         a_src[i] = a.A + (int64_t)min(r, a.M - 1) * a.lda + k0 + kc * 8;
-        a_dst[i] = r * LDS_STRIDE + kc * 8;
+        a_dst[i] = r * SG_STRIDE + kc * 8;
     }
-    u32x4 ra[4];            // the A tile in flight (requested after the previous one was parked in LDS)
-    u32x4 wq0[4], wq1[4];   // W tiles in flight, index = k32 step * 2 + column tile
+    u32x4 ra[SG_ACH];               // the A tile in flight (requested after the previous one was parked in LDS)
+    u32x4 wq0[SG_WLD], wq1[SG_WLD]; // W tiles in flight, index = k32 step * 2 + column tile
     floatx4 acc[8][2];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-#ifdef SGV_NO_W
-#define SG_WLOAD(ptr, kt) (u32x4{(unsigned)(kt), 0x3c003c00u, 0x3c003c00u, 0x3c003c00u})
-#else
 #define SG_WLOAD(ptr, kt) (*reinterpret_cast<const u32x4*>(ptr))
-#endif
-#define SG_LOAD(sl, kt)                                                                          \
-    {                                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                         \
-            ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * KS);                     \
-        _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
-            wq##sl[s_ * 2 + j_] = SG_WLOAD(wp[j_] + (kt) * KS + s_ * 32, kt);                    \
-    }
+#define SG_LOAD_A(kt)                                                                            \
+    _Pragma("unroll") for (int i_ = 0; i_ < SG_ACH; ++i_)                                        \
+        ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * KS);
+#define SG_LOAD_W(sl, kt)                                                                        \
+    _Pragma("unroll") for (int s_ = 0; s_ < SG_BK / 32; ++s_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
+        wq##sl[s_ * 2 + j_] = SG_WLOAD(wp[j_] + (kt) * KS + s_ * 32, kt);
+#define SG_CONVERT(sl)                                                                           \
+    _Pragma("unroll") for (int q_ = 0; q_ < SG_WLD; ++q_) cf[q_] = bf16x8_to_half8(wq##sl[q_]);
 #define SG_STORE_A(sl)                                                                           \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) *reinterpret_cast<u32x4*>(&As##sl[a_dst[i_]]) = ra[i_];
+    _Pragma("unroll") for (int i_ = 0; i_ < SG_ACH; ++i_) *reinterpret_cast<u32x4*>(&As##sl[a_dst[i_]]) = ra[i_];
 #define SG_COMPUTE(sl)                                                                           \
-    _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) {                                           \
-        half8 bf_[2];                                                                            \
-        _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) bf_[j_] = bf16x8_to_half8(wq##sl[s_ * 2 + j_]); \
+    _Pragma("unroll") for (int s_ = 0; s_ < SG_BK / 32; ++s_) {                                  \
         _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                       \
             half8 af_ = *reinterpret_cast<const half8*>(                                         \
-                &As##sl[(i_ * 16 + c16) * LDS_STRIDE + s_ * 32 + g4 * 8]);                       \
-            acc[i_][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[0], acc[i_][0], 0, 0, 0); \
-            acc[i_][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, bf_[1], acc[i_][1], 0, 0, 0); \
+                &As##sl[(i_ * 16 + c16) * SG_STRIDE + s_ * 32 + g4 * 8]);                        \
+            acc[i_][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, cf[s_ * 2 + 0], acc[i_][0], 0, 0, 0); \
+            acc[i_][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, cf[s_ * 2 + 1], acc[i_][1], 0, 0, 0); \
         }                                                                                        \
     }
-    // full step: compute tile kt, park A tile kt+1, request tile kt+2 into the freed slot
-#define SG_STEP_FULL(sl, other, kt)  { SG_COMPUTE(sl) SG_STORE_A(other) SG_LOAD(sl, (kt) + 2) __syncthreads(); }
-#define SG_STEP_NOLOAD(sl, other)    { SG_COMPUTE(sl) SG_STORE_A(other) __syncthreads(); }
-#define SG_STEP_LAST(sl)             { SG_COMPUTE(sl) }
+    // Step kt (slot = kt & 1): convert W tile kt to fp16, which frees its raw registers for the
+    // request of W tile kt+2 -- two full steps before it is needed; consume; park A tile kt+1 in
+    // the other LDS buffer and request A tile kt+2.
+#define SG_STEP_FULL(sl, other, kt)  { SG_CONVERT(sl) SG_LOAD_W(sl, (kt) + 2) __builtin_amdgcn_sched_barrier(0); SG_COMPUTE(sl) SG_STORE_A(other) SG_LOAD_A((kt) + 2) __syncthreads(); }
+#define SG_STEP_NOLOAD(sl, other)    { SG_CONVERT(sl) SG_COMPUTE(sl) SG_STORE_A(other) __syncthreads(); }
+#define SG_STEP_LAST(sl)             { SG_CONVERT(sl) SG_COMPUTE(sl) }
 
     // The steady-state path has no conditional loads anywhere between its first request and its
     // last wait: with vector loads returning in order, a wait count is exact only when every path
     // to it has issued the same requests.  Short K slices take a separate, simpler path.
+    half8 cf[SG_WLD];
     if (nk >= 4) {
-        SG_LOAD(0, 0)
+        SG_LOAD_A(0)
+        SG_LOAD_W(0, 0)
         SG_STORE_A(0)
-        SG_LOAD(1, 1)
+        SG_LOAD_A(1)
+        SG_LOAD_W(1, 1)
         __syncthreads();
         int kt = 0;
         for (; kt + 3 < nk; kt += 2) {
@@ -364,9 +368,11 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
         }
     } else {
         for (int kt = 0; kt < nk; ++kt) {
-            SG_LOAD(0, kt)
+            SG_LOAD_A(kt)
+            SG_LOAD_W(0, kt)
             SG_STORE_A(0)
             __syncthreads();
+            SG_CONVERT(0)
             SG_COMPUTE(0)
             __syncthreads();
         }
@@ -375,7 +381,9 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
 #undef SG_STEP_FULL
 #undef SG_STEP_NOLOAD
 #undef SG_STEP_LAST
-#undef SG_LOAD
+#undef SG_LOAD_A
+#undef SG_LOAD_W
+#undef SG_CONVERT
 #undef SG_STORE_A
 
     // team reduction: team 1 parks its accumulators in LDS as a 128 x 128 fp32 tile (row m,
@@ -423,16 +431,16 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
     }
 }
 
-// K slices hold an even number of 64-wide k-tiles (two teams per workgroup).
+// K slices hold an even number of team steps (two teams per workgroup).
 static void stream_split(GemmArgs& a, int& splits) {
     if (splits < 1) splits = 1;
-    int kt2 = a.K / (2 * BK);                     // pairs of k-tiles
+    int kt2 = a.K / (2 * SG_BK);                  // pairs of team steps
     int per = (kt2 + splits - 1) / splits;
-    a.k_per_split = per * 2 * BK;
+    a.k_per_split = per * 2 * SG_BK;
     splits = (kt2 + per - 1) / per;
 }
 
-bool k_gemm_stream_supported(int N, int K) { return K % (2 * BK) == 0 && N % 128 == 0; }
+bool k_gemm_stream_supported(int N, int K) { return K % (2 * SG_BK) == 0 && N % 128 == 0; }
 
 int k_gemm_stream_splits_used(int K, int splits) {
     GemmArgs a;
