@@ -10,6 +10,7 @@ struct GemmArgs {
     const bf16_t* W = nullptr;  // [Wrows, K] row-major
     int M = 0, N = 0, K = 0;    // N = output columns (MG_SWIGLU: d_ffn)
     int Wrows = 0;              // filled by the launcher
+    int n_blocks_n = 0;         // filled by the launcher
     int k_per_split = 0;        // filled by the launcher
     int up_offset = 0;          // MG_SWIGLU: row of W where the up projection starts
     float* outF = nullptr;      // MG_STORE_F32 (+ split * split_stride) / MG_RESID
@@ -39,3 +40,4 @@ int k_gemm_mfma_splits_used(int K, int splits);
 void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s);
 bool k_gemm_stream_supported(int N, int K);       // K multiple of 128, N multiple of 128
 int k_gemm_stream_splits_used(int K, int splits);
+extern int g_big_tiles;

@@ -71,7 +71,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     f16_t* Ws = As + 2 * BM * LDS_STRIDE;                         // [2][BN][LDS_STRIDE]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int nb = blockIdx.x, mb = blockIdx.y, ks = blockIdx.z;
+    // Tile order: workgroup ids walk groups of 8 row blocks column by column, so that the tiles in
+    // flight at any time cover a compact region (few distinct A row blocks and W column blocks),
+    // and -- ids being dealt round-robin to the 8 XCDs -- each XCD keeps re-using one A row block
+    // from its own L2.
+    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM, ks = blockIdx.z;
+    int nb, mb;
+    {
+        const int id = blockIdx.x, per_group = 8 * NB;
+        const int group = id / per_group, first = group * 8, gsz = min(MB - first, 8), r = id % per_group;
+        mb = first + r % gsz;
+        nb = r / gsz;
+    }
     const int m0 = mb * BM;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
     const int nk = (kend - kbeg + BK - 1) / BK;
@@ -84,35 +95,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < A_CH; ++i) {
         int c = tid + i * 256, r = c >> 3, kc = c & 7;
         int m = m0 + r;
-        a_src[i] = (m < a.M) ? a.A + (int64_t)m * a.lda + kc * 8 : nullptr;
+        a_src[i] = a.A + (int64_t)min(m, a.M - 1) * a.lda + kc * 8;   // rows >= M: any finite-or-not data, never stored
         a_dst[i] = r * LDS_STRIDE + kc * 8;
     }
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
         int c = tid + i * 256, r = c >> 3, kc = c & 7;
         int wr = w_row_of<EPI, BN>(r, nb, a);
-        w_src[i] = (wr < a.Wrows) ? a.W + (int64_t)wr * a.K + kc * 8 : nullptr;
+        w_src[i] = a.W + (int64_t)min(wr, a.Wrows - 1) * a.K + kc * 8;
         w_dst[i] = r * LDS_STRIDE + kc * 8;
     }
 
-    uint4 ra[A_CH], rw[W_CH];
-    auto load_g = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            ra[i] = a_src[i] ? *reinterpret_cast<const uint4*>(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < W_CH; ++i)
-            rw[i] = w_src[i] ? *reinterpret_cast<const uint4*>(w_src[i] + k0) : make_uint4(0, 0, 0, 0);
-    };
-    auto store_l = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            *reinterpret_cast<uint4*>(As + buf * BM * LDS_STRIDE + a_dst[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < W_CH; ++i)
-            *reinterpret_cast<uint4*>(Ws + buf * BN * LDS_STRIDE + w_dst[i]) = bf16x8_to_f16x8(rw[i]);
-    };
-
+    // Two register sets alternate between k-tiles: a tile is requested at the start of step kt-2's
+    // successor... concretely, tile kt+2 is requested at the start of step kt and parked in LDS at
+    // the end of step kt+1, so every global load has two full steps to arrive.  The steady-state
+    // loop issues the same requests on every path (vector loads return in order; a wait count is
+    // exact only then); prologue and the last two steps are peeled.
+    u32x4_t ra0[A_CH], rw0[W_CH], ra1[A_CH], rw1[W_CH];
+#define MG_LOAD(sl, kt)                                                                          \
+    {                                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < A_CH; ++i_)                                      \
+            ra##sl[i_] = *reinterpret_cast<const u32x4_t*>(a_src[i_] + kbeg + (kt) * BK);        \
+        _Pragma("unroll") for (int i_ = 0; i_ < W_CH; ++i_)                                      \
+            rw##sl[i_] = *reinterpret_cast<const u32x4_t*>(w_src[i_] + kbeg + (kt) * BK);        \
+    }
+#define MG_PARK(sl, buf)                                                                         \
+    {                                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < A_CH; ++i_)                                      \
+            *reinterpret_cast<u32x4_t*>(As + (buf) * BM * LDS_STRIDE + a_dst[i_]) = ra##sl[i_];  \
+        _Pragma("unroll") for (int i_ = 0; i_ < W_CH; ++i_)                                      \
+            *reinterpret_cast<half8*>(Ws + (buf) * BN * LDS_STRIDE + w_dst[i_]) = bf16x8_to_half8(rw##sl[i_]); \
+    }
     floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -120,34 +133,70 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    if (nk > 0) {
-        load_g(kbeg);
-        store_l(0);
-    }
-    __syncthreads();
     const int lrow = lane & 31, lk = (lane >> 5) * 8;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load_g(kbeg + (kt + 1) * BK);
-        const f16_t* Ab = As + cur * BM * LDS_STRIDE + (wm * TM * 32 + lrow) * LDS_STRIDE + lk;
-        const f16_t* Wb = Ws + cur * BN * LDS_STRIDE + (wn * TN * 32 + lrow) * LDS_STRIDE + lk;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            half8 af[TM], bf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const half8*>(Ab + i * 32 * LDS_STRIDE + kk);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const half8*>(Wb + j * 32 * LDS_STRIDE + kk);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_l(cur ^ 1);
-        __syncthreads();
+#define MG_FRAGS(dst_a, dst_b, kk)                                                               \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                               \
+        dst_a[i] = *reinterpret_cast<const half8*>(Ab + i * 32 * LDS_STRIDE + (kk));             \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                               \
+        dst_b[j] = *reinterpret_cast<const half8*>(Wb + j * 32 * LDS_STRIDE + (kk));
+#define MG_MFMAS(src_a, src_b)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(src_a[i], src_b[j], acc[i][j], 0, 0, 0);
+    // fragments of k-slice kk+16 are fetched from LDS while the MFMAs of slice kk run
+#define MG_COMPUTE(buf)                                                                          \
+    {                                                                                            \
+        const f16_t* Ab = As + (buf) * BM * LDS_STRIDE + (wm * TM * 32 + lrow) * LDS_STRIDE + lk; \
+        const f16_t* Wb = Ws + (buf) * BN * LDS_STRIDE + (wn * TN * 32 + lrow) * LDS_STRIDE + lk; \
+        half8 afA[TM], bfA[TN], afB[TM], bfB[TN];                                                \
+        MG_FRAGS(afA, bfA, 0)                                                                    \
+        MG_FRAGS(afB, bfB, 16)                                                                   \
+        MG_MFMAS(afA, bfA)                                                                       \
+        MG_FRAGS(afA, bfA, 32)                                                                   \
+        MG_MFMAS(afB, bfB)                                                                       \
+        MG_FRAGS(afB, bfB, 48)                                                                   \
+        MG_MFMAS(afA, bfA)                                                                       \
+        MG_MFMAS(afB, bfB)                                                                       \
     }
+    // step with tile parity p: request tile kt+2 into set p (its previous tile is already parked),
+    // consume LDS buffer p, park set 1-p (tile kt+1) into buffer 1-p
+#define MG_STEP_FULL(p, q, kt) { MG_LOAD(p, (kt) + 2) __builtin_amdgcn_sched_barrier(0); MG_COMPUTE(p) MG_PARK(q, q) __syncthreads(); }
+#define MG_STEP_PARK(p, q)     { MG_COMPUTE(p) MG_PARK(q, q) __syncthreads(); }
+#define MG_STEP_LAST(p)        { MG_COMPUTE(p) }
+    if (nk >= 3) {
+        MG_LOAD(0, 0)
+        MG_LOAD(1, 1)
+        MG_PARK(0, 0)
+        __syncthreads();
+        int kt = 0;
+        for (; kt + 3 < nk; kt += 2) {
+            MG_STEP_FULL(0, 1, kt)
+            MG_STEP_FULL(1, 0, kt + 1)
+        }
+        if (nk - kt == 3) {
+            MG_STEP_FULL(0, 1, kt)
+            MG_STEP_PARK(1, 0)
+            MG_STEP_LAST(0)
+        } else {
+            MG_STEP_PARK(0, 1)
+            MG_STEP_LAST(1)
+        }
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+            MG_LOAD(0, kt)
+            MG_PARK(0, 0)
+            __syncthreads();
+            MG_COMPUTE(0)
+            __syncthreads();
+        }
+    }
+#undef MG_LOAD
+#undef MG_PARK
+#undef MG_COMPUTE
+#undef MG_FRAGS
+#undef MG_MFMAS
+#undef MG_STEP_FULL
+#undef MG_STEP_PARK
+#undef MG_STEP_LAST
 
     // ---- epilogue.  acc[i][j][r] is C(row, col) with
     //   row = m0 + wm*TM*32 + i*32 + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
@@ -470,9 +519,13 @@ static void launch(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s)
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    dim3 grid(n_blocks_n, (a.M + BM - 1) / BM, splits);
-    gemm_mfma_kernel<BM, BN, WGM, WGN, EPI><<<grid, 256, lds, s>>>(a);
+    GemmArgs b = a;
+    b.n_blocks_n = n_blocks_n;
+    dim3 grid(n_blocks_n * ((a.M + BM - 1) / BM), 1, splits);
+    gemm_mfma_kernel<BM, BN, WGM, WGN, EPI><<<grid, 256, lds, s>>>(b);
 }
+
+int g_big_tiles = 0;   // 1: 256 x 128 workgroup tiles for large M (measured slower than 128 x 128 at 2 workgroups per CU)
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
     if (K % BK != 0) return false;
@@ -488,12 +541,33 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     int per = (kt + splits - 1) / splits;
     a.k_per_split = per * BK;
     splits = (kt + per - 1) / per;
+    const bool big = a.M >= 1024 && splits == 1 && g_big_tiles;
     switch (epi) {
-        case MG_STORE_F32: a.Wrows = a.N; launch<128, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, splits, s); break;
-        case MG_STORE_F16: a.Wrows = a.N; launch<128, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s); break;
-        case MG_RESID: a.Wrows = a.N; launch<128, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s); break;
-        case MG_SWIGLU: a.Wrows = a.up_offset + a.N; launch<128, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s); break;
-        case MG_QKV: a.Wrows = a.N; launch<128, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s); break;
+        case MG_STORE_F32:
+            a.Wrows = a.N;
+            if (big) launch<256, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, 1, s);
+            else launch<128, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, splits, s);
+            break;
+        case MG_STORE_F16:
+            a.Wrows = a.N;
+            if (big) launch<256, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s);
+            else launch<128, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s);
+            break;
+        case MG_RESID:
+            a.Wrows = a.N;
+            if (big) launch<256, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s);
+            else launch<128, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s);
+            break;
+        case MG_SWIGLU:
+            a.Wrows = a.up_offset + a.N;
+            if (big) launch<256, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
+            else launch<128, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
+            break;
+        case MG_QKV:
+            a.Wrows = a.N;
+            if (big) launch<256, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
+            else launch<128, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
+            break;
         default: break;
     }
 }

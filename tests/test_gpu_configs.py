@@ -43,3 +43,69 @@ def test_1b_shape_scoring_and_rollout_subset():
     errs = check_scores(*[a[rows] for a in got], ref, 2e-2, 0.003)
     print("1b subset:", st, errs)
     ro.close()
+
+
+def _run_and_check(shape, B, P_lo, P_hi, G, rows, seed=4, temp=1.0, chunk=None, score_positions=None):
+    """Generate with the GPU path, then verify `rows` with the oracle at the shape's full width and
+    depth: every generated token along the GPU trajectory, and teacher-forced scores of both models."""
+    wp, wr = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
+    Wp, Wr = R.Weights(wp), R.Weights(wr)
+    Lmax = P_hi + G
+    ro = R.Rollout(R.make_cfg(shape, B, Lmax, max_chunk_tokens=chunk), Wp, DEV)
+    ids, lens = synth.make_prompts(shape.vocab, B, P_hi, P_lo, 3)
+    out = torch.zeros(B, G, dtype=torch.int32, device=DEV)
+    olp = torch.zeros(B, G, dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                      # captured-graph decode, as bench.py runs it
+        ro.rollout_generate(R.sample_cfg(seed, temp), torch.tensor(ids, device=DEV), lens, G, out, None, olp)
+        side.synchronize()
+    ro.rollout_check()
+    g = out.cpu().numpy()
+    full = np.zeros((B, Lmax), np.int32)
+    for b in range(B):
+        full[b, :lens[b]] = ids[b, :lens[b]]
+        full[b, lens[b]:lens[b] + G] = g[b]
+    L = (lens + G).astype(np.int32)
+    outs = [torch.zeros(B, Lmax, dtype=torch.float32, device=DEV) for _ in range(4)]
+    ro.score_logprobs_kl(Wp, Wr, torch.tensor(full, device=DEV), L, lens, 0.003, *outs)
+    ro.rollout_check()
+    got = [o.cpu().numpy() for o in outs]
+    ro.close()
+    del ro
+    mp = O.Model(shape, synth.weights_for_oracle(wp))
+    mr = O.Model(shape, synth.weights_for_oracle(wr))
+    del wp, wr
+    torch.cuda.empty_cache()
+    st = verify_rollout(mp, [ids[b, :lens[b]] for b in range(B)], g, olp.cpu().numpy(), temp, seed, 0, 1e-3, 2e-2,
+                        rows=rows)
+    ref = O.score_batch(mp, mr, full[rows], L[rows], lens[rows], 0.003)
+    errs = check_scores(*[a[rows] for a in got], ref, 2e-2, 0.003)
+    # generation log-probs are the teacher-forced policy scores of the same tokens
+    for b in rows:
+        assert np.abs(got[0][b, lens[b]:L[b]] - olp.cpu().numpy()[b]).max() < 2e-2
+    return st, errs
+
+
+def test_70b_shape_two_layers():
+    """Config 5's width (d 8192, 64 query / 8 KV heads: GQA group of 8, FFN 28672, vocab 128256) at
+    two layers: exercises the widest rows and the 8-wave attention workgroups."""
+    s = synth.scaled_shape(synth.L70B, "70b_2l", n_layers=2)
+    st, errs = _run_and_check(s, 3, 30, 44, 6, rows=[1])
+    print("70b-shape 2 layers:", st, errs)
+
+
+def test_8b_long_ragged_four_layers():
+    """Config 4's regime (ragged prompts, contexts of 1-2 k tokens, split-KV decode, long causal
+    prefill) at the 8B width with four layers, so the oracle finishes in about a minute."""
+    s = synth.scaled_shape(synth.L8B, "8b_4l", n_layers=4)
+    st, errs = _run_and_check(s, 3, 1030, 1700, 5, rows=[0])
+    print("8b long ragged 4 layers:", st, errs)
+
+
+@pytest.mark.slow
+def test_8b_full_depth_subset():
+    """Config 3's model at full width and depth (32 layers): batch 4, prompts of 40, 8 generated
+    tokens; the oracle checks one row (both models)."""
+    s = synth.L8B
+    st, errs = _run_and_check(s, 4, 40, 40, 8, rows=[2])
+    print("8b full depth:", st, errs)
