@@ -685,3 +685,29 @@ void k_kl(const float* lp, const float* lr, const int* seq_len, const int* promp
     dim3 grid((Lmax + 255) / 256, B);
     kl_kernel<<<grid, 256, 0, s>>>(lp, lr, seq_len, prompt_len, Lmax, coef, kl, pen);
 }
+
+// ---------------------------------------------------------------- log-prob from per-group (max, sum-exp) partials
+// One wave per row: combine the nparts pairs written by the LM-head GEMM epilogue into
+// log sum_v exp(z_v) and write logp = z_target - lse at [slot, pos + 1].
+__global__ __launch_bounds__(64) void lse_reduce_kernel(const float2* part, int nparts, const float* z_tgt,
+                                                        const int* tok_tgt, const int* tok_slot, const int* tok_pos,
+                                                        float* logp_out, int ld_out) {
+    const int r = blockIdx.x;
+    if (tok_tgt[r] < 0) return;
+    const float2* p = part + (int64_t)r * nparts;
+    float m = -INFINITY, s = 0.f;
+    for (int i = threadIdx.x; i < nparts; i += 64) {
+        float2 v = p[i];
+        float mn = fmaxf(m, v.x);
+        s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
+        m = mn;
+    }
+    float mt = wave_max(m);
+    s = wave_sum(s * __expf(m - mt));
+    if (threadIdx.x == 0) logp_out[(int64_t)tok_slot[r] * ld_out + tok_pos[r] + 1] = z_tgt[r] - mt - logf(s);
+}
+void k_lse_reduce(const float2* part, int nparts, const float* z_tgt, int nrows, const int* tok_tgt,
+                  const int* tok_slot, const int* tok_pos, float* logp_out, int ld_out, hipStream_t s) {
+    if (nrows <= 0) return;
+    lse_reduce_kernel<<<nrows, 64, 0, s>>>(part, nparts, z_tgt, tok_tgt, tok_slot, tok_pos, logp_out, ld_out);
+}

@@ -117,3 +117,5 @@ void k_lse_gather(const float* logits, int ldz, int V, int nrows, const int* tok
 void k_kl(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int B, int Lmax, float coef,
           float* kl, float* pen, hipStream_t s);
 void k_out_len(const int* gen_count, int* out_len, int B, hipStream_t s);
+void k_lse_reduce(const float2* part, int nparts, const float* z_tgt, int nrows, const int* tok_tgt,
+                  const int* tok_slot, const int* tok_pos, float* logp_out, int ld_out, hipStream_t s);

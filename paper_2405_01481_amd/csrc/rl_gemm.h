@@ -2,7 +2,7 @@
 #pragma once
 #include "rl_common.h"
 
-enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4 };
+enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4, MG_LSE = 5 };
 
 struct GemmArgs {
     const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
@@ -27,6 +27,12 @@ struct GemmArgs {
     f16_t* pool = nullptr;
     const int* block_table = nullptr;
     int mpps = 0, layer = 0, Hq = 0, Hkv = 0, hd = 0;
+    // MG_LSE (LM head for scoring): per row and per 64-column group the pair (max, sum exp(z - max))
+    // goes to lse_part[row][N/64]; the logit of the row's target token (tgt[row] >= 0) to z_tgt[row].
+    // The logits themselves are never stored.
+    const int* tgt = nullptr;
+    float2* lse_part = nullptr;
+    float* z_tgt = nullptr;
     int vt_cap = 0;             // > 0: v_out is dim-major [Hkv][hd][vt_cap tokens]; 0: token-major [M][Hkv][hd]
     KvGeom geo{};
 };

@@ -232,6 +232,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
                     float g = acc[i][j][r], u = acc[i][j + 1][r];
                     if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
                 }
+            } else if (EPI == MG_LSE) {
+                // this wave's TN*32 columns of row m: running (max, sum of exponentials) over the
+                // lanes that share the row (the 32 lanes of a half-wave), and the target's logit
+                float mx = acc[i][0][r];
+#pragma unroll
+                for (int j = 1; j < TN; ++j) mx = fmaxf(mx, acc[i][j][r]);
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, RL_WAVE));
+                float se = 0.f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) se += __expf(acc[i][j][r] - mx);
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) se += __shfl_xor(se, o, RL_WAVE);
+                const int nparts = (a.N / BN) * WGN;
+                if (lrow == 0) a.lse_part[(int64_t)m * nparts + nb * WGN + wn] = make_float2(mx, se);
+                const int t = a.tgt[m];
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (t == nb * BN + wn * TN * 32 + j * 32 + lrow) a.z_tgt[m] = acc[i][j][r];
             } else if (EPI == MG_QKV) {
                 // columns of this tile belong to one head (hd 128) or two (hd 64); pairs (j, j + hd/2)
                 // sit in adjacent 32-column MFMA tiles of this lane.
@@ -562,6 +581,10 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
             a.Wrows = a.up_offset + a.N;
             if (big) launch<256, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
             else launch<128, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
+            break;
+        case MG_LSE:
+            a.Wrows = a.N;
+            launch<128, 128, 2, 2, MG_LSE>(a, a.N / 128, 1, s);
             break;
         case MG_QKV:
             a.Wrows = a.N;

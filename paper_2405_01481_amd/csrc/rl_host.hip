@@ -33,7 +33,7 @@ struct Layout {
     size_t last_tok, seq_len, gen_count, finished, cur_tok, step_count;
     size_t tok_ids, tok_pos, tok_slot, tok_tgt;
     size_t seq_first, row_start, row_len, full_len, d_seq_len, d_prompt_len, errflag;
-    size_t splitk, attn_part, attn_ml, lse_part, blocks;
+    size_t splitk, attn_part, attn_ml, lse_part, z_tgt, blocks;
     size_t total;
     int rows, logit_rows, mpps, nqkv, vt_cap, max_blocks;
 };
@@ -95,7 +95,8 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.splitk = take((size_t)kMaxSplitK * 128 * ((c.max_batch + 127) / 128) * maxn * 4);
     L.attn_part = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * c.head_dim * 4);
     L.attn_ml = take((size_t)c.max_batch * c.n_q_heads * kMaxAttnSplits * 2 * 4);
-    L.lse_part = take((size_t)rows * ((c.vocab + 127) / 128) * 2 * 4);
+    L.lse_part = take((size_t)rows * ((c.vocab + 63) / 64) * sizeof(float2));
+    L.z_tgt = take((size_t)rows * 4);
     L.max_blocks = rows / 32 + c.max_batch;
     L.blocks = take((size_t)L.max_blocks * sizeof(int4));
     L.total = off;
@@ -758,6 +759,17 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
                 c->at<int>(L.errflag), s);
         run_layers(c, W, n, false, false, ch.max_ctx, ch.nblocks, s);
         k_rmsnorm(m.dtype, c->at<float>(L.x), W.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
+        if (c->impl == 1) {
+            // LM head with the log-sum-exp and the target gather in its epilogue: no logits in memory
+            GemmArgs g;
+            g.M = n; g.A = c->at<f16_t>(L.h); g.lda = m.d_model; g.W = (const bf16_t*)W.lm_head; g.N = m.vocab;
+            g.K = m.d_model; g.tgt = c->at<int>(L.tok_tgt); g.lse_part = c->at<float2>(L.lse_part);
+            g.z_tgt = c->at<float>(L.z_tgt);
+            mfma(c, RL_K_LMHEAD_SCORE, MG_LSE, g, 1, s);
+            k_lse_reduce(c->at<float2>(L.lse_part), m.vocab / 64, c->at<float>(L.z_tgt), n, c->at<int>(L.tok_tgt),
+                         c->at<int>(L.tok_slot), c->at<int>(L.tok_pos), logp_out, Lmax, s);
+            continue;
+        }
         const size_t e = esz_of(m.dtype);
         for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
             int nr = std::min(L.logit_rows, n - r0);
