@@ -25,12 +25,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // (columns >= G are zero padding).  Per-wave results are merged through LDS; with more
 // than one split the workgroup writes an unnormalised partial (o, m, l) per head.
 template <int HD, int PT>
-__global__ __launch_bounds__(256) void attn_decode_kernel(DecodeAttnArgs a) {
+__global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
     static_assert(PT == 16, "page tile is one 16-row MFMA block");
     constexpr int KS = HD / 32;    // k-steps of the 16x16x32 S^T MFMAs
     constexpr int DB = HD / 16;    // 16-dim blocks of O^T
     __shared__ float sm_m[4][16], sm_l[4][16];
-    __shared__ float sm_o[4][16][HD + 4];
+    __shared__ float sm_o[4][8][HD + 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, g4 = lane >> 4;
     const int b = blockIdx.x, g = blockIdx.y, split = blockIdx.z;
@@ -40,8 +40,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(DecodeAttnArgs a) {
     const int chunk = (npages + (int)gridDim.z - 1) / (int)gridDim.z;
     const int pbeg = split * chunk, pend = min(npages, pbeg + chunk);
     const int* bt = a.block_table + (int64_t)b * a.mpps;
-    const f16_t* kbase = a.pool + a.geo.k_off(a.layer, 0, g, 0, 0);
-    const f16_t* vbase = a.pool + a.geo.v_off(a.layer, 0, g, 0, 0);
+    const f16_t* kbase = a.pool + a.geo.k_off(a.layer, 0, g, 0, 0) + col * HD + g4 * 8;
+    const f16_t* vbase = a.pool + a.geo.v_off(a.layer, 0, g, 0, 0) + col * PT + g4 * 4;
     const int64_t page_stride = a.geo.page_elems();
 
     // Q^T operand: lane (head col, k-group g4) holds q[head][s*32 + g4*8 .. +8)
@@ -57,61 +57,60 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(DecodeAttnArgs a) {
 #pragma unroll
     for (int d = 0; d < DB; ++d) acc[d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int p0 = pbeg + wave * 2; p0 < pend; p0 += 8) {
-        const bool two = p0 + 1 < pend;
-        const int64_t pg0 = bt[p0];
-        const int64_t pg1 = two ? bt[p0 + 1] : pg0;
-        const f16_t* k0 = kbase + pg0 * page_stride + col * HD + g4 * 8;
-        const f16_t* k1 = kbase + pg1 * page_stride + col * HD + g4 * 8;
-        const f16_t* v0 = vbase + pg0 * page_stride + col * PT + g4 * 4;
-        const f16_t* v1 = vbase + pg1 * page_stride + col * PT + g4 * 4;
-        half8 kf0[KS], kf1[KS];
-        half4 vf0[DB], vf1[DB];
+    // One page per iteration; the next page's K and V tiles are requested before the current
+    // page is consumed, so a wave always has a page in flight.
+    half8 kf[KS], kn[KS];
+    half4 vf[DB], vn[DB];
+    int p = pbeg + wave;
+    if (p < pend) {
+        const int64_t pg = bt[p];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            kf0[s] = *reinterpret_cast<const half8*>(k0 + s * 32);
-            kf1[s] = *reinterpret_cast<const half8*>(k1 + s * 32);
-        }
+        for (int s = 0; s < KS; ++s) kn[s] = *reinterpret_cast<const half8*>(kbase + pg * page_stride + s * 32);
 #pragma unroll
-        for (int d = 0; d < DB; ++d) {
-            vf0[d] = *reinterpret_cast<const half4*>(v0 + d * 16 * PT);
-            vf1[d] = *reinterpret_cast<const half4*>(v1 + d * 16 * PT);
-        }
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        for (int d = 0; d < DB; ++d) vn[d] = *reinterpret_cast<const half4*>(vbase + pg * page_stride + d * 16 * PT);
+    }
+    for (; p < pend; p += 4) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf0[s], qf[s], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf1[s], qf[s], s1, 0, 0, 0);
+        for (int s = 0; s < KS; ++s) kf[s] = kn[s];
+#pragma unroll
+        for (int d = 0; d < DB; ++d) vf[d] = vn[d];
+        {
+            const int pn = min(p + 4, pend - 1);          // the last iteration re-reads a valid page, unused
+            const int64_t pg = bt[pn];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kn[s] = *reinterpret_cast<const half8*>(kbase + pg * page_stride + s * 32);
+#pragma unroll
+            for (int d = 0; d < DB; ++d) vn[d] = *reinterpret_cast<const half4*>(vbase + pg * page_stride + d * 16 * PT);
         }
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], qf[s], s0, 0, 0, 0);
         // lane holds keys p*16 + g4*4 + i of head `col`
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int t0 = p0 * PT + g4 * 4 + i;
+            int t0 = p * PT + g4 * 4 + i;
             s0[i] = (t0 < ctx) ? s0[i] * scale : -INFINITY;
-            s1[i] = (two && t0 + PT < ctx) ? s1[i] * scale : -INFINITY;
-            mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
+            mx = fmaxf(mx, s0[i]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, RL_WAVE));
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
-        const float m_new = fmaxf(m_run, mx);       // finite: the first key of page p0 is always valid
+        const float m_new = fmaxf(m_run, mx);       // finite: the first key of page p is always valid
         const float alpha = exp2f(m_run - m_new);
-        half4 pf0, pf1;
+        half4 pf0;
         float ps = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float e0 = exp2f(s0[i] - m_new), e1 = exp2f(s1[i] - m_new);
-            ps += e0 + e1;
+            float e0 = exp2f(s0[i] - m_new);
+            ps += e0;
             pf0[i] = (f16_t)e0;
-            pf1[i] = (f16_t)e1;
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
             acc[d] *= alpha;
-            acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf0[d], pf0, acc[d], 0, 0, 0);
-            acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf1[d], pf1, acc[d], 0, 0, 0);
+            acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf[d], pf0, acc[d], 0, 0, 0);
         }
     }
     // wave totals: l over the four key groups

@@ -429,7 +429,7 @@ static void lm_head_logits(rl_ctx* c, int cls, const WeightsHost& W, const void*
 }
 
 static bool fast_path_supported(const rl_model_cfg& m) {
-    if (m.dtype != RL_BF16 || m.d_model > 8192) return false;
+    if (m.dtype != RL_BF16 || m.d_model > 8192 || m.n_q_heads / m.n_kv_heads > 8) return false;
     const int nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, qd = m.n_q_heads * m.head_dim;
     return k_gemm_mfma_supported(MG_QKV, nqkv, m.d_model, m.head_dim) &&
            k_gemm_mfma_supported(MG_STORE_F32, m.d_model, qd, m.head_dim) &&
