@@ -62,13 +62,15 @@ __device__ __forceinline__ int w_row_of(int r, int nb, const GemmArgs& a) {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-    constexpr int A_CH = BM * 8 / 256, W_CH = BN * 8 / 256;   // 16-byte chunks per thread per k-tile
+    constexpr int LSTR = BKT + 8;   // halfs per LDS row (+16 B pad: conflict-free ds_read_b128)
+    constexpr int CPR = BKT / 8;    // 16-byte chunks per tile row
+    constexpr int A_CH = BM * CPR / 256, W_CH = BN * CPR / 256;   // chunks per thread per k-tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    f16_t* As = reinterpret_cast<f16_t*>(smem);                   // [2][BM][LDS_STRIDE]
-    f16_t* Ws = As + 2 * BM * LDS_STRIDE;                         // [2][BN][LDS_STRIDE]
+    f16_t* As = reinterpret_cast<f16_t*>(smem);                   // [2][BM][LSTR]
+    f16_t* Ws = As + 2 * BM * LSTR;                         // [2][BN][LSTR]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     // Tile order: workgroup ids walk groups of 8 row blocks column by column, so that the tiles in
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     }
     const int m0 = mb * BM;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
-    const int nk = (kend - kbeg + BK - 1) / BK;
+    const int nk = (kend - kbeg + BKT - 1) / BKT;
 
     // per-thread global source rows for the staged loads
     const f16_t* a_src[A_CH];
@@ -93,17 +95,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     int a_dst[A_CH], w_dst[W_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
-        int c = tid + i * 256, r = c >> 3, kc = c & 7;
+        int c = tid + i * 256, r = c / CPR, kc = c % CPR;
         int m = m0 + r;
         a_src[i] = a.A + (int64_t)min(m, a.M - 1) * a.lda + kc * 8;   // rows >= M: any finite-or-not data, never stored
-        a_dst[i] = r * LDS_STRIDE + kc * 8;
+        a_dst[i] = r * LSTR + kc * 8;
     }
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
-        int c = tid + i * 256, r = c >> 3, kc = c & 7;
+        int c = tid + i * 256, r = c / CPR, kc = c % CPR;
         int wr = w_row_of<EPI, BN>(r, nb, a);
         w_src[i] = a.W + (int64_t)min(wr, a.Wrows - 1) * a.K + kc * 8;
-        w_dst[i] = r * LDS_STRIDE + kc * 8;
+        w_dst[i] = r * LSTR + kc * 8;
     }
 
     // Two register sets alternate between k-tiles: a tile is requested at the start of step kt-2's
@@ -115,16 +117,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 #define MG_LOAD(sl, kt)                                                                          \
     {                                                                                            \
         _Pragma("unroll") for (int i_ = 0; i_ < A_CH; ++i_)                                      \
-            ra##sl[i_] = *reinterpret_cast<const u32x4_t*>(a_src[i_] + kbeg + (kt) * BK);        \
+            ra##sl[i_] = *reinterpret_cast<const u32x4_t*>(a_src[i_] + kbeg + (kt) * BKT);        \
         _Pragma("unroll") for (int i_ = 0; i_ < W_CH; ++i_)                                      \
-            rw##sl[i_] = *reinterpret_cast<const u32x4_t*>(w_src[i_] + kbeg + (kt) * BK);        \
+            rw##sl[i_] = *reinterpret_cast<const u32x4_t*>(w_src[i_] + kbeg + (kt) * BKT);        \
     }
 #define MG_PARK(sl, buf)                                                                         \
     {                                                                                            \
         _Pragma("unroll") for (int i_ = 0; i_ < A_CH; ++i_)                                      \
-            *reinterpret_cast<u32x4_t*>(As + (buf) * BM * LDS_STRIDE + a_dst[i_]) = ra##sl[i_];  \
+            *reinterpret_cast<u32x4_t*>(As + (buf) * BM * LSTR + a_dst[i_]) = ra##sl[i_];  \
         _Pragma("unroll") for (int i_ = 0; i_ < W_CH; ++i_)                                      \
-            *reinterpret_cast<half8*>(Ws + (buf) * BN * LDS_STRIDE + w_dst[i_]) = bf16x8_to_half8(rw##sl[i_]); \
+            *reinterpret_cast<half8*>(Ws + (buf) * BN * LSTR + w_dst[i_]) = bf16x8_to_half8(rw##sl[i_]); \
     }
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -136,26 +138,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     const int lrow = lane & 31, lk = (lane >> 5) * 8;
 #define MG_FRAGS(dst_a, dst_b, kk)                                                               \
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                               \
-        dst_a[i] = *reinterpret_cast<const half8*>(Ab + i * 32 * LDS_STRIDE + (kk));             \
+        dst_a[i] = *reinterpret_cast<const half8*>(Ab + i * 32 * LSTR + (kk));             \
     _Pragma("unroll") for (int j = 0; j < TN; ++j)                                               \
-        dst_b[j] = *reinterpret_cast<const half8*>(Wb + j * 32 * LDS_STRIDE + (kk));
+        dst_b[j] = *reinterpret_cast<const half8*>(Wb + j * 32 * LSTR + (kk));
 #define MG_MFMAS(src_a, src_b)                                                                   \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(src_a[i], src_b[j], acc[i][j], 0, 0, 0);
     // fragments of k-slice kk+16 are fetched from LDS while the MFMAs of slice kk run
 #define MG_COMPUTE(buf)                                                                          \
     {                                                                                            \
-        const f16_t* Ab = As + (buf) * BM * LDS_STRIDE + (wm * TM * 32 + lrow) * LDS_STRIDE + lk; \
-        const f16_t* Wb = Ws + (buf) * BN * LDS_STRIDE + (wn * TN * 32 + lrow) * LDS_STRIDE + lk; \
+        const f16_t* Ab = As + (buf) * BM * LSTR + (wm * TM * 32 + lrow) * LSTR + lk;            \
+        const f16_t* Wb = Ws + (buf) * BN * LSTR + (wn * TN * 32 + lrow) * LSTR + lk;            \
         half8 afA[TM], bfA[TN], afB[TM], bfB[TN];                                                \
         MG_FRAGS(afA, bfA, 0)                                                                    \
-        MG_FRAGS(afB, bfB, 16)                                                                   \
-        MG_MFMAS(afA, bfA)                                                                       \
-        MG_FRAGS(afA, bfA, 32)                                                                   \
-        MG_MFMAS(afB, bfB)                                                                       \
-        MG_FRAGS(afB, bfB, 48)                                                                   \
-        MG_MFMAS(afA, bfA)                                                                       \
-        MG_MFMAS(afB, bfB)                                                                       \
+        _Pragma("unroll") for (int kk = 0; kk < BKT; kk += 32) {                                 \
+            MG_FRAGS(afB, bfB, kk + 16)                                                          \
+            MG_MFMAS(afA, bfA)                                                                   \
+            if (kk + 32 < BKT) { MG_FRAGS(afA, bfA, kk + 32) }                                   \
+            MG_MFMAS(afB, bfB)                                                                   \
+        }                                                                                        \
     }
     // step with tile parity p: request tile kt+2 into set p (its previous tile is already parked),
     // consume LDS buffer p, park set 1-p (tile kt+1) into buffer 1-p
@@ -529,19 +530,19 @@ void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s) {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
 static void launch(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
-    constexpr size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(f16_t);
+    constexpr size_t lds = (size_t)2 * (BM + BN) * (BKT + 8) * sizeof(f16_t);
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WGM, WGN, EPI>,
+        (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, BKT>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
     dim3 grid(n_blocks_n * ((a.M + BM - 1) / BM), 1, splits);
-    gemm_mfma_kernel<BM, BN, WGM, WGN, EPI><<<grid, 256, lds, s>>>(b);
+    gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, BKT><<<grid, 256, lds, s>>>(b);
 }
 
 int g_big_tiles = 0;   // 1: 256 x 128 workgroup tiles for large M (measured slower than 128 x 128 at 2 workgroups per CU)
@@ -564,22 +565,22 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     switch (epi) {
         case MG_STORE_F32:
             a.Wrows = a.N;
-            if (big) launch<256, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, 1, s);
+            if (big) launch<128, 128, 2, 2, MG_STORE_F32, 32>(a, a.N / 128, 1, s);
             else launch<128, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, splits, s);
             break;
         case MG_STORE_F16:
             a.Wrows = a.N;
-            if (big) launch<256, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s);
+            if (big) launch<128, 128, 2, 2, MG_STORE_F16, 32>(a, a.N / 128, 1, s);
             else launch<128, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s);
             break;
         case MG_RESID:
             a.Wrows = a.N;
-            if (big) launch<256, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s);
+            if (big) launch<128, 128, 2, 2, MG_RESID, 32>(a, a.N / 128, 1, s);
             else launch<128, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s);
             break;
         case MG_SWIGLU:
             a.Wrows = a.up_offset + a.N;
-            if (big) launch<256, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
+            if (big) launch<128, 128, 2, 2, MG_SWIGLU, 32>(a, a.N / 64, 1, s);
             else launch<128, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
             break;
         case MG_LSE:
@@ -588,7 +589,7 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
             break;
         case MG_QKV:
             a.Wrows = a.N;
-            if (big) launch<256, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
+            if (big) launch<128, 128, 2, 2, MG_QKV, 32>(a, a.N / 128, 1, s);
             else launch<128, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
             break;
         default: break;
