@@ -336,7 +336,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 enum { SG_PARTIAL = 0, SG_SWIGLU = 1 };
 #define SG_BK 64                       // k extent of one team step
-#define SG_STRIDE (SG_BK + 8)           // halfs per LDS row (+16 B pad: conflict-free ds_read_b128)
+#define SG_STRIDE (SG_BK + 16)          // halfs per LDS row: 160 B rows measured conflict-free for the 16x16x32 operand order (144 B is not)
 #define SG_TILE_HALFS (128 * SG_STRIDE)
 #define SG_ACH (SG_BK / 16)             // 16-byte A chunks per thread per step
 #define SG_WLD (SG_BK / 16)             // W loads per wave-lane per step (k32 steps x 2 column tiles)
