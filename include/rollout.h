@@ -165,7 +165,9 @@ const char* rollout_last_error(void);
 
 /* impl 0 = plain reference kernels for every step (any dtype);
  * impl 1 = tuned gfx950 kernels where they exist (bf16 MFMA GEMMs, MFMA
- * attention, fused LM-head log-sum-exp).  Default 1 for bf16, 0 for fp32. */
+ * attention, fused LM-head log-sum-exp).  Default 1 for bf16, 0 for fp32.
+ * impl 2 = impl 1, except that the large-M GEMMs take their 256 x 256-tile kernel for every shape it
+ * supports instead of only where the grid fills the chip (lets small test shapes reach that kernel). */
 int rollout_set_impl(rl_ctx* ctx, int32_t impl);
 
 /* Kernel classes for timing. */

@@ -27,23 +27,27 @@ struct GemmArgs {
     f16_t* pool = nullptr;
     const int* block_table = nullptr;
     int mpps = 0, layer = 0, Hq = 0, Hkv = 0, hd = 0;
-    // MG_LSE (LM head for scoring): per row and per 64-column group the pair (max, sum exp(z - max))
-    // goes to lse_part[row][N/64]; the logit of the row's target token (tgt[row] >= 0) to z_tgt[row].
+    // MG_LSE (LM head for scoring): per row and per column group (k_gemm_mfma_lse_parts groups of equal
+    // width) the pair (max, sum exp(z - max)) goes to lse_part[row][group]; the logit of the row's target token (tgt[row] >= 0) to z_tgt[row].
     // The logits themselves are never stored.
     const int* tgt = nullptr;
     float2* lse_part = nullptr;
     float* z_tgt = nullptr;
     int vt_cap = 0;             // > 0: v_out is dim-major [Hkv][hd][vt_cap tokens]; 0: token-major [M][Hkv][hd]
     KvGeom geo{};
+    // 256 x 256 workgroup tiles (splits == 1 only): 0 never, 1 when the grid fills the chip at one workgroup
+    // per CU, 2 whenever the shape allows (N multiple of 256, K of 128)
+    int big_mode = 1;
 };
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd);
 // splits > 1 only with MG_STORE_F32: partial sums of split s go to outF + s * split_stride.
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
 int k_gemm_mfma_splits_used(int K, int splits);
+// Number of column groups per row that an MG_LSE launch of this shape writes (at most N / 64).
+int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode);
 // Weight-streaming variant for M <= 128 (decode): epi MG_STORE_F32 (split-K partials / plain
 // fp32 store when splits == 1) or MG_SWIGLU.  Same shape requirements as k_gemm_mfma.
 void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s);
 bool k_gemm_stream_supported(int N, int K);       // K multiple of 128, N multiple of 128
 int k_gemm_stream_splits_used(int K, int splits);
-extern int g_big_tiles;

@@ -42,23 +42,162 @@ __device__ __forceinline__ half8 bf16x8_to_half8(u32x4_t w) {
 // Which row of W feeds LDS row r of the B tile of column-block nb.
 //  EPI_SWIGLU: the tile holds BN/2 gate rows and the matching BN/2 up rows, interleaved in
 //              blocks of 32 so that a wave's adjacent 32-column MFMA tiles are (gate, up).
-//  MG_QKV with head_dim 128: the head's halves are interleaved in blocks of 32 so that a
-//              wave holds columns j and j + 64 in the same lane.
+//  MG_QKV with head_dim 128: the halves of each head (128 tile columns) are interleaved in blocks of
+//              32 so that a wave holds columns j and j + 64 in the same lane.
 template <int EPI, int BN>
 __device__ __forceinline__ int w_row_of(int r, int nb, const GemmArgs& a) {
     if (EPI == MG_SWIGLU) {
         int blk = r >> 5, within = r & 31;
         int col = nb * (BN / 2) + (blk >> 1) * 32 + within;
         return (blk & 1) ? a.up_offset + col : col;
-    } else if (EPI == MG_QKV && BN == 128) {
+    } else if (EPI == MG_QKV) {
         if (a.hd == 128) {
-            int blk = r >> 5, within = r & 31;      // LDS blocks: [0:32) [64:96) [32:64) [96:128)
+            int blk = (r & 127) >> 5, within = r & 31;   // per head, LDS blocks: [0:32) [64:96) [32:64) [96:128)
             int src = ((blk & 1) ? 64 : 0) + (blk >> 1) * 32 + within;
-            return nb * BN + src;
+            return nb * BN + (r & ~127) + src;
         }
         return nb * BN + r;
     } else {
         return nb * BN + r;
+    }
+}
+
+// Tile order.  The tile sequence walks bands of 8 row blocks column by column, so that consecutive
+// tiles share few A row blocks and few W column blocks.  Workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2: XCD x takes the contiguous run [x*C, (x+1)*C) of the sequence, so the
+// tiles resident on one XCD at any time form a compact block and re-use their operands from that L2.
+// The grid holds 8*C ids; returns false for the (at most 7) ids past the end.
+__device__ __forceinline__ bool tile_of(int id, int MB, int NB, int& mb, int& nb) {
+    const int T = MB * NB, C = (T + 7) >> 3;
+    const int pos = (id & 7) * C + (id >> 3);
+    if (pos >= T) return false;
+    const int per_group = 8 * NB;
+    const int group = pos / per_group, first = group * 8, gsz = min(MB - first, 8), r = pos % per_group;
+    mb = first + r % gsz;
+    nb = r / gsz;
+    return true;
+}
+
+// Epilogue shared by the tile kernels, for one 32-row band of a wave's accumulators: acc[j][r] of the
+// wave in tile-column position wn is C(row, col) with
+//   row = m_base + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
+template <int EPI, int BN, int TN, int WGN>
+__device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs& a, int m_base, int nb, int wn,
+                                            int ks, int lane) {
+    const int lg = lane >> 5, lrow = lane & 31;
+    {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+            if (m >= a.M) continue;
+            if (EPI == MG_STORE_F32) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
+                    if (n < a.N) a.outF[(int64_t)ks * a.split_stride + (int64_t)m * a.ldc + n] = acc[j][r];
+                }
+            } else if (EPI == MG_STORE_F16) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
+                    if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)acc[j][r];
+                }
+            } else if (EPI == MG_RESID) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
+                    if (n < a.N) a.outF[(int64_t)m * a.ldc + n] += acc[j][r];
+                }
+            } else if (EPI == MG_SWIGLU) {
+#pragma unroll
+                for (int j = 0; j < TN; j += 2) {
+                    int n = nb * (BN / 2) + (wn * TN + j) / 2 * 32 + lrow;
+                    float g = acc[j][r], u = acc[j + 1][r];
+                    if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
+                }
+            } else if (EPI == MG_LSE) {
+                // this wave's TN*32 columns of row m: running (max, sum of exponentials) over the
+                // lanes that share the row (the 32 lanes of a half-wave), and the target's logit
+                float mx = acc[0][r];
+#pragma unroll
+                for (int j = 1; j < TN; ++j) mx = fmaxf(mx, acc[j][r]);
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, RL_WAVE));
+                float se = 0.f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) se += __expf(acc[j][r] - mx);
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) se += __shfl_xor(se, o, RL_WAVE);
+                const int nparts = (a.N / BN) * WGN;
+                if (lrow == 0) a.lse_part[(int64_t)m * nparts + nb * WGN + wn] = make_float2(mx, se);
+                const int t = a.tgt[m];
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (t == nb * BN + wn * TN * 32 + j * 32 + lrow) a.z_tgt[m] = acc[j][r];
+            } else if (EPI == MG_QKV) {
+                // columns of this tile belong to one head (hd 128) or two (hd 64); pairs (j, j + hd/2)
+                // sit in adjacent 32-column MFMA tiles of this lane.
+                // pos < 0 marks a padding row of the packed token list: it gets zeros (so that
+                // nothing non-finite is ever read back as a key or value) and no cache slot
+                const int pos_raw = a.tok_pos[m];
+                const bool pad = pos_raw < 0;
+                const int pos = pad ? 0 : pos_raw;
+                const int hd = a.hd, half = hd >> 1;
+#pragma unroll
+                for (int j = 0; j < TN; j += 2) {
+                    // tile-local LDS column of acc[j]: c0; its partner acc[j+1] is c0 + 32 in LDS order
+                    int c0 = wn * TN * 32 + j * 32 + lrow;
+                    int col0;                             // global qkv column of v0; v1 is col0 + hd/2
+                    if (hd == 128) {
+                        int blk = (c0 & 127) >> 5;        // even LDS block of this head
+                        col0 = nb * BN + (c0 & ~127) + (blk >> 1) * 32 + (c0 & 31);
+                    } else {
+                        col0 = nb * BN + c0;
+                    }
+                    float v0 = pad ? 0.f : acc[j][r], v1 = pad ? 0.f : acc[j + 1][r];
+                    const int head = col0 / hd, jj = col0 % hd;      // jj < half
+                    const int Hq = a.Hq, Hkv = a.Hkv;
+                    if (head < Hq + Hkv) {
+                        float2 cs = a.rope[(int64_t)pos * half + jj];
+                        float r0 = v0 * cs.x - v1 * cs.y, r1 = v1 * cs.x + v0 * cs.y;
+                        v0 = r0; v1 = r1;
+                    }
+                    if (head < Hq) {
+                        f16_t* o = a.q_out + (int64_t)m * Hq * hd + head * hd + jj;
+                        o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                    } else if (head < Hq + Hkv) {
+                        int g = head - Hq;
+                        if (a.k_out) {
+                            f16_t* o = a.k_out + ((int64_t)m * Hkv + g) * hd + jj;
+                            o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                        }
+                        if (a.pool && !pad) {
+                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
+                            int st = pos % a.geo.PT;
+                            a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = (f16_t)v0;
+                            a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
+                        }
+                    } else {
+                        int g = head - Hq - Hkv;
+                        if (a.v_out) {
+                            if (a.vt_cap > 0) {   // dim-major: vT[kv head][dim][token]
+                                a.v_out[((int64_t)g * hd + jj) * a.vt_cap + m] = (f16_t)v0;
+                                a.v_out[((int64_t)g * hd + jj + half) * a.vt_cap + m] = (f16_t)v1;
+                            } else {
+                                f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
+                                o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                            }
+                        }
+                        if (a.pool && !pad) {
+                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
+                            int st = pos % a.geo.PT;
+                            a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = (f16_t)v0;
+                            a.pool[a.geo.v_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
+                        }
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -73,18 +212,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     f16_t* Ws = As + 2 * BM * LSTR;                         // [2][BN][LSTR]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    // Tile order: workgroup ids walk groups of 8 row blocks column by column, so that the tiles in
-    // flight at any time cover a compact region (few distinct A row blocks and W column blocks),
-    // and -- ids being dealt round-robin to the 8 XCDs -- each XCD keeps re-using one A row block
-    // from its own L2.
     const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM, ks = blockIdx.z;
     int nb, mb;
-    {
-        const int id = blockIdx.x, per_group = 8 * NB;
-        const int group = id / per_group, first = group * 8, gsz = min(MB - first, 8), r = id % per_group;
-        mb = first + r % gsz;
-        nb = r / gsz;
-    }
+    if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
     const int m0 = mb * BM;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
     const int nk = (kend - kbeg + BKT - 1) / BKT;
@@ -199,124 +329,150 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 #undef MG_STEP_PARK
 #undef MG_STEP_LAST
 
-    // ---- epilogue.  acc[i][j][r] is C(row, col) with
-    //   row = m0 + wm*TM*32 + i*32 + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
-    const int lg = lane >> 5;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) mg_epilogue<EPI, BN, TN, WGN>(acc[i], a, m0 + wm * TM * 32 + i * 32, nb, wn, ks, lane);
+}
+
+// ------------------------------------------------------------------ large-M GEMM, 256 x 256 tiles
+// One workgroup of four waves per CU; each wave owns a 128 x 128 block of C (16 accumulator tiles, 256
+// registers), so one k-slice of 16 costs 8 LDS fragment reads for 16 MFMAs -- half the LDS traffic per
+// flop of the 128 x 128 kernel, which is bound by it.
+//  * Operands are staged by global -> LDS loads (no registers in between) into four stages of 32 k each;
+//    rows are 64 B and the 16-byte chunks of a row are XOR-swizzled with (row >> 2) & 3 -- on the
+//    source side of the load -- so that the fragment reads are bank-conflict free without padding.
+//    W stays bf16 in LDS and is converted to fp16 in registers after the fragment read.
+//  * The staging loads are issued from inline assembly: the compiler's wait-count pass would otherwise
+//    force every one of them to complete at each barrier.  vmcnt is therefore managed by hand -- a
+//    tile's loads are issued three k-tiles ahead, and every step waits until at most the two youngest
+//    tiles (16 loads per wave) are in flight.  The loop issues the same number of loads on every trip
+//    (the last trips re-request the final tile), so the counts hold to the end; vmcnt(0) before the
+//    epilogue makes sure no load can land in LDS after the workgroup has ended.
+//  * The instruction order inside a k-slice is fixed with scheduling fences: one MFMA, then one unit of
+//    the next slice's preparation (a fragment read, half a fragment's conversion, a staging load).
+//  * One barrier per k-tile: after it, every wave has read its last fragments of the tile's stage, which
+//    can then be refilled, and the next tile is complete in LDS.
+// Requires K % 128 == 0 and operand byte offsets below 4 GiB (checked by the launcher).
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmArgs a) {
+    constexpr int BM = 256, BN = 256;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A 16 KB | W 16 KB]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM;
+    int nb, mb;
+    if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
+    const int m0 = mb * BM;
+    const int nk = a.K / 32;
+    // Staging: instruction t of wave w fills LDS bytes [(t*4 + w) KB, +1 KB) of the A (or W) part of a
+    // stage = tile rows (t*4+w)*16 .. +16; lane -> row + lane/4, physical chunk lane%4, which holds the
+    // row's logical chunk (lane%4) ^ ((row>>2)&3).
+    unsigned a_off[4], w_off[4];
+    {
+        const int lc = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-            if (m >= a.M) continue;
-            if (EPI == MG_STORE_F32) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
-                    if (n < a.N) a.outF[(int64_t)ks * a.split_stride + (int64_t)m * a.ldc + n] = acc[i][j][r];
-                }
-            } else if (EPI == MG_STORE_F16) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
-                    if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)acc[i][j][r];
-                }
-            } else if (EPI == MG_RESID) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
-                    if (n < a.N) a.outF[(int64_t)m * a.ldc + n] += acc[i][j][r];
-                }
-            } else if (EPI == MG_SWIGLU) {
-#pragma unroll
-                for (int j = 0; j < TN; j += 2) {
-                    int n = nb * (BN / 2) + (wn * TN + j) / 2 * 32 + lrow;
-                    float g = acc[i][j][r], u = acc[i][j + 1][r];
-                    if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
-                }
-            } else if (EPI == MG_LSE) {
-                // this wave's TN*32 columns of row m: running (max, sum of exponentials) over the
-                // lanes that share the row (the 32 lanes of a half-wave), and the target's logit
-                float mx = acc[i][0][r];
-#pragma unroll
-                for (int j = 1; j < TN; ++j) mx = fmaxf(mx, acc[i][j][r]);
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, RL_WAVE));
-                float se = 0.f;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) se += __expf(acc[i][j][r] - mx);
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) se += __shfl_xor(se, o, RL_WAVE);
-                const int nparts = (a.N / BN) * WGN;
-                if (lrow == 0) a.lse_part[(int64_t)m * nparts + nb * WGN + wn] = make_float2(mx, se);
-                const int t = a.tgt[m];
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    if (t == nb * BN + wn * TN * 32 + j * 32 + lrow) a.z_tgt[m] = acc[i][j][r];
-            } else if (EPI == MG_QKV) {
-                // columns of this tile belong to one head (hd 128) or two (hd 64); pairs (j, j + hd/2)
-                // sit in adjacent 32-column MFMA tiles of this lane.
-                // pos < 0 marks a padding row of the packed token list: it gets zeros (so that
-                // nothing non-finite is ever read back as a key or value) and no cache slot
-                const int pos_raw = a.tok_pos[m];
-                const bool pad = pos_raw < 0;
-                const int pos = pad ? 0 : pos_raw;
-                const int hd = a.hd, half = hd >> 1;
-#pragma unroll
-                for (int j = 0; j < TN; j += 2) {
-                    // tile-local LDS column of acc[i][j]: c0; its partner acc[i][j+1] is c0 + 32 in LDS order
-                    int c0 = wn * TN * 32 + j * 32 + lrow;
-                    int col0;                             // global qkv column of v0; v1 is col0 + hd/2
-                    if (hd == 128) {
-                        int blk = c0 >> 5;                // even LDS block
-                        col0 = nb * BN + (blk >> 1) * 32 + (c0 & 31);
-                    } else {
-                        col0 = nb * BN + c0;
-                    }
-                    float v0 = pad ? 0.f : acc[i][j][r], v1 = pad ? 0.f : acc[i][j + 1][r];
-                    const int head = col0 / hd, jj = col0 % hd;      // jj < half
-                    const int Hq = a.Hq, Hkv = a.Hkv;
-                    if (head < Hq + Hkv) {
-                        float2 cs = a.rope[(int64_t)pos * half + jj];
-                        float r0 = v0 * cs.x - v1 * cs.y, r1 = v1 * cs.x + v0 * cs.y;
-                        v0 = r0; v1 = r1;
-                    }
-                    if (head < Hq) {
-                        f16_t* o = a.q_out + (int64_t)m * Hq * hd + head * hd + jj;
-                        o[0] = (f16_t)v0; o[half] = (f16_t)v1;
-                    } else if (head < Hq + Hkv) {
-                        int g = head - Hq;
-                        if (a.k_out) {
-                            f16_t* o = a.k_out + ((int64_t)m * Hkv + g) * hd + jj;
-                            o[0] = (f16_t)v0; o[half] = (f16_t)v1;
-                        }
-                        if (a.pool && !pad) {
-                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
-                            int st = pos % a.geo.PT;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = (f16_t)v0;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
-                        }
-                    } else {
-                        int g = head - Hq - Hkv;
-                        if (a.v_out) {
-                            if (a.vt_cap > 0) {   // dim-major: vT[kv head][dim][token]
-                                a.v_out[((int64_t)g * hd + jj) * a.vt_cap + m] = (f16_t)v0;
-                                a.v_out[((int64_t)g * hd + jj + half) * a.vt_cap + m] = (f16_t)v1;
-                            } else {
-                                f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
-                                o[0] = (f16_t)v0; o[half] = (f16_t)v1;
-                            }
-                        }
-                        if (a.pool && !pad) {
-                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
-                            int st = pos % a.geo.PT;
-                            a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = (f16_t)v0;
-                            a.pool[a.geo.v_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
-                        }
-                    }
-                }
-            }
+        for (int t = 0; t < 4; ++t) {
+            const int r = (t * 4 + wave) * 16 + (lane >> 2);
+            a_off[t] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
+            w_off[t] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u;
         }
     }
+    const char* Ag = reinterpret_cast<const char*>(a.A);
+    const char* Wg = reinterpret_cast<const char*>(a.W);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+#define BG_LOAD(stage, kt, q)                                                                                   \
+    {                                                                                                           \
+        const unsigned sa_ = lds_base + (stage) * 32768 + wave * 1024 + ((q) & 3) * 4096 + ((q) >> 2) * 16384;  \
+        const char* g_ = ((q) < 4 ? Ag : Wg) + (size_t)(kt) * 64;                                               \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
+                     :: "s"(sa_), "v"((q) < 4 ? a_off[(q) & 3] : w_off[(q) & 3]), "s"(g_) : "memory");          \
+    }
+    // fragment addresses: row lane%32 of a 32-row block, logical chunk ks*2 + lane/32, swizzled
+    int fa[2][2], fw[2][2];   // [stage pair][k-slice]
+#pragma unroll
+    for (int hp = 0; hp < 2; ++hp)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int ko = ((ks * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
+            fa[hp][ks] = hp * 65536 + (wm * 128 + (lane & 31)) * 64 + ko;
+            fw[hp][ks] = hp * 65536 + 16384 + (wn * 128 + (lane & 31)) * 64 + ko;
+        }
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    half8 af[2][4];
+    u32x4_t bf[2][4], bw[4];
+#define BG_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
+#define BG_LDA(stage, ks, i) *reinterpret_cast<const half8*>(smem + fa[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (i) * 2048)
+#define BG_LDW(stage, ks, j) *reinterpret_cast<const u32x4_t*>(smem + fw[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (j) * 2048)
+    // One k-slice: 16 MFMAs on fragment set CUR; between them, in this order, the 4 W and 4 A fragment
+    // reads of slice (NSTAGE, NKS) into the other set, the conversion of those W fragments, and four
+    // staging loads (requests HALF*4 .. +4 of tile DKT into stage DSTAGE).
+#define BG_SLICE(CUR, NSTAGE, NKS, HALF, DSTAGE, DKT)                                                           \
+    _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                                            \
+        const int j_ = q >> 2, i_ = q & 3;                                                                      \
+        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
+        if (q < 4) bw[q & 3] = BG_LDW(NSTAGE, NKS, q & 3);                                                      \
+        else if (q < 8) af[1 - (CUR)][q & 3] = BG_LDA(NSTAGE, NKS, q & 3);                                      \
+        else {                                                                                                  \
+            const int jj_ = (q - 8) >> 1, h_ = ((q - 8) & 1) * 2;                                               \
+            bf[1 - (CUR)][jj_][h_] = BG_CVT2(bw[jj_][h_]);                                                      \
+            bf[1 - (CUR)][jj_][h_ + 1] = BG_CVT2(bw[jj_][h_ + 1]);                                              \
+        }                                                                                                       \
+        if ((q & 3) == 1) BG_LOAD(DSTAGE, DKT, (HALF) * 4 + (q >> 2))                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                                      \
+    }
+    // k-tile kt sits in stage S = kt % 4.  Its first slice also issues the second half of the requests
+    // for tile kt+3; after the barrier its stage is free and takes the first half of tile kt+4.
+#define BG_STEP(S, KT)                                                                                          \
+    {                                                                                                           \
+        { const int dkt_ = min((KT) + 3, nk - 1);                                                               \
+          BG_SLICE(0, S, 1, 1, ((S) + 3) & 3, dkt_) }                                                           \
+        __builtin_amdgcn_s_waitcnt(0x4070);   /* vmcnt(16) lgkmcnt(0): own part of tile kt+1 landed */         \
+        __syncthreads();                                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                      \
+        { const int dkt_ = min((KT) + 4, nk - 1);                                                               \
+          BG_SLICE(1, ((S) + 1) & 3, 0, 0, S, dkt_) }                                                           \
+    }
+    // prologue: tiles 0..2 and the first half of tile 3
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        const int kt_ = min(st, nk - 1);
+#pragma unroll
+        for (int q = 0; q < (st < 3 ? 8 : 4); ++q) BG_LOAD(st, kt_, q)
+    }
+    __builtin_amdgcn_s_waitcnt(0x4F74);   // vmcnt(20): tile 0 landed
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[0][i] = BG_LDA(0, 0, i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        bw[j] = BG_LDW(0, 0, j);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bf[0][j][c] = BG_CVT2(bw[j][c]);
+    }
+    for (int kt = 0; kt < nk; kt += 4) {   // nk % 4 == 0
+        BG_STEP(0, kt)
+        BG_STEP(1, kt + 1)
+        BG_STEP(2, kt + 2)
+        BG_STEP(3, kt + 3)
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): nothing may land in LDS after the workgroup ends
+#undef BG_LOAD
+#undef BG_CVT2
+#undef BG_LDA
+#undef BG_LDW
+#undef BG_SLICE
+#undef BG_STEP
+    // written out: with the largest epilogue the unroller gives up on a loop over the four bands
+    mg_epilogue<EPI, BN, 4, 2>(acc[0], a, m0 + wm * 128, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, 4, 2>(acc[1], a, m0 + wm * 128 + 32, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, 4, 2>(acc[2], a, m0 + wm * 128 + 64, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, 4, 2>(acc[3], a, m0 + wm * 128 + 96, nb, wn, 0, lane);
 }
 
 // ------------------------------------------------------------------ weight-streaming GEMM (decode, M <= 128)
@@ -541,17 +697,45 @@ static void launch(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s)
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
-    dim3 grid(n_blocks_n * ((a.M + BM - 1) / BM), 1, splits);
+    dim3 grid(8 * ((n_blocks_n * ((a.M + BM - 1) / BM) + 7) / 8), 1, splits);
     gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, BKT><<<grid, 256, lds, s>>>(b);
 }
 
-int g_big_tiles = 0;   // 1: 256 x 128 workgroup tiles for large M (measured slower than 128 x 128 at 2 workgroups per CU)
+template <int EPI>
+static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
+    constexpr int lds = 4 * 32768;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)gemm_big_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    GemmArgs b = a;
+    b.n_blocks_n = n_blocks_n;
+    dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8));
+    gemm_big_kernel<EPI><<<grid, 256, lds, s>>>(b);
+}
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
     if (K % BK != 0) return false;
     if (epi == MG_SWIGLU) return N % 64 == 0;
     if (epi == MG_QKV) return N % 128 == 0 && (hd == 64 || hd == 128);
     return N % 128 == 0;
+}
+
+// Whether the 256 x 256 kernel takes this GEMM (a.Wrows filled in).
+static bool use_big(int epi, const GemmArgs& a, int splits) {
+    if (!a.big_mode || splits != 1) return false;
+    const int out_cols = epi == MG_SWIGLU ? 2 * a.N : a.N;   // tile columns
+    if (out_cols % 256 != 0 || a.K % 128 != 0) return false;
+    if ((uint64_t)a.M * a.lda * 2 >= (1ull << 32) || (uint64_t)a.Wrows * a.K * 2 >= (1ull << 32)) return false;
+    const int64_t tiles = (int64_t)((a.M + 255) / 256) * (out_cols / 256);
+    return a.big_mode >= 2 || tiles >= 512;   // one workgroup per CU: at least two rounds of 256
+}
+
+int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
+    GemmArgs a;
+    a.M = M; a.N = N; a.K = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
+    return use_big(MG_LSE, a, 1) ? N / 128 : N / 64;
 }
 
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
@@ -561,35 +745,31 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     int per = (kt + splits - 1) / splits;
     a.k_per_split = per * BK;
     splits = (kt + per - 1) / per;
-    const bool big = a.M >= 1024 && splits == 1 && g_big_tiles;
+    a.Wrows = epi == MG_SWIGLU ? a.up_offset + a.N : a.N;
+    const bool big = use_big(epi, a, splits);
     switch (epi) {
         case MG_STORE_F32:
-            a.Wrows = a.N;
-            if (big) launch<128, 128, 2, 2, MG_STORE_F32, 32>(a, a.N / 128, 1, s);
+            if (big) launch_big<MG_STORE_F32>(a, a.N / 256, s);
             else launch<128, 128, 2, 2, MG_STORE_F32>(a, a.N / 128, splits, s);
             break;
         case MG_STORE_F16:
-            a.Wrows = a.N;
-            if (big) launch<128, 128, 2, 2, MG_STORE_F16, 32>(a, a.N / 128, 1, s);
+            if (big) launch_big<MG_STORE_F16>(a, a.N / 256, s);
             else launch<128, 128, 2, 2, MG_STORE_F16>(a, a.N / 128, 1, s);
             break;
         case MG_RESID:
-            a.Wrows = a.N;
-            if (big) launch<128, 128, 2, 2, MG_RESID, 32>(a, a.N / 128, 1, s);
+            if (big) launch_big<MG_RESID>(a, a.N / 256, s);
             else launch<128, 128, 2, 2, MG_RESID>(a, a.N / 128, 1, s);
             break;
         case MG_SWIGLU:
-            a.Wrows = a.up_offset + a.N;
-            if (big) launch<128, 128, 2, 2, MG_SWIGLU, 32>(a, a.N / 64, 1, s);
+            if (big) launch_big<MG_SWIGLU>(a, a.N / 128, s);
             else launch<128, 128, 2, 2, MG_SWIGLU>(a, a.N / 64, 1, s);
             break;
         case MG_LSE:
-            a.Wrows = a.N;
-            launch<128, 128, 2, 2, MG_LSE>(a, a.N / 128, 1, s);
+            if (big) launch_big<MG_LSE>(a, a.N / 256, s);
+            else launch<128, 128, 2, 2, MG_LSE>(a, a.N / 128, 1, s);
             break;
         case MG_QKV:
-            a.Wrows = a.N;
-            if (big) launch<128, 128, 2, 2, MG_QKV, 32>(a, a.N / 128, 1, s);
+            if (big) launch_big<MG_QKV>(a, a.N / 256, s);
             else launch<128, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
             break;
         default: break;

@@ -158,6 +158,7 @@ struct rl_ctx {
     WeightsHost policy;
     KvGeom geo;
     int impl = 0;
+    int big_mode = 1;                // GemmArgs::big_mode of every tuned GEMM
     // sequences
     int B = 0;                       // live sequences (0 = no prefill yet)
     std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len)
@@ -316,8 +317,10 @@ static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged,
     return false;
 }
 
-static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a, int splits, hipStream_t s) {
+static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a0, int splits, hipStream_t s) {
     ProfScope ps(c, cls, s);
+    GemmArgs a = a0;
+    a.big_mode = c->big_mode;
     if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU) &&
         k_gemm_stream_supported(a.N, a.K))
         k_gemm_stream(epi, a, splits, s);
@@ -576,10 +579,11 @@ int rollout_reset(rl_ctx* c) {
 
 int rollout_set_impl(rl_ctx* c, int32_t impl) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
-    if (impl != 0 && impl != 1) return fail(RL_EINVAL, "impl must be 0 or 1");
-    if (impl == 1 && !fast_path_supported(c->cfg))
-        return fail(RL_EINVAL, "impl 1 needs bf16 weights and GEMM widths that are multiples of 128 (K of 64)");
-    c->impl = impl;
+    if (impl < 0 || impl > 2) return fail(RL_EINVAL, "impl must be 0, 1 or 2");
+    if (impl >= 1 && !fast_path_supported(c->cfg))
+        return fail(RL_EINVAL, "impl 1 / 2 need bf16 weights and GEMM widths that are multiples of 128 (K of 64)");
+    c->impl = impl >= 1 ? 1 : 0;
+    c->big_mode = impl == 2 ? 2 : 1;
     return RL_OK;
 }
 
@@ -766,7 +770,7 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
             g.K = m.d_model; g.tgt = c->at<int>(L.tok_tgt); g.lse_part = c->at<float2>(L.lse_part);
             g.z_tgt = c->at<float>(L.z_tgt);
             mfma(c, RL_K_LMHEAD_SCORE, MG_LSE, g, 1, s);
-            k_lse_reduce(c->at<float2>(L.lse_part), m.vocab / 64, c->at<float>(L.z_tgt), n, c->at<int>(L.tok_tgt),
+            k_lse_reduce(c->at<float2>(L.lse_part), k_gemm_mfma_lse_parts(n, m.vocab, m.d_model, c->big_mode), c->at<float>(L.z_tgt), n, c->at<int>(L.tok_tgt),
                          c->at<int>(L.tok_slot), c->at<int>(L.tok_pos), logp_out, Lmax, s);
             continue;
         }

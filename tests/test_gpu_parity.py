@@ -244,6 +244,33 @@ def test_tuned_and_plain_kernels_agree(shape):
     ro.close()
 
 
+@pytest.mark.parametrize("shape", [MINI64, MINI128], ids=lambda s: s.name)
+def test_big_tile_gemm_kernel_against_oracle(shape):
+    """impl 2 sends every large-M GEMM (QKV with RoPE and cache write, output and down projections,
+    SwiGLU, scoring LM head with fused log-sum-exp) through the 256 x 256-tile kernel, which the
+    benchmark shapes reach by size alone.  Here: ragged scoring over two row blocks with a partial
+    second one, and a prefill whose cache the decode steps then read."""
+    B, G = 6, 6
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 80, chunk=512)
+    ro.rollout_set_impl(2)
+    seqs, slens, plens = synth.make_sequences(shape.vocab, B, 72, 40, 0.4, 91)
+    assert int(slens.sum()) > 256                          # second row block in use
+    got = _score(ro, Wp, Wr, seqs, slens, plens, 0.25)
+    errs = check_scores(*got, O.score_batch(mp, mr, seqs, slens, plens, 0.25), 2e-2, 0.25)
+    print(shape.name, "impl 2 scoring errs", errs)
+    ids, lens = synth.make_prompts(shape.vocab, B, 70, 45, 92)
+    g_ids, g_len, g_lp = _generate(ro, ids, lens, G, 1.0, seed=11)
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    st = verify_rollout(mp, prompts, g_ids, g_lp, 1.0, 11, 0, 1e-3, 2e-2)
+    assert st["n_checked"] == B * G
+    # the two tile kernels agree closely on the same inputs
+    ro.rollout_set_impl(1)
+    ref = _score(ro, Wp, Wr, seqs, slens, plens, 0.25)
+    for a, b in zip(got, ref):
+        assert np.abs(a - b).max() < 5e-3
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
