@@ -85,6 +85,30 @@ template <int EPI, int BN, int TN, int WGN>
 __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs& a, int m_base, int nb, int wn,
                                             int ks, int lane) {
     const int lg = lane >> 5, lrow = lane & 31;
+    if (EPI == MG_RESID) {
+        // read-modify-write of the fp32 residual stream: all of the band's loads are issued before the
+        // first add (rows past M read row M-1 instead of branching, so nothing separates the loads)
+        float old[TN][16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = min(m_base + 8 * (r >> 2) + 4 * lg + (r & 3), a.M - 1);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                old[j][r] = a.outF[(int64_t)m * a.ldc + min(nb * BN + wn * TN * 32 + j * 32 + lrow, a.N - 1)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+            if (m >= a.M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
+                if (n < a.N) a.outF[(int64_t)m * a.ldc + n] = old[j][r] + acc[j][r];
+            }
+        }
+        return;
+    }
     {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -101,12 +125,6 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 for (int j = 0; j < TN; ++j) {
                     int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
                     if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)acc[j][r];
-                }
-            } else if (EPI == MG_RESID) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    int n = nb * BN + wn * TN * 32 + j * 32 + lrow;
-                    if (n < a.N) a.outF[(int64_t)m * a.ldc + n] += acc[j][r];
                 }
             } else if (EPI == MG_SWIGLU) {
 #pragma unroll
@@ -410,8 +428,9 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmArgs a) {
 #define BG_LDA(stage, ks, i) *reinterpret_cast<const half8*>(smem + fa[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (i) * 2048)
 #define BG_LDW(stage, ks, j) *reinterpret_cast<const u32x4_t*>(smem + fw[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (j) * 2048)
     // One k-slice: 16 MFMAs on fragment set CUR; between them, in this order, the 4 W and 4 A fragment
-    // reads of slice (NSTAGE, NKS) into the other set, the conversion of those W fragments, and four
-    // staging loads (requests HALF*4 .. +4 of tile DKT into stage DSTAGE).
+    // reads of slice (NSTAGE, NKS) into the other set, then the conversion of those W fragments; four
+    // staging loads (requests HALF*4 .. +4 of tile DKT into stage DSTAGE) share slots with the fragment
+    // reads, which keeps every slot within the eight issue cycles one MFMA covers.
 #define BG_SLICE(CUR, NSTAGE, NKS, HALF, DSTAGE, DKT)                                                           \
     _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                                            \
         const int j_ = q >> 2, i_ = q & 3;                                                                      \
@@ -423,7 +442,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmArgs a) {
             bf[1 - (CUR)][jj_][h_] = BG_CVT2(bw[jj_][h_]);                                                      \
             bf[1 - (CUR)][jj_][h_ + 1] = BG_CVT2(bw[jj_][h_ + 1]);                                              \
         }                                                                                                       \
-        if ((q & 3) == 1) BG_LOAD(DSTAGE, DKT, (HALF) * 4 + (q >> 2))                                           \
+        if (q < 8 && (q & 1)) BG_LOAD(DSTAGE, DKT, (HALF) * 4 + (q >> 1))                                           \
         __builtin_amdgcn_sched_barrier(0);                                                                      \
     }
     // k-tile kt sits in stage S = kt % 4.  Its first slice also issues the second half of the requests
