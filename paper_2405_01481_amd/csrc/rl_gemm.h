@@ -46,8 +46,8 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
 int k_gemm_mfma_splits_used(int K, int splits);
 // Number of column groups per row that an MG_LSE launch of this shape writes (at most N / 64).
 int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode);
-// Weight-streaming variant for M <= 128 (decode): epi MG_STORE_F32 (split-K partials / plain
-// fp32 store when splits == 1) or MG_SWIGLU.  Same shape requirements as k_gemm_mfma.
-void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s);
-bool k_gemm_stream_supported(int N, int K);       // K multiple of 128, N multiple of 128
-int k_gemm_stream_splits_used(int K, int splits);
+// Decode GEMM (M <= 128, lda * 2 * 128 below 4 GiB) on 128-column tiles with LDS operand rings: epi MG_STORE_F32 (split-K partials to
+// outF + split * split_stride; plain store when one split) or MG_SWIGLU (never split).
+bool k_gemm_decode_supported(int epi, int N, int K);   // K and tile columns multiples of 128
+int k_gemm_decode_splits_used(int K, int splits);
+void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s);

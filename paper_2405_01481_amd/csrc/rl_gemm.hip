@@ -1,14 +1,17 @@
 // MFMA GEMMs for gfx950:  C[M,N] = A[M,K] (fp16, row-major) * W[N,K]^T (bf16, row-major).
 //
-// Weights stay bf16 in HBM and are converted to fp16 while they are staged into LDS (exact
-// for every weight of normal fp16 magnitude); the contraction runs on
-// v_mfma_f32_32x32x16_f16 with fp32 accumulation.  One kernel template serves
-//   * the large-M GEMMs of prefill / scoring (grid over M and N tiles), and
-//   * the weight-streaming GEMMs of a decode step (M <= 128 rows, split over K so that all
-//     256 CUs stream a slice of W; partial sums go to a [split][M][N] fp32 buffer and are
-//     reduced, in a fixed order, by the consumer kernel).
-// Epilogues: fp32 store / split-K partial, fp16 store, residual add, SwiGLU, and
-// RoPE + q/k/v split for the QKV projection.
+// Weights stay bf16 in HBM and are converted to fp16 on their way to the MFMA operand registers
+// (exact for every weight of normal fp16 magnitude); the contraction runs on
+// v_mfma_f32_32x32x16_f16 with fp32 accumulation.  Three kernels share one set of epilogues:
+//   * gemm_mfma_kernel: 128 x 128 tiles staged through registers, two workgroups per CU -- small and
+//     medium M, and split-K for decode batches above 128 rows;
+//   * gemm_dma_kernel:  256 x 256 tiles staged by global -> LDS loads -- the large-M GEMMs of prefill
+//     and scoring once the grid fills the chip;
+//   * gemm_ring_kernel: the weight-streaming GEMMs of a decode step (M <= 128 rows), split over K so
+//     that all 256 CUs stream a slice of W; partial sums go to a [split][M][N] fp32 buffer and are
+//     reduced, in a fixed order, by the consumer kernel.
+// Epilogues: fp32 store / split-K partial, fp16 store, residual add, SwiGLU, RoPE + q/k/v split for
+// the QKV projection, and log-sum-exp + target gather for the scoring LM head.
 #include "rl_common.h"
 #include "rl_gemm.h"
 
@@ -351,358 +354,288 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < TM; ++i) mg_epilogue<EPI, BN, TN, WGN>(acc[i], a, m0 + wm * TM * 32 + i * 32, nb, wn, ks, lane);
 }
 
-// ------------------------------------------------------------------ large-M GEMM, 256 x 256 tiles
-// One workgroup of four waves per CU; each wave owns a 128 x 128 block of C (16 accumulator tiles, 256
-// registers), so one k-slice of 16 costs 8 LDS fragment reads for 16 MFMAs -- half the LDS traffic per
-// flop of the 128 x 128 kernel, which is bound by it.
-//  * Operands are staged by global -> LDS loads (no registers in between) into four stages of 32 k each;
-//    rows are 64 B and the 16-byte chunks of a row are XOR-swizzled with (row >> 2) & 3 -- on the
-//    source side of the load -- so that the fragment reads are bank-conflict free without padding.
-//    W stays bf16 in LDS and is converted to fp16 in registers after the fragment read.
+// ------------------------------------------------------------------ tile GEMM with global -> LDS staging
+// Four waves (WGM x WGN) per workgroup, tile BM x BN, k-tile 32, four LDS stages.
+// Used as 256 x 256 (2 x 2 waves of 128 x 128, one workgroup per CU) for the large-M GEMMs: 16
+// accumulator tiles per wave, so one k-slice of 16 costs 8 LDS fragment reads for 16 MFMAs -- half the
+// LDS traffic per flop of the 128 x 128 register-staged kernel above, which is bound by it.  (Split over
+// K works too -- blockIdx.z, partial sums to outF + split * split_stride -- but is not used.)
+//  * Operands are staged by global -> LDS loads (no registers in between); rows are 64 B and the 16-byte
+//    chunks of a row are XOR-swizzled with (row >> 2) & 3 -- on the source side of the load -- so that
+//    the fragment reads are bank-conflict free without padding.  W stays bf16 in LDS and is converted
+//    to fp16 in registers after the fragment read.
 //  * The staging loads are issued from inline assembly: the compiler's wait-count pass would otherwise
 //    force every one of them to complete at each barrier.  vmcnt is therefore managed by hand -- a
 //    tile's loads are issued three k-tiles ahead, and every step waits until at most the two youngest
-//    tiles (16 loads per wave) are in flight.  The loop issues the same number of loads on every trip
-//    (the last trips re-request the final tile), so the counts hold to the end; vmcnt(0) before the
-//    epilogue makes sure no load can land in LDS after the workgroup has ended.
-//  * The instruction order inside a k-slice is fixed with scheduling fences: one MFMA, then one unit of
-//    the next slice's preparation (a fragment read, half a fragment's conversion, a staging load).
+//    tiles are in flight.  The loop issues the same number of loads on every trip (the last trips
+//    re-request the final tile), so the counts hold to the end; vmcnt(0) before the epilogue makes
+//    sure no load can land in LDS after the workgroup has ended.  Loads the compiler adds (none in the
+//    loop) could only make these waits stricter: completion is in order.
+//  * The instruction order inside a k-slice is fixed with scheduling fences: one MFMA, then a unit of
+//    the next slice's preparation (fragment reads and staging loads in the first half of the slice, the
+//    conversion of the W fragments in the second).
 //  * One barrier per k-tile: after it, every wave has read its last fragments of the tile's stage, which
 //    can then be refilled, and the next tile is complete in LDS.
-// Requires K % 128 == 0 and operand byte offsets below 4 GiB (checked by the launcher).
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmArgs a) {
-    constexpr int BM = 256, BN = 256;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A 16 KB | W 16 KB]
+// Requires (k extent per split) % 128 == 0 and operand byte offsets below 4 GiB (checked by the launcher).
+constexpr int dma_waitcnt(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
+
+template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
+__global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
+    constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+    constexpr int SLOTS = TM * TN, HS = SLOTS / 2;   // MFMAs per k-slice; slots of its first half
+    constexpr int STAGE = (BM + BN) * 64;            // bytes per stage: A rows then W rows, 64 B each
+    constexpr int LPT = (BM + BN) / 64;              // staging loads per wave per k-tile
+    constexpr int L1 = LPT / 2;                      // loads [0, L1) go out one step later than [L1, LPT)
+    constexpr int RPS = (TN + TM) / HS, CPS = 2 * TN / HS;   // fragment reads / conversion halves per slot
+    static_assert(WGM * WGN == 4 && SLOTS % 2 == 0 && (TN + TM) % HS == 0 && (2 * TN) % HS == 0, "tile shape");
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "whole 16-row blocks per wave and operand");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A BM x 64 B | W BN x 64 B]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM, ks = blockIdx.z;
     int nb, mb;
     if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
     const int m0 = mb * BM;
-    const int nk = a.K / 32;
-    // Staging: instruction t of wave w fills LDS bytes [(t*4 + w) KB, +1 KB) of the A (or W) part of a
-    // stage = tile rows (t*4+w)*16 .. +16; lane -> row + lane/4, physical chunk lane%4, which holds the
-    // row's logical chunk (lane%4) ^ ((row>>2)&3).
-    unsigned a_off[4], w_off[4];
+    const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
+    const int nk = (kend - kbeg) / 32;               // multiple of 4
+    // Staging: load l of wave w fills the 1 KB block l*4 + w of a stage = 16 rows of A (l < BM/64) or W;
+    // lane -> row + lane/4, physical chunk lane%4, which holds the row's logical chunk (lane%4) ^ ((row>>2)&3).
+    unsigned g_off[LPT];
     {
         const int lc = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int r = (t * 4 + wave) * 16 + (lane >> 2);
-            a_off[t] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
-            w_off[t] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u;
+        for (int l = 0; l < LPT; ++l) {
+            if (l < BM / 64) {
+                const int r = (l * 4 + wave) * 16 + (lane >> 2);
+                g_off[l] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
+            } else {
+                const int r = ((l - BM / 64) * 4 + wave) * 16 + (lane >> 2);
+                g_off[l] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u;
+            }
         }
     }
-    const char* Ag = reinterpret_cast<const char*>(a.A);
-    const char* Wg = reinterpret_cast<const char*>(a.W);
+    const char* Ag = reinterpret_cast<const char*>(a.A + kbeg);
+    const char* Wg = reinterpret_cast<const char*>(a.W + kbeg);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-#define BG_LOAD(stage, kt, q)                                                                                   \
+#define DG_LOAD(stage, kt, l)                                                                                   \
     {                                                                                                           \
-        const unsigned sa_ = lds_base + (stage) * 32768 + wave * 1024 + ((q) & 3) * 4096 + ((q) >> 2) * 16384;  \
-        const char* g_ = ((q) < 4 ? Ag : Wg) + (size_t)(kt) * 64;                                               \
+        const unsigned sa_ = lds_base + (stage) * STAGE + ((l) * 4 + wave) * 1024;                              \
+        const char* g_ = ((l) < BM / 64 ? Ag : Wg) + (size_t)(kt) * 64;                                         \
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
-                     :: "s"(sa_), "v"((q) < 4 ? a_off[(q) & 3] : w_off[(q) & 3]), "s"(g_) : "memory");          \
+                     :: "s"(sa_), "v"(g_off[l]), "s"(g_) : "memory");                                           \
     }
     // fragment addresses: row lane%32 of a 32-row block, logical chunk ks*2 + lane/32, swizzled
     int fa[2][2], fw[2][2];   // [stage pair][k-slice]
 #pragma unroll
     for (int hp = 0; hp < 2; ++hp)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int ko = ((ks * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
-            fa[hp][ks] = hp * 65536 + (wm * 128 + (lane & 31)) * 64 + ko;
-            fw[hp][ks] = hp * 65536 + 16384 + (wn * 128 + (lane & 31)) * 64 + ko;
+        for (int sl = 0; sl < 2; ++sl) {
+            const int ko = ((sl * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
+            fa[hp][sl] = hp * 2 * STAGE + (wm * TM * 32 + (lane & 31)) * 64 + ko;
+            fw[hp][sl] = hp * 2 * STAGE + BM * 64 + (wn * TN * 32 + (lane & 31)) * 64 + ko;
         }
-    floatx16 acc[4][4];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    half8 af[2][4];
-    u32x4_t bf[2][4], bw[4];
-#define BG_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
-#define BG_LDA(stage, ks, i) *reinterpret_cast<const half8*>(smem + fa[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (i) * 2048)
-#define BG_LDW(stage, ks, j) *reinterpret_cast<const u32x4_t*>(smem + fw[(stage) >> 1][ks] + ((stage) & 1) * 32768 + (j) * 2048)
-    // One k-slice: 16 MFMAs on fragment set CUR; between them, in this order, the 4 W and 4 A fragment
-    // reads of slice (NSTAGE, NKS) into the other set, then the conversion of those W fragments; four
-    // staging loads (requests HALF*4 .. +4 of tile DKT into stage DSTAGE) share slots with the fragment
-    // reads, which keeps every slot within the eight issue cycles one MFMA covers.
-#define BG_SLICE(CUR, NSTAGE, NKS, HALF, DSTAGE, DKT)                                                           \
-    _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                                            \
-        const int j_ = q >> 2, i_ = q & 3;                                                                      \
+    half8 af[2][TM];
+    u32x4_t bf[2][TN], bw[TN];
+#define DG_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
+#define DG_LDA(stage, sl, i) *reinterpret_cast<const half8*>(smem + fa[(stage) >> 1][sl] + ((stage) & 1) * STAGE + (i) * 2048)
+#define DG_LDW(stage, sl, j) *reinterpret_cast<const u32x4_t*>(smem + fw[(stage) >> 1][sl] + ((stage) & 1) * STAGE + (j) * 2048)
+    // One k-slice: SLOTS MFMAs on fragment set CUR.  After each MFMA of the first half: RPS fragment reads
+    // of slice (NSTAGE, NSL) into the other set (W fragments first) and the staging loads [LB, LE) of
+    // tile DKT into stage DSTAGE (spread over the slots); after each MFMA of the second half: CPS
+    // half-fragment conversions of those W fragments.
+#define DG_SLICE(CUR, NSTAGE, NSL, LB, LE, DSTAGE, DKT)                                                         \
+    _Pragma("unroll") for (int q = 0; q < SLOTS; ++q) {                                                         \
+        const int j_ = q / TM, i_ = q % TM;                                                                     \
         acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
-        if (q < 4) bw[q & 3] = BG_LDW(NSTAGE, NKS, q & 3);                                                      \
-        else if (q < 8) af[1 - (CUR)][q & 3] = BG_LDA(NSTAGE, NKS, q & 3);                                      \
-        else {                                                                                                  \
-            const int jj_ = (q - 8) >> 1, h_ = ((q - 8) & 1) * 2;                                               \
-            bf[1 - (CUR)][jj_][h_] = BG_CVT2(bw[jj_][h_]);                                                      \
-            bf[1 - (CUR)][jj_][h_ + 1] = BG_CVT2(bw[jj_][h_ + 1]);                                              \
+        if (q < HS) {                                                                                           \
+            _Pragma("unroll") for (int u_ = 0; u_ < RPS; ++u_) {                                                \
+                const int f_ = q * RPS + u_;                                                                    \
+                if (f_ < TN) bw[f_ < TN ? f_ : 0] = DG_LDW(NSTAGE, NSL, f_);                                    \
+                else af[1 - (CUR)][f_ >= TN ? f_ - TN : 0] = DG_LDA(NSTAGE, NSL, f_ - TN);                      \
+            }                                                                                                   \
+            _Pragma("unroll") for (int l_ = (LB); l_ < (LE); ++l_) {                                            \
+                const int slot_ = HS >= 2 * ((LE) - (LB)) ? 2 * (l_ - (LB)) + 1 : (l_ - (LB)) % HS;             \
+                if (slot_ == q) DG_LOAD(DSTAGE, DKT, l_)                                                        \
+            }                                                                                                   \
+        } else {                                                                                                \
+            _Pragma("unroll") for (int u_ = 0; u_ < CPS; ++u_) {                                                \
+                const int c_ = (q - HS) * CPS + u_, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                           \
+                bf[1 - (CUR)][jj_][h_] = DG_CVT2(bw[jj_][h_]);                                                  \
+                bf[1 - (CUR)][jj_][h_ + 1] = DG_CVT2(bw[jj_][h_ + 1]);                                          \
+            }                                                                                                   \
         }                                                                                                       \
-        if (q < 8 && (q & 1)) BG_LOAD(DSTAGE, DKT, (HALF) * 4 + (q >> 1))                                           \
         __builtin_amdgcn_sched_barrier(0);                                                                      \
     }
-    // k-tile kt sits in stage S = kt % 4.  Its first slice also issues the second half of the requests
-    // for tile kt+3; after the barrier its stage is free and takes the first half of tile kt+4.
-#define BG_STEP(S, KT)                                                                                          \
+    // k-tile kt sits in stage S = kt % 4.  Its first slice also issues the later part of the requests
+    // for tile kt+3; after the barrier its stage is free and takes the first part of tile kt+4.
+#define DG_STEP(S, KT)                                                                                          \
     {                                                                                                           \
         { const int dkt_ = min((KT) + 3, nk - 1);                                                               \
-          BG_SLICE(0, S, 1, 1, ((S) + 3) & 3, dkt_) }                                                           \
-        __builtin_amdgcn_s_waitcnt(0x4070);   /* vmcnt(16) lgkmcnt(0): own part of tile kt+1 landed */         \
+          DG_SLICE(0, S, 1, L1, LPT, ((S) + 3) & 3, dkt_) }                                                     \
+        __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT, 0));   /* own part of tile kt+1 landed, own reads done */ \
         __syncthreads();                                                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                      \
         { const int dkt_ = min((KT) + 4, nk - 1);                                                               \
-          BG_SLICE(1, ((S) + 1) & 3, 0, 0, S, dkt_) }                                                           \
+          DG_SLICE(1, ((S) + 1) & 3, 0, 0, L1, S, dkt_) }                                                       \
     }
-    // prologue: tiles 0..2 and the first half of tile 3
+    // prologue: tiles 0..2 and the first part of tile 3
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
         const int kt_ = min(st, nk - 1);
 #pragma unroll
-        for (int q = 0; q < (st < 3 ? 8 : 4); ++q) BG_LOAD(st, kt_, q)
+        for (int l = 0; l < (st < 3 ? LPT : L1); ++l) DG_LOAD(st, kt_, l)
     }
-    __builtin_amdgcn_s_waitcnt(0x4F74);   // vmcnt(20): tile 0 landed
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT + L1, 15));   // tile 0 landed
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) af[0][i] = BG_LDA(0, 0, i);
+    for (int i = 0; i < TM; ++i) af[0][i] = DG_LDA(0, 0, i);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        bw[j] = BG_LDW(0, 0, j);
+    for (int j = 0; j < TN; ++j) {
+        bw[j] = DG_LDW(0, 0, j);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bf[0][j][c] = BG_CVT2(bw[j][c]);
+        for (int c = 0; c < 4; ++c) bf[0][j][c] = DG_CVT2(bw[j][c]);
     }
     for (int kt = 0; kt < nk; kt += 4) {   // nk % 4 == 0
-        BG_STEP(0, kt)
-        BG_STEP(1, kt + 1)
-        BG_STEP(2, kt + 2)
-        BG_STEP(3, kt + 3)
+        DG_STEP(0, kt)
+        DG_STEP(1, kt + 1)
+        DG_STEP(2, kt + 2)
+        DG_STEP(3, kt + 3)
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): nothing may land in LDS after the workgroup ends
-#undef BG_LOAD
-#undef BG_CVT2
-#undef BG_LDA
-#undef BG_LDW
-#undef BG_SLICE
-#undef BG_STEP
-    // written out: with the largest epilogue the unroller gives up on a loop over the four bands
-    mg_epilogue<EPI, BN, 4, 2>(acc[0], a, m0 + wm * 128, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, 4, 2>(acc[1], a, m0 + wm * 128 + 32, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, 4, 2>(acc[2], a, m0 + wm * 128 + 64, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, 4, 2>(acc[3], a, m0 + wm * 128 + 96, nb, wn, 0, lane);
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after the workgroup ends
+#undef DG_LOAD
+#undef DG_CVT2
+#undef DG_LDA
+#undef DG_LDW
+#undef DG_SLICE
+#undef DG_STEP
+    // written out: with the largest epilogue the unroller gives up on a loop over the bands
+    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, ks, lane);
+    if (TM > 1) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, ks, lane);
+    if (TM > 2) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 2 ? 2 : 0], a, m0 + wm * TM * 32 + 64, nb, wn, ks, lane);
+    if (TM > 3) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 3 ? 3 : 0], a, m0 + wm * TM * 32 + 96, nb, wn, ks, lane);
 }
 
-// ------------------------------------------------------------------ weight-streaming GEMM (decode, M <= 128)
-// One workgroup = 128 rows x 128 columns of C over one K slice, computed by two teams of
-// four waves: team t takes the k-tiles t, t+2, t+4, ... of the slice (a split over K inside
-// the workgroup, reduced through LDS at the end), so every SIMD hosts two waves that hide
-// each other's LDS / MFMA-issue latencies.  Inside a team the four waves split the columns
-// (32 each, two 16-wide MFMA tiles) and each wave reads ITS OWN rows of W straight from
-// global memory in B-operand layout (every row contributes 64 contiguous bytes per load
-// instruction), one k-tile ahead of the one being consumed; W never touches LDS.  The
-// activations (shared by a team's waves, and L2-resident) are staged through LDS.
-// v_mfma_f32_16x16x32_f16, fp32 accumulation.
-//   SG_PARTIAL: outF[ks][m][n] = partial sum of K slice ks
-//   SG_SWIGLU : a wave's two column tiles are (gate, up) rows of W for the same 16 outputs;
-//               the workgroup covers 64 outputs; outH[m][n] = silu(gate) * up
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-enum { SG_PARTIAL = 0, SG_SWIGLU = 1 };
-#define SG_BK 64                       // k extent of one team step
-#define SG_STRIDE (SG_BK + 16)          // halfs per LDS row: 160 B rows measured conflict-free for the 16x16x32 operand order (144 B is not)
-#define SG_TILE_HALFS (128 * SG_STRIDE)
-#define SG_ACH (SG_BK / 16)             // 16-byte A chunks per thread per step
-#define SG_WLD (SG_BK / 16)             // W loads per wave-lane per step (k32 steps x 2 column tiles)
-
-template <int EPI>
-__global__ __launch_bounds__(512) void gemm_stream_kernel(GemmArgs a) {
-    // [team][buffer][128 rows x LDS_STRIDE]; reused as a 128 x 128 fp32 tile for the team reduction
-    __shared__ __attribute__((aligned(16))) f16_t As[2 * 2 * SG_TILE_HALFS];
-    const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6, team = threadIdx.x >> 8;
-    const int c16 = lane & 15, g4 = lane >> 4;
-    const int nb = blockIdx.x, ks = blockIdx.y;
+// ------------------------------------------------------------------ decode GEMM (M <= 128), LDS rings
+// HBM-bound: C[128, 128 columns] per workgroup over one K slice (blockIdx.z; partial sums go to
+// outF + split * split_stride and are reduced by the consumer).  What counts is how many bytes of W a CU
+// keeps in flight, so the operands are staged by global -> LDS loads into two rings of 16 KB stages
+// (k-tile 64: rows of 128 B, whole cache lines per row and request): five stages of W, which comes from
+// HBM, and three of A, which every workgroup re-reads from L2.  Loads complete in issue order per wave,
+// so the two depths need separate issuers: waves 0-3 request only W (four tiles ahead), waves 4-7 only A
+// (two tiles ahead); each waits on its own vmcnt (by hand: the loads are issued from inline assembly so
+// that the compiler does not force them to complete at every barrier), and the barrier that follows
+// publishes the tile to all eight waves, which share the MFMA work (WGM x WGN waves of 32x32x16 tiles).
+// The same number of loads is issued on every trip (the last trips re-request the final tile), so the
+// wait counts hold to the end; vmcnt(0) before the epilogue keeps loads from landing in LDS after the
+// workgroup has ended.  16-byte chunks of a row are XOR-swizzled with (row >> 1) & 7 on the source side
+// of the loads: fragment reads are bank-conflict free without padding.
+template <int EPI, int WGM, int WGN>
+__global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
+    constexpr int BN = 128, DW = 5, DA = 3, ST = 16384;
+    constexpr int TM = 128 / WGM / 32, TN = BN / WGN / 32;
+    static_assert(WGM * WGN == 8, "eight waves");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [DW][W 128 x 128 B] [DA][A 128 x 128 B]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool isW = wave < 4;
+    const int w4 = wave & 3, wm = wave / WGN, wn = wave % WGN;
+    const int ks = blockIdx.z;
+    int nb, mb;
+    if (!tile_of(blockIdx.x, 1, a.n_blocks_n, mb, nb)) return;
     const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
-    // team steps of the slice: (kend - kbeg) / SG_BK, an even number (the launcher guarantees it);
-    // this team's steps start at kbeg + team * SG_BK and are 2 * SG_BK apart
-    const int nk = (kend - kbeg) / (2 * SG_BK);
-    const int k0 = kbeg + team * SG_BK;
-    constexpr int KS = 2 * SG_BK;
-    f16_t* As0 = As + team * 2 * SG_TILE_HALFS;
-    f16_t* As1 = As0 + SG_TILE_HALFS;
-
-    // this lane's two W rows
-    const bf16_t* wp[2];
+    const int nk = (kend - kbeg) / 64;
+    // Staging: instruction t of issuer wave w4 fills the 1 KB block t*4 + w4 of a stage = rows (t*4+w4)*8 .. +8;
+    // lane -> row + lane/8, physical chunk lane%8, which holds the row's logical chunk (lane%8) ^ ((row>>1)&7).
+    unsigned g_off[4];
+    {
+        const int lc = (lane & 7) ^ (((w4 & 1) * 4 + (lane >> 4)) & 7);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        int row;
-        if (EPI == SG_SWIGLU) row = (j ? a.up_offset : 0) + nb * 64 + wave * 16 + c16;
-        else row = nb * 128 + wave * 32 + j * 16 + c16;
-        wp[j] = a.W + (int64_t)row * a.K + k0 + g4 * 8;
+        for (int t = 0; t < 4; ++t) {
+            const int r = (t * 4 + w4) * 8 + (lane >> 3);
+            g_off[t] = isW ? ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u
+                           : ((unsigned)min(r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
+        }
     }
-    // A staging: 4 chunks of 16 B per thread per k-tile.  Rows >= M are read from row M-1: a row
-    // of C depends on the same row of A only, and rows >= M are never stored.
-    const f16_t* a_src[SG_ACH];
-    int a_dst[SG_ACH];
-#pragma unroll
-    for (int i = 0; i < SG_ACH; ++i) {
-        int c = tid + i * 256, r = c / (SG_BK / 8), kc = c % (SG_BK / 8);
-        a_src[i] = a.A + (int64_t)min(r, a.M - 1) * a.lda + k0 + kc * 8;
-        a_dst[i] = r * SG_STRIDE + kc * 8;
+    const char* gbase = isW ? reinterpret_cast<const char*>(a.W + kbeg) : reinterpret_cast<const char*>(a.A + kbeg);
+    const int depth = isW ? DW : DA;
+    const unsigned ring = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem + (isW ? 0 : DW * ST) + w4 * 1024;
+#define RG_ISSUE(stage, kt)                                                                                     \
+    {                                                                                                           \
+        const char* g_ = gbase + (size_t)(kt) * 128;                                                            \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                         \
+            const unsigned sa_ = ring + (stage) * ST + t * 4096;                                                \
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                        \
+                         :: "s"(sa_), "v"(g_off[t]), "s"(g_) : "memory");                                       \
+        }                                                                                                       \
     }
-    u32x4 ra[SG_ACH];               // the A tile in flight (requested after the previous one was parked in LDS)
-    u32x4 wq0[SG_WLD], wq1[SG_WLD]; // W tiles in flight, index = k32 step * 2 + column tile
-    floatx4 acc[8][2];
+    // fragment addresses (stage 0): row lane%32 of a 32-row block, logical chunk slice*2 + lane/32, swizzled
+    int fa[4], fw[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-#define SG_WLOAD(ptr, kt) (*reinterpret_cast<const u32x4*>(ptr))
-#define SG_LOAD_A(kt)                                                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < SG_ACH; ++i_)                                        \
-        ra[i_] = *reinterpret_cast<const u32x4*>(a_src[i_] + (kt) * KS);
-#define SG_LOAD_W(sl, kt)                                                                        \
-    _Pragma("unroll") for (int s_ = 0; s_ < SG_BK / 32; ++s_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
-        wq##sl[s_ * 2 + j_] = SG_WLOAD(wp[j_] + (kt) * KS + s_ * 32, kt);
-#define SG_CONVERT(sl)                                                                           \
-    _Pragma("unroll") for (int q_ = 0; q_ < SG_WLD; ++q_) cf[q_] = bf16x8_to_half8(wq##sl[q_]);
-#define SG_STORE_A(sl)                                                                           \
-    _Pragma("unroll") for (int i_ = 0; i_ < SG_ACH; ++i_) *reinterpret_cast<u32x4*>(&As##sl[a_dst[i_]]) = ra[i_];
-#define SG_COMPUTE(sl)                                                                           \
-    _Pragma("unroll") for (int s_ = 0; s_ < SG_BK / 32; ++s_) {                                  \
-        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                       \
-            half8 af_ = *reinterpret_cast<const half8*>(                                         \
-                &As##sl[(i_ * 16 + c16) * SG_STRIDE + s_ * 32 + g4 * 8]);                        \
-            acc[i_][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, cf[s_ * 2 + 0], acc[i_][0], 0, 0, 0); \
-            acc[i_][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_, cf[s_ * 2 + 1], acc[i_][1], 0, 0, 0); \
-        }                                                                                        \
+    for (int sl = 0; sl < 4; ++sl) {
+        const int ko = ((sl * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 16;
+        fa[sl] = DW * ST + (wm * TM * 32 + (lane & 31)) * 128 + ko;
+        fw[sl] = (wn * TN * 32 + (lane & 31)) * 128 + ko;
     }
-    // Step kt (slot = kt & 1): convert W tile kt to fp16, which frees its raw registers for the
-    // request of W tile kt+2 -- two full steps before it is needed; consume; park A tile kt+1 in
-    // the other LDS buffer and request A tile kt+2.
-#define SG_STEP_FULL(sl, other, kt)  { SG_CONVERT(sl) SG_LOAD_W(sl, (kt) + 2) __builtin_amdgcn_sched_barrier(0); SG_COMPUTE(sl) SG_STORE_A(other) SG_LOAD_A((kt) + 2) __syncthreads(); }
-#define SG_STEP_NOLOAD(sl, other)    { SG_CONVERT(sl) SG_COMPUTE(sl) SG_STORE_A(other) __syncthreads(); }
-#define SG_STEP_LAST(sl)             { SG_CONVERT(sl) SG_COMPUTE(sl) }
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // The steady-state path has no conditional loads anywhere between its first request and its
-    // last wait: with vector loads returning in order, a wait count is exact only when every path
-    // to it has issued the same requests.  Short K slices take a separate, simpler path.
-    half8 cf[SG_WLD];
-    if (nk >= 4) {
-        SG_LOAD_A(0)
-        SG_LOAD_W(0, 0)
-        SG_STORE_A(0)
-        SG_LOAD_A(1)
-        SG_LOAD_W(1, 1)
+    for (int st = 0; st < depth - 1; ++st) RG_ISSUE(st, min(st, nk - 1))
+    int fill = depth - 1, a_st = 0, w_st = 0;   // stage to refill next; stages holding tile kt
+    for (int kt = 0; kt < nk; ++kt) {
+        // tile kt landed: a W issuer may still have tiles kt+1 .. kt+3 in flight, an A issuer tile kt+1
+        if (isW) __builtin_amdgcn_s_waitcnt(dma_waitcnt(4 * (DW - 2), 0));
+        else __builtin_amdgcn_s_waitcnt(dma_waitcnt(4 * (DA - 2), 0));
         __syncthreads();
-        int kt = 0;
-        for (; kt + 3 < nk; kt += 2) {
-            SG_STEP_FULL(0, 1, kt)
-            SG_STEP_FULL(1, 0, kt + 1)
+        // every wave is done with tile kt-1: its stage takes tile kt + depth - 1
+        RG_ISSUE(fill, min(kt + depth - 1, nk - 1))
+        fill = fill + 1 == depth ? 0 : fill + 1;
+        // k-slices of 16: the fragments of slice sl+1 are requested before slice sl is converted and multiplied
+        half8 af[2][TM];
+        u32x4_t bw[2][TN];
+        const int ao = a_st * ST, wo = w_st * ST;
+#define RG_READ(set, sl)                                                                                        \
+        {                                                                                                       \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                      \
+                bw[set][j] = *reinterpret_cast<const u32x4_t*>(smem + fw[sl] + wo + j * 4096);                  \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                      \
+                af[set][i] = *reinterpret_cast<const half8*>(smem + fa[sl] + ao + i * 4096);                    \
         }
-        if (nk - kt == 3) {
-            SG_STEP_FULL(0, 1, kt)
-            SG_STEP_NOLOAD(1, 0)
-            SG_STEP_LAST(0)
-        } else {
-            SG_STEP_NOLOAD(0, 1)
-            SG_STEP_LAST(1)
+        RG_READ(0, 0)
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            if (sl < 3) RG_READ((sl + 1) & 1, sl + 1)
+            __builtin_amdgcn_sched_barrier(0);
+            half8 bf[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = bf16x8_to_half8(bw[sl & 1][j]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[sl & 1][i], bf[j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-    } else {
-        for (int kt = 0; kt < nk; ++kt) {
-            SG_LOAD_A(kt)
-            SG_LOAD_W(0, kt)
-            SG_STORE_A(0)
-            __syncthreads();
-            SG_CONVERT(0)
-            SG_COMPUTE(0)
-            __syncthreads();
-        }
+#undef RG_READ
+        a_st = a_st + 1 == DA ? 0 : a_st + 1;
+        w_st = w_st + 1 == DW ? 0 : w_st + 1;
     }
-#undef SG_COMPUTE
-#undef SG_STEP_FULL
-#undef SG_STEP_NOLOAD
-#undef SG_STEP_LAST
-#undef SG_LOAD_A
-#undef SG_LOAD_W
-#undef SG_CONVERT
-#undef SG_STORE_A
-
-    // team reduction: team 1 parks its accumulators in LDS as a 128 x 128 fp32 tile (row m,
-    // tile-local column), team 0 adds them to its own, in this fixed order
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(As);
-    if (team == 1) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    red[(i * 16 + g4 * 4 + r) * 128 + wave * 32 + j * 16 + c16] = acc[i][j][r];
-    }
-    __syncthreads();
-    if (team == 1) return;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[i][j][r] += red[(i * 16 + g4 * 4 + r) * 128 + wave * 32 + j * 16 + c16];
-
-    // epilogue: acc[i][j][r] = C(row i*16 + g4*4 + r, column tile j, col c16)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int m = i * 16 + g4 * 4 + r;
-            if (m >= a.M) continue;
-            if (EPI == SG_PARTIAL) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    int n = nb * 128 + wave * 32 + j * 16 + c16;
-                    a.outF[(int64_t)ks * a.split_stride + (int64_t)m * a.ldc + n] = acc[i][j][r];
-                }
-            } else {
-                int n = nb * 64 + wave * 16 + c16;
-                float g = acc[i][0][r], u = acc[i][1][r];
-                a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
-            }
-        }
-    }
-}
-
-// K slices hold an even number of team steps (two teams per workgroup).
-static void stream_split(GemmArgs& a, int& splits) {
-    if (splits < 1) splits = 1;
-    int kt2 = a.K / (2 * SG_BK);                  // pairs of team steps
-    int per = (kt2 + splits - 1) / splits;
-    a.k_per_split = per * 2 * SG_BK;
-    splits = (kt2 + per - 1) / per;
-}
-
-bool k_gemm_stream_supported(int N, int K) { return K % (2 * SG_BK) == 0 && N % 128 == 0; }
-
-int k_gemm_stream_splits_used(int K, int splits) {
-    GemmArgs a;
-    a.K = K;
-    stream_split(a, splits);
-    return splits;
-}
-
-void k_gemm_stream(int epi, GemmArgs a, int splits, hipStream_t s) {
-    if (a.M <= 0 || a.N <= 0) return;
-    stream_split(a, splits);
-    if (epi == MG_SWIGLU) {
-        dim3 grid(a.N / 64, 1);
-        gemm_stream_kernel<SG_SWIGLU><<<grid, 512, 0, s>>>(a);
-    } else {
-        dim3 grid(a.N / 128, splits);
-        gemm_stream_kernel<SG_PARTIAL><<<grid, 512, 0, s>>>(a);
-    }
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after the workgroup ends
+#undef RG_ISSUE
+    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, wm * TM * 32, nb, wn, ks, lane);
+    if (TM > 1) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 1 ? 1 : 0], a, wm * TM * 32 + 32, nb, wn, ks, lane);
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
@@ -720,18 +653,25 @@ static void launch(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s)
     gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, BKT><<<grid, 256, lds, s>>>(b);
 }
 
-template <int EPI>
-static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
-    constexpr int lds = 4 * 32768;
+template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
+static void launch_dma(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
+    constexpr int lds = 4 * (BM + BN) * 64;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_big_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute((const void*)gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
-    dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8));
-    gemm_big_kernel<EPI><<<grid, 256, lds, s>>>(b);
+    dim3 grid(8 * ((n_blocks_n * ((a.M + BM - 1) / BM) + 7) / 8), 1, splits);
+    gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG><<<grid, 256, lds, s>>>(b);
+}
+template <int EPI>
+static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
+    GemmArgs b = a;
+    b.k_per_split = a.K;
+    launch_dma<EPI, 256, 256, 2, 2, 1>(b, n_blocks_n, 1, s);
 }
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
@@ -793,6 +733,47 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
             break;
         default: break;
     }
+}
+
+// ---- decode (M <= 128): ring kernel on 128-column tiles, split over K in units of 128
+bool k_gemm_decode_supported(int epi, int N, int K) {
+    if (epi != MG_STORE_F32 && epi != MG_SWIGLU) return false;
+    const int cols = epi == MG_SWIGLU ? 2 * N : N;
+    return K % 128 == 0 && cols % 128 == 0 && (uint64_t)cols * K * 2 < (1ull << 32);
+}
+
+int k_gemm_decode_splits_used(int K, int splits) {
+    const int units = K / 128;
+    if (splits < 1) splits = 1;
+    const int per = (units + splits - 1) / splits;
+    return (units + per - 1) / per;
+}
+
+template <int EPI, int WGM, int WGN>
+static void launch_ring(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
+    constexpr int lds = 8 * 16384;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)gemm_ring_kernel<EPI, WGM, WGN>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    GemmArgs b = a;
+    b.n_blocks_n = n_blocks_n;
+    dim3 grid(8 * ((n_blocks_n + 7) / 8), 1, splits);
+    gemm_ring_kernel<EPI, WGM, WGN><<<grid, 512, lds, s>>>(b);
+}
+
+void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0 || a.M > 128) return;
+    if (epi == MG_SWIGLU) splits = 1;
+    const int units = a.K / 128;
+    if (splits < 1) splits = 1;
+    const int per = (units + splits - 1) / splits;
+    a.k_per_split = per * 128;
+    splits = (units + per - 1) / per;
+    a.Wrows = epi == MG_SWIGLU ? a.up_offset + a.N : a.N;
+    if (epi == MG_SWIGLU) launch_ring<MG_SWIGLU, 4, 2>(a, a.N / 64, 1, s);   // gate / up pairs: two column tiles per wave
+    else launch_ring<MG_STORE_F32, 2, 4>(a, a.N / 128, splits, s);
 }
 
 int k_gemm_mfma_splits_used(int K, int splits) {

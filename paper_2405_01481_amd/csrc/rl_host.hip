@@ -322,18 +322,20 @@ static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a0, int splits, hi
     GemmArgs a = a0;
     a.big_mode = c->big_mode;
     if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU) &&
-        k_gemm_stream_supported(a.N, a.K))
-        k_gemm_stream(epi, a, splits, s);
+        k_gemm_decode_supported(epi, a.N, a.K))
+        k_gemm_decode(epi, a, splits, s);
     else
         k_gemm_mfma(epi, a, splits, s);
 }
 
-// Split count for a weight-streaming GEMM with n_tiles column tiles: the streaming kernel keeps
-// one 8-wave workgroup per CU, so aim for as many workgroups as fit in one round of 256 CUs.
-static int decode_splits(int n_tiles, int K) {
-    int want = std::max(1, 256 / std::max(1, n_tiles));
+// Split count for a decode GEMM of n rows with N output columns: one 8-wave workgroup per CU and 128-column
+// tiles, so aim for as many workgroups as fit in one round of 256 CUs.  Returns the number of partial
+// buffers the kernel that mfma() picks for this shape will actually write.
+static int decode_splits(int n, int N, int K) {
+    int want = std::max(1, 256 / std::max(1, N / 128));
     want = std::min(want, kMaxSplitK);
-    return k_gemm_stream_splits_used(K, want);
+    if (n <= 128 && k_gemm_decode_supported(MG_STORE_F32, N, K)) return k_gemm_decode_splits_used(K, want);
+    return k_gemm_mfma_splits_used(K, want);
 }
 
 // bf16 weights / fp16 activations on the MFMA kernels.
@@ -363,7 +365,7 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             // weight-streaming GEMMs, split over K; consumers reduce the partial sums
             g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
             g.outF = part; g.ldc = L.nqkv; g.split_stride = (int64_t)n * L.nqkv;
-            int sp = decode_splits(L.nqkv / 128, m.d_model);
+            int sp = decode_splits(n, L.nqkv, m.d_model);
             mfma(c, gcls, MG_STORE_F32, g, sp, s);
             k_rope_append_split(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
                                 m.n_q_heads, s);
@@ -371,7 +373,7 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             g = GemmArgs();
             g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
-            sp = decode_splits(m.d_model / 128, qd);
+            sp = decode_splits(n, m.d_model, qd);
             mfma(c, gcls, MG_STORE_F32, g, sp, s);
             k_resid_norm(1, x, part, sp, g.split_stride, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
             g = GemmArgs();
@@ -381,7 +383,7 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             g = GemmArgs();
             g.M = n; g.A = ffn; g.lda = m.d_ffn; g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model; g.K = m.d_ffn;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
-            sp = decode_splits(m.d_model / 128, m.d_ffn);
+            sp = decode_splits(n, m.d_model, m.d_ffn);
             mfma(c, gcls, MG_STORE_F32, g, sp, s);
             const void* next = (l + 1 < m.n_layers) ? W.attn_norm[l + 1] : W.final_norm;
             k_resid_norm(1, x, part, sp, g.split_stride, next, h, n, m.d_model, m.rms_eps, s);
