@@ -77,7 +77,14 @@ typedef struct rl_weights {
     const void* const* ffn_norm;    /* [d_model] */
     const void* const* w_gate_up;   /* [2 d_ffn, d_model]: gate rows then up rows */
     const void* const* w_down;      /* [d_model, d_ffn] */
-    int32_t location;               /* 0 = device resident.  Other values are rejected (RL_EINVAL). */
+    int32_t location;               /* 0 = device resident.
+                                       1 = every tensor pointer above (globals and the entries of the per-layer
+                                       arrays) is HOST memory -- pinned (hipHostMalloc) if the transfers are to
+                                       overlap with compute -- and the set is streamed through `staging`.
+                                       Accepted by score_logprobs_kl only; rollout_init wants location 0. */
+    void* staging;                  /* location 1: dev buffer of rollout_weight_staging_bytes(cfg) bytes, 256-byte
+                                       aligned, scratch for the duration of the call.  Ignored for location 0. */
+    size_t staging_bytes;
 } rl_weights;
 
 typedef struct rl_sample_cfg {
@@ -92,6 +99,9 @@ typedef struct rl_sample_cfg {
  * (0 if cfg is NULL or invalid). */
 size_t rollout_workspace_bytes(const rl_model_cfg* cfg);
 size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg);
+/* Bytes of rl_weights.staging for a host-resident weight set (location 1): two layers of weights, one
+ * [vocab, d_model] table and the fp32 residual stream of max_batch sequences of max_seq tokens. */
+size_t rollout_weight_staging_bytes(const rl_model_cfg* cfg);
 
 /* Create a context that generates with `policy` (Section 3.2: the engine keeps
  * weights, KV cache and activations resident).  workspace and kv_pool are dev
@@ -144,7 +154,10 @@ int rollout_generate(rl_ctx* ctx, const rl_sample_cfg* sample,
  * min(Lmax, max_seq), 0 <= prompt_len[b] <= L_b.  Outputs: dev fp32 [B, Lmax],
  * any may be NULL.  reference may be NULL (policy pass only; logp_ref, kl and
  * kl_penalty must then be NULL).  Does not touch the KV cache of live sequences.
- * Errors: RL_EINVAL. */
+ * Either weight set may be host-resident (location 1: "reference weights streamed layer by layer"): its
+ * layers are copied into the set's staging buffer on a stream of the library's own, two layers deep,
+ * while the previous layer runs on `stream` for all tokens; results are identical to the resident case.
+ * Errors: RL_EINVAL, RL_ENOSPACE (staging buffer too small). */
 int score_logprobs_kl(rl_ctx* ctx, const rl_weights* policy, const rl_weights* reference,
                       const int32_t* ids, const int32_t* seq_len, const int32_t* prompt_len,
                       int32_t B, int32_t Lmax, float kl_coef,

@@ -124,11 +124,20 @@ static int validate_cfg(const rl_model_cfg* c) {
 struct WeightsHost {
     const void *tok_embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
     std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+    int location = 0;            // 0: device pointers; 1: host pointers, streamed through `staging`
+    char* staging = nullptr;     // dev
+    size_t staging_bytes = 0;
 };
 
-static int copy_weights(const rl_model_cfg& c, const rl_weights* w, WeightsHost& out, const char* what) {
+static int copy_weights(const rl_model_cfg& c, const rl_weights* w, WeightsHost& out, const char* what,
+                        bool allow_host = false) {
     if (!w) return fail(RL_EINVAL, "%s weights are NULL", what);
-    if (w->location != 0) return fail(RL_EINVAL, "%s weights: only device-resident weights (location 0) are supported", what);
+    if (w->location != 0 && !(allow_host && w->location == 1))
+        return fail(RL_EINVAL, "%s weights: location %d not supported here (0 = device%s)", what, w->location,
+                    allow_host ? ", 1 = host, streamed" : "; host-resident weights only in score_logprobs_kl");
+    out.location = w->location;
+    out.staging = (char*)w->staging;
+    out.staging_bytes = w->staging_bytes;
     if (!w->tok_embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
         !w->w_gate_up || !w->w_down)
         return fail(RL_EINVAL, "%s weights: NULL member", what);
@@ -159,6 +168,10 @@ struct rl_ctx {
     KvGeom geo;
     int impl = 0;
     int big_mode = 1;                // GemmArgs::big_mode of every tuned GEMM
+    // host-resident weight sets (scoring only): copies run on a stream of the library's own
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t ev_begin = nullptr, ev_glob_copied = nullptr, ev_glob_free = nullptr;
+    hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     // sequences
     int B = 0;                       // live sequences (0 = no prefill yet)
     std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len)
@@ -282,13 +295,12 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblo
 }
 
 static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                             int nblocks, hipStream_t s) {
+                             int nblocks, hipStream_t s, float* x, int l0, int l1) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int dt = m.dtype;
     const size_t e = esz_of(dt);
     const int qd = m.n_q_heads * m.head_dim;
-    float* x = c->at<float>(L.x);
     void* h = c->at<char>(L.h);
     float* qkv = c->at<float>(L.qkv);
     void* q = c->at<char>(L.q);
@@ -301,7 +313,7 @@ static bool run_layers_plain(rl_ctx* c, const WeightsHost& W, int n, bool paged,
     const int* bt = c->at<int>(L.block_table);
     const float2* rope = c->at<float2>(L.rope);
     const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
-    for (int l = 0; l < m.n_layers; ++l) {
+    for (int l = l0; l < l1; ++l) {
         k_rmsnorm(dt, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s);
         gemm(c, gcls, EPI_STORE_F32, h, m.d_model, W.wqkv[l], nullptr, n, L.nqkv, m.d_model, qkv, nullptr, L.nqkv, s);
         k_rope_append(dt, qkv, 1, 0, n, tpos, tslot, rope, q, paged ? nullptr : kb, paged ? nullptr : vb,
@@ -340,11 +352,10 @@ static int decode_splits(int n, int N, int K) {
 
 // bf16 weights / fp16 activations on the MFMA kernels.
 static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                            int nblocks, hipStream_t s) {
+                            int nblocks, hipStream_t s, float* x, int l0, int l1) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int qd = m.n_q_heads * m.head_dim;
-    float* x = c->at<float>(L.x);
     f16_t* h = c->at<f16_t>(L.h);
     f16_t* q = c->at<f16_t>(L.q);
     f16_t* kb = c->at<f16_t>(L.kbuf);
@@ -358,7 +369,7 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
     const float2* rope = c->at<float2>(L.rope);
     const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
     if (paged) k_rmsnorm(1, x, W.attn_norm[0], h, n, m.d_model, m.rms_eps, s);
-    for (int l = 0; l < m.n_layers; ++l) {
+    for (int l = l0; l < l1; ++l) {
         GemmArgs g;
         g.M = n;
         if (paged) {
@@ -413,10 +424,13 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
     return paged;
 }
 
+// Layers [l0, l1) (default: all) on the n packed rows whose residual stream is x (default: the workspace's).
 static bool run_layers(rl_ctx* c, const WeightsHost& W, int n, bool paged, bool write_pages, int max_ctx,
-                       int nblocks, hipStream_t s) {
-    if (c->impl == 1) return run_layers_fast(c, W, n, paged, write_pages, max_ctx, nblocks, s);
-    return run_layers_plain(c, W, n, paged, write_pages, max_ctx, nblocks, s);
+                       int nblocks, hipStream_t s, float* x = nullptr, int l0 = 0, int l1 = -1) {
+    if (!x) x = c->at<float>(c->L.x);
+    if (l1 < 0) l1 = c->cfg.n_layers;
+    if (c->impl == 1) return run_layers_fast(c, W, n, paged, write_pages, max_ctx, nblocks, s, x, l0, l1);
+    return run_layers_plain(c, W, n, paged, write_pages, max_ctx, nblocks, s, x, l0, l1);
 }
 
 // LM head on rows [0, nr) of h: logits fp32 [nr, V]
@@ -567,6 +581,13 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
 void rollout_destroy(rl_ctx* c) {
     if (!c) return;
     if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
+    if (c->copy_stream) {
+        (void)hipStreamSynchronize(c->copy_stream);
+        (void)hipStreamDestroy(c->copy_stream);
+        for (hipEvent_t e : {c->ev_begin, c->ev_glob_copied, c->ev_glob_free, c->ev_copied[0], c->ev_copied[1],
+                             c->ev_free[0], c->ev_free[1]})
+            if (e) (void)hipEventDestroy(e);
+    }
     for (int k = 0; k < RL_K_COUNT; ++k)
         for (auto& r : c->prof[k]) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
@@ -747,7 +768,33 @@ int rollout_generate(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prom
     return RL_OK;
 }
 
-// One teacher-forced pass of one weight set over all sequences; writes logp_out [B, Lmax].
+// Final norm, LM head and log-prob of every target token for the n packed rows whose residual stream is x.
+static void score_head(rl_ctx* c, const WeightsHost& W, float* x, int n, float* logp_out, int Lmax, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    k_rmsnorm(m.dtype, x, W.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
+    if (c->impl == 1) {
+        // LM head with the log-sum-exp and the target gather in its epilogue: no logits in memory
+        GemmArgs g;
+        g.M = n; g.A = c->at<f16_t>(L.h); g.lda = m.d_model; g.W = (const bf16_t*)W.lm_head; g.N = m.vocab;
+        g.K = m.d_model; g.tgt = c->at<int>(L.tok_tgt); g.lse_part = c->at<float2>(L.lse_part);
+        g.z_tgt = c->at<float>(L.z_tgt);
+        mfma(c, RL_K_LMHEAD_SCORE, MG_LSE, g, 1, s);
+        k_lse_reduce(c->at<float2>(L.lse_part), k_gemm_mfma_lse_parts(n, m.vocab, m.d_model, c->big_mode),
+                     c->at<float>(L.z_tgt), n, c->at<int>(L.tok_tgt), c->at<int>(L.tok_slot), c->at<int>(L.tok_pos),
+                     logp_out, Lmax, s);
+        return;
+    }
+    const size_t e = esz_of(m.dtype);
+    for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
+        int nr = std::min(L.logit_rows, n - r0);
+        lm_head_logits(c, RL_K_LMHEAD_SCORE, W, c->at<char>(L.h) + (size_t)r0 * m.d_model * e, nr, s);
+        k_lse_gather(c->at<float>(L.logits), m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0,
+                     c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, logp_out, Lmax, s);
+    }
+}
+
+// One teacher-forced pass of one device-resident weight set over all sequences; writes logp_out [B, Lmax].
 static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const int32_t* seq_len, int B, int Lmax,
                       float* logp_out, hipStream_t s) {
     const rl_model_cfg& m = c->cfg;
@@ -758,33 +805,165 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
     while (b0 < B) {
         Chunk ch;
         b0 = chunk_take(c, len_of, b0, B, ch);
-        const int n = ch.n;
         int rc = pack_chunk(c, ids, Lmax, ch, true, s);
         if (rc) return rc;
-        k_embed(m.dtype, c->at<int>(L.tok_ids), n, W.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+        k_embed(m.dtype, c->at<int>(L.tok_ids), ch.n, W.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
                 c->at<int>(L.errflag), s);
-        run_layers(c, W, n, false, false, ch.max_ctx, ch.nblocks, s);
-        k_rmsnorm(m.dtype, c->at<float>(L.x), W.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
-        if (c->impl == 1) {
-            // LM head with the log-sum-exp and the target gather in its epilogue: no logits in memory
-            GemmArgs g;
-            g.M = n; g.A = c->at<f16_t>(L.h); g.lda = m.d_model; g.W = (const bf16_t*)W.lm_head; g.N = m.vocab;
-            g.K = m.d_model; g.tgt = c->at<int>(L.tok_tgt); g.lse_part = c->at<float2>(L.lse_part);
-            g.z_tgt = c->at<float>(L.z_tgt);
-            mfma(c, RL_K_LMHEAD_SCORE, MG_LSE, g, 1, s);
-            k_lse_reduce(c->at<float2>(L.lse_part), k_gemm_mfma_lse_parts(n, m.vocab, m.d_model, c->big_mode), c->at<float>(L.z_tgt), n, c->at<int>(L.tok_tgt),
-                         c->at<int>(L.tok_slot), c->at<int>(L.tok_pos), logp_out, Lmax, s);
-            continue;
-        }
-        const size_t e = esz_of(m.dtype);
-        for (int r0 = 0; r0 < n; r0 += L.logit_rows) {
-            int nr = std::min(L.logit_rows, n - r0);
-            lm_head_logits(c, RL_K_LMHEAD_SCORE, W, c->at<char>(L.h) + (size_t)r0 * m.d_model * e, nr, s);
-            k_lse_gather(c->at<float>(L.logits), m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0,
-                         c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, logp_out, Lmax, s);
-        }
+        run_layers(c, W, ch.n, false, false, ch.max_ctx, ch.nblocks, s);
+        score_head(c, W, c->at<float>(L.x), ch.n, logp_out, Lmax, s);
     }
     return RL_OK;
+}
+
+// ---- host-resident weight sets (the reference model of a PPO step that does not fit next to the policy;
+// Section 3.1: the reference shares the actor's architecture, and its weights are swapped in for the
+// reference-policy inference step).  The weights are streamed layer by layer into a two-slot device
+// staging buffer on a copy stream while the previous layer computes.  To pay for each layer's transfer
+// once per pass, the loop order is layer-major: the residual stream of ALL tokens stays on the device
+// (x_all) and every chunk runs layer l before any runs layer l+1.
+struct StageLayout {
+    size_t attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down, layer_bytes;   // offsets inside a slot
+    size_t slot[2], globals, final_norm, x_all, total;
+    size_t b_norm, b_wqkv, b_wo, b_gate_up, b_down, b_globals;              // tensor sizes in bytes
+    int64_t x_rows;
+};
+
+static StageLayout make_stage_layout(const rl_model_cfg& c) {
+    StageLayout S{};
+    const size_t e = esz_of(c.dtype);
+    const size_t d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim;
+    const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+    S.b_norm = d * e; S.b_wqkv = nqkv * d * e; S.b_wo = d * qd * e;
+    S.b_gate_up = 2 * (size_t)c.d_ffn * d * e; S.b_down = d * (size_t)c.d_ffn * e;
+    S.b_globals = (size_t)c.vocab * d * e;
+    size_t o = 0;
+    S.attn_norm = o; o += al(S.b_norm);
+    S.wqkv = o; o += al(S.b_wqkv);
+    S.wo = o; o += al(S.b_wo);
+    S.ffn_norm = o; o += al(S.b_norm);
+    S.w_gate_up = o; o += al(S.b_gate_up);
+    S.w_down = o; o += al(S.b_down);
+    S.layer_bytes = o;
+    size_t t = 0;
+    S.slot[0] = t; t += S.layer_bytes;
+    S.slot[1] = t; t += S.layer_bytes;
+    S.globals = t; t += al(S.b_globals);          // embedding table first, LM head afterwards
+    S.final_norm = t; t += al(S.b_norm);
+    // every sequence occupies a multiple of 32 rows on the tuned path
+    S.x_rows = (int64_t)c.max_batch * ((c.max_seq + 31) / 32 * 32);
+    S.x_all = t; t += al((size_t)S.x_rows * d * sizeof(float));
+    S.total = t;
+    return S;
+}
+
+static int ensure_copy_stream(rl_ctx* c) {
+    if (c->copy_stream) return RL_OK;
+    HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    for (hipEvent_t* e : {&c->ev_begin, &c->ev_glob_copied, &c->ev_glob_free, &c->ev_copied[0], &c->ev_copied[1],
+                          &c->ev_free[0], &c->ev_free[1]})
+        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    return RL_OK;
+}
+
+static int score_pass_streamed(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const int32_t* seq_len, int B,
+                               int Lmax, float* logp_out, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    const StageLayout S = make_stage_layout(m);
+    if (!W.staging) return fail(RL_EINVAL, "host-resident weights need a device staging buffer (rl_weights.staging)");
+    if (((uintptr_t)W.staging & 255) != 0) return fail(RL_EINVAL, "staging buffer must be 256-byte aligned");
+    if (W.staging_bytes < S.total)
+        return fail(RL_ENOSPACE, "staging buffer: %zu bytes given, %zu needed", W.staging_bytes, S.total);
+    int rc = ensure_copy_stream(c);
+    if (rc) return rc;
+    hipStream_t cs = c->copy_stream;
+    char* st = W.staging;
+    float* x_all = reinterpret_cast<float*>(st + S.x_all);
+
+    // chunks and their first rows in x_all
+    std::vector<int> len_of(seq_len, seq_len + B);
+    std::vector<Chunk> chunks;
+    std::vector<int64_t> first;
+    int64_t rows = 0;
+    for (int b0 = 0; b0 < B;) {
+        chunks.emplace_back();
+        b0 = chunk_take(c, len_of, b0, B, chunks.back());
+        first.push_back(rows);
+        rows += chunks.back().n;
+    }
+    if (rows > S.x_rows) return fail(RL_EINVAL, "internal: %lld packed rows exceed the staging rows", (long long)rows);
+
+    // device-pointer view of the staged weights: layer l lives in slot l % 2
+    WeightsHost D;
+    D.tok_embed = st + S.globals;
+    D.lm_head = st + S.globals;
+    D.final_norm = st + S.final_norm;
+    auto fill = [&](std::vector<const void*>& v, size_t off) {
+        v.resize(m.n_layers);
+        for (int l = 0; l < m.n_layers; ++l) v[l] = st + S.slot[l & 1] + off;
+    };
+    fill(D.attn_norm, S.attn_norm); fill(D.wqkv, S.wqkv); fill(D.wo, S.wo);
+    fill(D.ffn_norm, S.ffn_norm); fill(D.w_gate_up, S.w_gate_up); fill(D.w_down, S.w_down);
+    auto copy_layer = [&](int l) -> int {
+        char* slot = st + S.slot[l & 1];
+        HIP_TRY(hipMemcpyAsync(slot + S.attn_norm, W.attn_norm[l], S.b_norm, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipMemcpyAsync(slot + S.wqkv, W.wqkv[l], S.b_wqkv, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipMemcpyAsync(slot + S.wo, W.wo[l], S.b_wo, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipMemcpyAsync(slot + S.ffn_norm, W.ffn_norm[l], S.b_norm, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipMemcpyAsync(slot + S.w_gate_up, W.w_gate_up[l], S.b_gate_up, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipMemcpyAsync(slot + S.w_down, W.w_down[l], S.b_down, hipMemcpyHostToDevice, cs));
+        HIP_TRY(hipEventRecord(c->ev_copied[l & 1], cs));
+        return RL_OK;
+    };
+
+    k_fill_f32(logp_out, 0.f, (int64_t)B * Lmax, s);
+    // the staging buffer may still be read by work queued earlier on s
+    HIP_TRY(hipEventRecord(c->ev_begin, s));
+    HIP_TRY(hipStreamWaitEvent(cs, c->ev_begin, 0));
+    HIP_TRY(hipMemcpyAsync(st + S.globals, W.tok_embed, S.b_globals, hipMemcpyHostToDevice, cs));
+    HIP_TRY(hipMemcpyAsync(st + S.final_norm, W.final_norm, S.b_norm, hipMemcpyHostToDevice, cs));
+    HIP_TRY(hipEventRecord(c->ev_glob_copied, cs));
+    for (int l = 0; l < std::min(2, m.n_layers); ++l)
+        if ((rc = copy_layer(l))) return rc;
+
+    // embedding of every chunk into x_all
+    HIP_TRY(hipStreamWaitEvent(s, c->ev_glob_copied, 0));
+    for (size_t k = 0; k < chunks.size(); ++k) {
+        if ((rc = pack_chunk(c, ids, Lmax, chunks[k], true, s))) return rc;
+        k_embed(m.dtype, c->at<int>(L.tok_ids), chunks[k].n, D.tok_embed, m.d_model, m.vocab,
+                x_all + first[k] * m.d_model, c->at<int>(L.errflag), s);
+    }
+    // the LM head takes the embedding table's place once the gathers are done
+    HIP_TRY(hipEventRecord(c->ev_glob_free, s));
+    HIP_TRY(hipStreamWaitEvent(cs, c->ev_glob_free, 0));
+    HIP_TRY(hipMemcpyAsync(st + S.globals, W.lm_head, S.b_globals, hipMemcpyHostToDevice, cs));
+    HIP_TRY(hipEventRecord(c->ev_glob_copied, cs));
+
+    for (int l = 0; l < m.n_layers; ++l) {
+        HIP_TRY(hipStreamWaitEvent(s, c->ev_copied[l & 1], 0));
+        for (size_t k = 0; k < chunks.size(); ++k) {
+            if ((rc = pack_chunk(c, ids, Lmax, chunks[k], true, s))) return rc;
+            run_layers(c, D, chunks[k].n, false, false, chunks[k].max_ctx, chunks[k].nblocks, s,
+                       x_all + first[k] * m.d_model, l, l + 1);
+        }
+        if (l + 2 < m.n_layers) {   // slot l % 2 is free once layer l has run on every chunk
+            HIP_TRY(hipEventRecord(c->ev_free[l & 1], s));
+            HIP_TRY(hipStreamWaitEvent(cs, c->ev_free[l & 1], 0));
+            if ((rc = copy_layer(l + 2))) return rc;
+        }
+    }
+    HIP_TRY(hipStreamWaitEvent(s, c->ev_glob_copied, 0));
+    for (size_t k = 0; k < chunks.size(); ++k) {
+        if ((rc = pack_chunk(c, ids, Lmax, chunks[k], true, s))) return rc;
+        score_head(c, D, x_all + first[k] * m.d_model, chunks[k].n, logp_out, Lmax, s);
+    }
+    return RL_OK;
+}
+
+size_t rollout_weight_staging_bytes(const rl_model_cfg* cfg) {
+    if (validate_cfg(cfg) != RL_OK) return 0;
+    return make_stage_layout(*cfg).total;
 }
 
 int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* reference, const int32_t* ids,
@@ -806,18 +985,20 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
         return fail(RL_EINVAL, "kl outputs need logp_policy and logp_ref buffers");
     hipStream_t s = (hipStream_t)stream;
     WeightsHost wp, wr;
-    int rc = copy_weights(m, policy, wp, "policy");
+    int rc = copy_weights(m, policy, wp, "policy", true);
     if (rc) return rc;
     if (reference) {
-        rc = copy_weights(m, reference, wr, "reference");
+        rc = copy_weights(m, reference, wr, "reference", true);
         if (rc) return rc;
     }
     if (logp_policy) {
-        rc = score_pass(c, wp, ids, seq_len, B, Lmax, logp_policy, s);
+        rc = wp.location == 1 ? score_pass_streamed(c, wp, ids, seq_len, B, Lmax, logp_policy, s)
+                              : score_pass(c, wp, ids, seq_len, B, Lmax, logp_policy, s);
         if (rc) return rc;
     }
     if (reference && logp_ref) {
-        rc = score_pass(c, wr, ids, seq_len, B, Lmax, logp_ref, s);
+        rc = wr.location == 1 ? score_pass_streamed(c, wr, ids, seq_len, B, Lmax, logp_ref, s)
+                              : score_pass(c, wr, ids, seq_len, B, Lmax, logp_ref, s);
         if (rc) return rc;
     }
     if (kl || kl_penalty) {

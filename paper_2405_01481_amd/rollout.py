@@ -36,7 +36,7 @@ class rl_model_cfg(C.Structure):
 class rl_weights(C.Structure):
     _fields_ = [("tok_embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")] + \
-               [("location", C.c_int32)]
+               [("location", C.c_int32), ("staging", C.c_void_p), ("staging_bytes", C.c_size_t)]
 
 
 class rl_sample_cfg(C.Structure):
@@ -59,6 +59,8 @@ def lib():
         L.rollout_workspace_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_kv_pool_bytes.restype = C.c_size_t
         L.rollout_kv_pool_bytes.argtypes = [C.POINTER(rl_model_cfg)]
+        L.rollout_weight_staging_bytes.restype = C.c_size_t
+        L.rollout_weight_staging_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_init.argtypes = [C.POINTER(rl_model_cfg), C.POINTER(rl_weights), vp, C.c_size_t, vp, C.c_size_t,
                                    C.POINTER(vp)]
         L.rollout_prefill.argtypes = [vp, vp, vp, i32, i32, vp]
@@ -105,13 +107,20 @@ def rollout_kv_pool_bytes(cfg: rl_model_cfg) -> int:
     return int(lib().rollout_kv_pool_bytes(C.byref(cfg)))
 
 
+def rollout_weight_staging_bytes(cfg: rl_model_cfg) -> int:
+    return int(lib().rollout_weight_staging_bytes(C.byref(cfg)))
+
+
 class Weights:
-    """Marshals a dict of torch tensors (layout of the input generator) into rl_weights; keeps them alive."""
+    """Marshals a dict of torch tensors (layout of the input generator) into rl_weights; keeps them alive.
+    With `staging` (a device uint8 tensor of rollout_weight_staging_bytes) the tensors are taken to be host
+    memory and the set is marked location 1 (streamed during scoring)."""
 
     _LAYER = ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")
 
-    def __init__(self, w):
+    def __init__(self, w, staging=None):
         self.tensors = w
+        self.staging = staging
         n = len(w["layers"])
         self._arrays = {}
         s = rl_weights()
@@ -127,6 +136,11 @@ class Weights:
             self._arrays[k] = arr
             setattr(s, k, C.cast(arr, C.POINTER(C.c_void_p)))
         s.location = 0
+        if staging is not None:
+            assert staging.is_cuda and all(not w[k].is_cuda for k in ("tok_embed", "final_norm", "lm_head"))
+            s.location = 1
+            s.staging = staging.data_ptr()
+            s.staging_bytes = staging.numel() * staging.element_size()
         self.struct = s
 
 

@@ -38,6 +38,14 @@ def test_sizes_and_cfg_validation():
         assert R.rollout_workspace_bytes(cfg) == 0, field
         assert R.rollout_last_error() != ""
     assert R.lib().rollout_workspace_bytes(None) == 0
+    # staging for a host-resident weight set: two layers + one [vocab, d] table + fp32 residual of all tokens
+    t = synth.TINY
+    layer = (2 * t.d_model + (t.n_q_heads + 2 * t.n_kv_heads) * t.head_dim * t.d_model
+             + t.d_model * t.n_q_heads * t.head_dim + 3 * t.d_ffn * t.d_model) * 4
+    lo = 2 * layer + t.vocab * t.d_model * 4 + 4 * 64 * t.d_model * 4
+    got = R.rollout_weight_staging_bytes(good)
+    assert lo <= got <= lo + 16 * 256 + t.d_model * 4
+    assert R.lib().rollout_weight_staging_bytes(None) == 0
 
 
 def test_null_and_state_errors_without_gpu():

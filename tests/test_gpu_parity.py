@@ -271,6 +271,53 @@ def test_big_tile_gemm_kernel_against_oracle(shape):
     ro.close()
 
 
+def _pinned_copy(w):
+    """The same weight dict with every tensor in pinned host memory."""
+    pin = lambda t: t.cpu().pin_memory()
+    out = {k: pin(w[k]) for k in ("tok_embed", "final_norm", "lm_head")}
+    out["layers"] = [{k: pin(v) for k, v in lay.items()} for lay in w["layers"]]
+    return out
+
+
+@pytest.mark.parametrize("shape,impl", [(MINI128, 1), (MINI128, 2), (MINI32F, 0)], ids=["mini128", "mini128-bigtiles", "mini32f"])
+def test_reference_streamed_from_host_matches_resident(shape, impl):
+    """Reference weights held in pinned host memory and streamed layer by layer (the 70B configuration's
+    reference pass): scores must equal the device-resident pass bit for bit -- the per-token arithmetic
+    is the same, only the loop order (layer-major over all chunks) and where the weights sit differ --
+    and meet the oracle tolerance.  Several chunks, several layers, two calls on the same staging."""
+    B = 6
+    wp = synth.make_weights(shape, 1, DEV)
+    wr = synth.make_weights(shape, 2, DEV)
+    cfg = R.make_cfg(shape, B, 72, max_chunk_tokens=150)
+    Wp, Wr = R.Weights(wp), R.Weights(wr)
+    ro = R.Rollout(cfg, Wp, DEV)
+    ro.rollout_set_impl(impl)
+    staging = torch.empty(R.rollout_weight_staging_bytes(cfg), dtype=torch.uint8, device=DEV)
+    Wr_host = R.Weights(_pinned_copy(wr), staging=staging)
+    mp = O.Model(shape, synth.weights_for_oracle(wp))
+    mr = O.Model(shape, synth.weights_for_oracle(wr))
+    lt, _ = _tol(shape)
+    for seed in (77, 78):                                   # second call reuses the staging buffer
+        ids, lens, plens = synth.make_sequences(shape.vocab, B, 72, 9, 0.4, seed)
+        res = _score(ro, Wp, Wr, ids, lens, plens, 0.5)
+        got = _score(ro, Wp, Wr_host, ids, lens, plens, 0.5)
+        for a, b in zip(got, res):
+            assert np.array_equal(a, b)
+        check_scores(*got, O.score_batch(mp, mr, ids, lens, plens, 0.5), lt, 0.5)
+    # policy streamed as well; too-small staging is refused
+    Wp_host = R.Weights(_pinned_copy(wp), staging=staging)
+    both = _score(ro, Wp_host, Wr_host, ids, lens, plens, 0.5)
+    for a, b in zip(both, res):
+        assert np.array_equal(a, b)
+    small = R.Weights(_pinned_copy(wr), staging=staging[:staging.numel() // 2])
+    with pytest.raises(R.RolloutError) as e:
+        _score(ro, Wp, small, ids, lens, plens)
+    assert e.value.code == R.RL_ENOSPACE
+    with pytest.raises(R.RolloutError):                     # generation needs resident weights
+        R.Rollout(cfg, Wr_host, DEV)
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
