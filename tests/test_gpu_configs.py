@@ -45,13 +45,24 @@ def test_1b_shape_scoring_and_rollout_subset():
     ro.close()
 
 
-def _run_and_check(shape, B, P_lo, P_hi, G, rows, seed=4, temp=1.0, chunk=None, score_positions=None):
+def _run_and_check(shape, B, P_lo, P_hi, G, rows, seed=4, temp=1.0, chunk=None, score_positions=None,
+                   ref_on_host=False):
     """Generate with the GPU path, then verify `rows` with the oracle at the shape's full width and
     depth: every generated token along the GPU trajectory, and teacher-forced scores of both models."""
     wp, wr = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
-    Wp, Wr = R.Weights(wp), R.Weights(wr)
     Lmax = P_hi + G
-    ro = R.Rollout(R.make_cfg(shape, B, Lmax, max_chunk_tokens=chunk), Wp, DEV)
+    cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=chunk)
+    if ref_on_host:
+        # reference weights live in pinned host memory and are streamed layer by layer while scoring
+        pin = lambda t: t.cpu().pin_memory()
+        wr = {**{k: pin(wr[k]) for k in ("tok_embed", "final_norm", "lm_head")},
+              "layers": [{k: pin(v) for k, v in lay.items()} for lay in wr["layers"]]}
+        torch.cuda.empty_cache()
+        staging = torch.empty(R.rollout_weight_staging_bytes(cfg), dtype=torch.uint8, device=DEV)
+        Wp, Wr = R.Weights(wp), R.Weights(wr, staging=staging)
+    else:
+        Wp, Wr = R.Weights(wp), R.Weights(wr)
+    ro = R.Rollout(cfg, Wp, DEV)
     ids, lens = synth.make_prompts(shape.vocab, B, P_hi, P_lo, 3)
     out = torch.zeros(B, G, dtype=torch.int32, device=DEV)
     olp = torch.zeros(B, G, dtype=torch.float32, device=DEV)
@@ -86,12 +97,14 @@ def _run_and_check(shape, B, P_lo, P_hi, G, rows, seed=4, temp=1.0, chunk=None, 
     return st, errs
 
 
-def test_70b_shape_two_layers():
-    """Config 5's width (d 8192, 64 query / 8 KV heads: GQA group of 8, FFN 28672, vocab 128256) at
-    two layers: exercises the widest rows and the 8-wave attention workgroups."""
-    s = synth.scaled_shape(synth.L70B, "70b_2l", n_layers=2)
-    st, errs = _run_and_check(s, 3, 30, 44, 6, rows=[1])
-    print("70b-shape 2 layers:", st, errs)
+def test_70b_shape_three_layers_reference_on_host():
+    """Config 5's width (d 8192, 64 query / 8 KV heads: GQA group of 8, FFN 28672, vocab 128256) and its
+    residency: the policy is on the device, the reference weights sit in pinned host memory and are
+    streamed layer by layer during scoring.  Three layers, so a staging slot is refilled while in use
+    elsewhere; exercises the widest rows and the 8-wave attention workgroups."""
+    s = synth.scaled_shape(synth.L70B, "70b_3l", n_layers=3)
+    st, errs = _run_and_check(s, 3, 30, 44, 6, rows=[1], ref_on_host=True)
+    print("70b-shape 3 layers, reference on host:", st, errs)
 
 
 def test_8b_long_ragged_four_layers():
