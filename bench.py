@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--impl", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=16384)
+    ap.add_argument("--ref-host", action="store_true",
+                    help="keep the reference weights in pinned host memory and stream them layer by layer while "
+                         "scoring (the 70B configuration's residency); reported in config.reference")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -127,9 +130,17 @@ def main():
 
     wp = synth.make_weights(shape, wl.policy_seed, dev)
     wr = synth.make_weights(shape, wl.ref_seed, dev)
-    Wp, Wr = R.Weights(wp), R.Weights(wr)
     Lmax = Pmax + G
     cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=max(Lmax, args.chunk))
+    if args.ref_host:
+        pin = lambda t: t.cpu().pin_memory()
+        wr = {**{k: pin(wr[k]) for k in ("tok_embed", "final_norm", "lm_head")},
+              "layers": [{k: pin(v) for k, v in lay.items()} for lay in wr["layers"]]}
+        torch.cuda.empty_cache()
+        staging = torch.empty(R.rollout_weight_staging_bytes(cfg), dtype=torch.uint8, device=dev)
+        Wp, Wr = R.Weights(wp), R.Weights(wr, staging=staging)
+    else:
+        Wp, Wr = R.Weights(wp), R.Weights(wr)
     ro = R.Rollout(cfg, Wp, dev)
     if args.impl >= 0:
         ro.rollout_set_impl(args.impl)
@@ -249,7 +260,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape.name, "layers": shape.n_layers, "batch": B,
                    "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
-                   "temperature": wl.temperature, "reduced": reduced, "impl": args.impl},
+                   "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
+                   "reference": "pinned host, streamed" if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
         "decode_tok_s": B * G / decode_s, "generate_tok_s": B * G / gen_s,
         "decode_hbm_gbps": decode_gbps, "decode_hbm_frac": decode_gbps / HBM_PEAK_GBPS,
