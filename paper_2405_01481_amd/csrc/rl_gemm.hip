@@ -112,6 +112,65 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
         }
         return;
     }
+    if (EPI == MG_QKV) {
+        // V columns with dim-major destinations (vT[kv head][dim][token], and the V pages of the cache):
+        // the four registers r = 4k .. 4k+3 of a lane are four consecutive tokens of one dimension, so they
+        // leave as one 8-byte store instead of four 2-byte stores a cache line apart from their neighbours'.
+        const int hd = a.hd, half = hd >> 1;
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+            const int c0 = wn * TN * 32 + j * 32 + lrow;
+            const int col0 = hd == 128 ? nb * BN + (c0 & ~127) + (((c0 & 127) >> 5) >> 1) * 32 + (c0 & 31) : nb * BN + c0;
+            const int head = col0 / hd, jj = col0 % hd;
+            if (head < a.Hq + a.Hkv || (a.vt_cap <= 0 && !a.pool)) continue;
+            const int g = head - a.Hq - a.Hkv;
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int m4 = m_base + 8 * rq + 4 * lg;
+                if (m4 >= a.M) continue;
+                int p[4];
+                typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+                half4 h0, h1;
+                bool all = true;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    p[t] = m4 + t < a.M ? a.tok_pos[m4 + t] : -1;     // < 0: padding row, stored as zero
+                    all = all && p[t] >= 0;
+                    h0[t] = p[t] >= 0 ? (f16_t)acc[j][4 * rq + t] : (f16_t)0.f;
+                    h1[t] = p[t] >= 0 ? (f16_t)acc[j + 1][4 * rq + t] : (f16_t)0.f;
+                }
+                if (a.v_out && a.vt_cap > 0) {
+                    f16_t* o0 = a.v_out + ((int64_t)g * hd + jj) * a.vt_cap + m4;
+                    f16_t* o1 = o0 + (int64_t)half * a.vt_cap;
+                    if (m4 + 3 < a.M) {
+                        *reinterpret_cast<half4*>(o0) = h0;
+                        *reinterpret_cast<half4*>(o1) = h1;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (m4 + t < a.M) { o0[t] = h0[t]; o1[t] = h1[t]; }
+                    }
+                }
+                if (a.pool) {
+                    if (all && p[0] % 4 == 0 && p[3] == p[0] + 3) {   // four tokens of one sequence: same page, adjacent slots
+                        const int64_t page = a.block_table[(int64_t)a.tok_slot[m4] * a.mpps + p[0] / a.geo.PT];
+                        const int st = p[0] % a.geo.PT;
+                        *reinterpret_cast<half4*>(a.pool + a.geo.v_off(a.layer, page, g, st, jj)) = h0;
+                        *reinterpret_cast<half4*>(a.pool + a.geo.v_off(a.layer, page, g, st, jj + half)) = h1;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (p[t] >= 0) {
+                                const int64_t page = a.block_table[(int64_t)a.tok_slot[m4 + t] * a.mpps + p[t] / a.geo.PT];
+                                const int st = p[t] % a.geo.PT;
+                                a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = h0[t];
+                                a.pool[a.geo.v_off(a.layer, page, g, st, jj + half)] = h1[t];
+                            }
+                    }
+                }
+            }
+        }
+    }
     {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -198,23 +257,10 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                             a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = (f16_t)v0;
                             a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
                         }
-                    } else {
+                    } else if (a.v_out && a.vt_cap <= 0) {   // token-major V (dim-major V and the pages: packed path above)
                         int g = head - Hq - Hkv;
-                        if (a.v_out) {
-                            if (a.vt_cap > 0) {   // dim-major: vT[kv head][dim][token]
-                                a.v_out[((int64_t)g * hd + jj) * a.vt_cap + m] = (f16_t)v0;
-                                a.v_out[((int64_t)g * hd + jj + half) * a.vt_cap + m] = (f16_t)v1;
-                            } else {
-                                f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
-                                o[0] = (f16_t)v0; o[half] = (f16_t)v1;
-                            }
-                        }
-                        if (a.pool && !pad) {
-                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
-                            int st = pos % a.geo.PT;
-                            a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = (f16_t)v0;
-                            a.pool[a.geo.v_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
-                        }
+                        f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
+                        o[0] = (f16_t)v0; o[half] = (f16_t)v1;
                     }
                 }
             }
