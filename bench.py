@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--impl", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=16384)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="first run three device copies of 1 GiB (read 1 GiB, write 1 GiB each): the known-size "
+                         "kernel that HBM-traffic counters of a rocprofv3 --pmc run are scaled by")
     ap.add_argument("--ref-host", action="store_true",
                     help="keep the reference weights in pinned host memory and stream them layer by layer while "
                          "scoring (the 70B configuration's residency); reported in config.reference")
@@ -127,6 +130,15 @@ def main():
     reduced = reduced or (B, Pmax, G) != (wl.batch, wl.prompt_max, wl.gen) or args.no_score
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     wp = synth.make_weights(shape, wl.policy_seed, dev)
     wr = synth.make_weights(shape, wl.ref_seed, dev)
@@ -246,8 +258,14 @@ def main():
         name = "attn_decode (paged GQA decode attention)"
         per_launch = attn_decode_bytes(shape, plen, G) / launches_per_step["attn_decode"]
         achieved = per_launch / (a_avg * 1e-3) / 1e9 if a_avg else None
+    # HBM-side bytes per launch from hardware counters cannot be taken inside this process; the figure is the
+    # one measured for this workload's decode GEMMs with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by
+    # what the counter reads for a 1 GiB device copy; summary in profiles/decode_gemm_hbm_traffic.md)
+    traffic = None
+    if g_tot >= a_tot and args.workload == "8b" and not args.layers and B == wl.batch and args.impl in (-1, 1, 2):
+        traffic = 143.9e6
     roofline = {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": (achieved / HBM_PEAK_GBPS) if achieved else None, "traffic": None,
+                "frac": (achieved / HBM_PEAK_GBPS) if achieved else None, "traffic": traffic,
                 "avg_launch_ms": g_avg if g_tot >= a_tot else a_avg, "bytes_per_launch": per_launch}
 
     line = {
