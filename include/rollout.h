@@ -130,7 +130,7 @@ int rollout_prefill(rl_ctx* ctx, const int32_t* prompt_ids, const int32_t* promp
  * append its K/V to the cache; sample the next token into tok_out[b] (dev int32
  * [B], may be NULL) and its temperature-1 log-probability into logp_out[b] (dev
  * fp32 [B], may be NULL).  A sequence that has emitted eos_id keeps emitting
- * eos_id with log-prob 0.  Errors: RL_ESTATE (no prefill yet), RL_EINVAL
+ * eos_id with log-prob 0 and no longer grows its cache.  Errors: RL_ESTATE (no prefill yet), RL_EINVAL
  * (sequence would exceed max_seq), RL_ENOMEM_PAGES. */
 int rollout_decode_step(rl_ctx* ctx, const rl_sample_cfg* sample, const int32_t* tok_in,
                         int32_t* tok_out, float* logp_out, void* stream);
@@ -142,6 +142,25 @@ int rollout_generate(rl_ctx* ctx, const rl_sample_cfg* sample,
                      const int32_t* prompt_ids, const int32_t* prompt_len,
                      int32_t B, int32_t Pmax, int32_t G,
                      int32_t* out_ids, int32_t* out_len, float* out_logp, void* stream);
+
+/* Queue mode of rollout_generate (Section 3.2: response lengths vary widely, so generation work is handed
+ * out dynamically rather than in fixed batches).  Q prompts, any number; at most max_batch are live at a
+ * time.  Prompt q generates until it emits eos_id or has produced gen_limit[q] tokens; its cache pages
+ * then go back to the pool and its slot takes the next prompt in line, which is prefilled while the other
+ * slots wait.  The host looks at the finished flags every 8 decode steps; a finished sequence is parked
+ * meanwhile (no cache growth, no attention).  Row q's tokens and log-probs are exactly those
+ * rollout_generate would give it in any batch: it draws U(seed, seq_id_base + q, n) for its n-th token and
+ * no kernel mixes rows.
+ * prompt_ids: dev int32 [Q, Pmax]; prompt_len, gen_limit: host int32 [Q], 1 <= gen_limit[q] <= Gmax and
+ * prompt_len[q] - 1 + gen_limit[q] <= max_seq.  out_ids: dev int32 [Q, Gmax]; out_len: dev int32 [Q]
+ * (tokens generated, the eos included); out_logp: dev fp32 [Q, Gmax] or NULL.  Entries past out_len[q]
+ * hold eos_id (-1 when there is none) and log-prob 0.  Waits for `stream` between bursts; no sequence
+ * stays live afterwards.  Errors: RL_EINVAL, RL_ENOMEM_PAGES (the pool cannot hold max_batch live
+ * sequences of these lengths). */
+int rollout_generate_queue(rl_ctx* ctx, const rl_sample_cfg* sample,
+                           const int32_t* prompt_ids, const int32_t* prompt_len, const int32_t* gen_limit,
+                           int32_t Q, int32_t Pmax, int32_t Gmax,
+                           int32_t* out_ids, int32_t* out_len, float* out_logp, void* stream);
 
 /* Teacher-forced scoring (the "log-probs calculation" stage, Section 3.1 and the
  * stage tables of Section 3.3).  For every sequence b of length L_b and every

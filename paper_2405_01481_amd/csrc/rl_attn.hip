@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
         }
         const int64_t head = (int64_t)b * a.Hq + g * G + hh;
         if (nsplit == 1) {
-            a.out[head * HD + d] = (f16_t)(o / l);
+            a.out[head * HD + d] = l > 0.f ? (f16_t)(o / l) : (f16_t)0.f;   // parked row (position -1): no keys, zeros
         } else {
             a.part_o[(head * nsplit + split) * HD + d] = o;
             if (d == 0) {
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, con
         o += wt * part_o[(head * nsplit + s) * HD + d];
         l += wt * part_ml[(head * nsplit + s) * 2 + 1];
     }
-    out[head * HD + d] = (f16_t)(o / l);
+    out[head * HD + d] = l > 0.f ? (f16_t)(o / l) : (f16_t)0.f;
 }
 
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {

@@ -52,17 +52,19 @@ void k_set_pages(int* block_table, int mpps, const int* triples_host, int n_trip
 }
 
 // ---------------------------------------------------------------- token bookkeeping
-__global__ void step_begin_kernel(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok,
-                                  int* tok_pos, int* tok_slot, int B) {
+// A finished sequence is parked: position -1, which every consumer reads as "no cache slot, no
+// attention, zeros" (the padding-row rule of the packed token lists), so it stops growing its cache.
+__global__ void step_begin_kernel(const int* tok_in, const int* last_tok, const int* seq_len, const int* finished,
+                                  int* cur_tok, int* tok_pos, int* tok_slot, int B) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     cur_tok[b] = tok_in ? tok_in[b] : last_tok[b];
-    tok_pos[b] = seq_len[b];
+    tok_pos[b] = finished[b] ? -1 : seq_len[b];
     tok_slot[b] = b;
 }
-void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok, int* tok_pos,
-                  int* tok_slot, int B, hipStream_t s) {
-    step_begin_kernel<<<(B + 255) / 256, 256, 0, s>>>(tok_in, last_tok, seq_len, cur_tok, tok_pos, tok_slot, B);
+void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, const int* finished, int* cur_tok,
+                  int* tok_pos, int* tok_slot, int B, hipStream_t s) {
+    step_begin_kernel<<<(B + 255) / 256, 256, 0, s>>>(tok_in, last_tok, seq_len, finished, cur_tok, tok_pos, tok_slot, B);
 }
 
 // Pack rows of a padded [*, ld_ids] id matrix into a flat token list.
@@ -71,27 +73,28 @@ void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, in
 // same row, or -1 when there is none inside full_len[r].
 // With align > 1 every row is padded to a multiple of align tokens; padding entries carry
 // token id 0, position -1 and no target.
-__global__ void pack_tokens_kernel(const int* ids, int ld_ids, const int* seq_first, const int* row_start,
-                                   const int* row_len, const int* full_len, int align, int* tok_ids, int* tok_pos,
-                                   int* tok_slot, int* tok_tgt) {
+__global__ void pack_tokens_kernel(const int* ids, int ld_ids, const int* seq_first, const int* row_slot,
+                                   const int* row_start, const int* row_len, const int* full_len, int align,
+                                   int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt) {
     int r = blockIdx.x;
     int b = seq_first[r], st = row_start[r], len = row_len[r];
+    const int slot = row_slot[r];
     const int alen = (len + align - 1) / align * align;
     const int* src = ids + (int64_t)b * ld_ids;
     for (int t = threadIdx.x; t < alen; t += blockDim.x) {
         const bool real = t < len;
         tok_ids[st + t] = real ? src[t] : 0;
         tok_pos[st + t] = real ? t : -1;
-        tok_slot[st + t] = b;
+        tok_slot[st + t] = slot;
         if (tok_tgt) tok_tgt[st + t] = (real && t + 1 < full_len[r]) ? src[t + 1] : -1;
     }
 }
-void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_start, const int* row_len,
-                   const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
-                   hipStream_t s) {
+void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_slot, const int* row_start,
+                   const int* row_len, const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot,
+                   int* tok_tgt, int nrows, hipStream_t s) {
     if (nrows <= 0) return;
-    pack_tokens_kernel<<<nrows, 256, 0, s>>>(ids, ld_ids, seq_first, row_start, row_len, full_len, align, tok_ids,
-                                             tok_pos, tok_slot, tok_tgt);
+    pack_tokens_kernel<<<nrows, 256, 0, s>>>(ids, ld_ids, seq_first, row_slot, row_start, row_len, full_len, align,
+                                             tok_ids, tok_pos, tok_slot, tok_tgt);
 }
 
 // After prefill of the first P-1 prompt tokens: remember the last prompt token, lengths, counters.
@@ -110,6 +113,31 @@ void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_t
                      int* finished, int* step_count, int B, hipStream_t s) {
     prefill_state_kernel<<<(B + 255) / 256, 256, 0, s>>>(ids, ld_ids, row_len, last_tok, seq_len, gen_count,
                                                          finished, step_count, B);
+}
+
+__global__ void prefill_state_slots_kernel(const int* ids, int ld_ids, int n, const int* seq_first, const int* row_slot,
+                                           const int* row_len, const int* limit, int* last_tok, int* seq_len,
+                                           int* gen_count, int* finished, int* step_count, int* out_row, int* seq_id,
+                                           int* gen_limit) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int row = seq_first[i], b = row_slot[i], P = row_len[i];
+    last_tok[b] = ids[(int64_t)row * ld_ids + P - 1];
+    seq_len[b] = P - 1;
+    gen_count[b] = 0;
+    finished[b] = 0;
+    step_count[b] = 0;
+    out_row[b] = row;
+    seq_id[b] = row;
+    gen_limit[b] = limit[i];
+}
+void k_prefill_state_slots(const int* ids, int ld_ids, int n, const int* seq_first, const int* row_slot,
+                           const int* row_len, const int* limit, int* last_tok, int* seq_len, int* gen_count,
+                           int* finished, int* step_count, int* out_row, int* seq_id, int* gen_limit, hipStream_t s) {
+    if (n <= 0) return;
+    prefill_state_slots_kernel<<<(n + 255) / 256, 256, 0, s>>>(ids, ld_ids, n, seq_first, row_slot, row_len, limit,
+                                                               last_tok, seq_len, gen_count, finished, step_count,
+                                                               out_row, seq_id, gen_limit);
 }
 
 __global__ void out_len_kernel(const int* gen_count, int* out_len, int B) {
@@ -257,6 +285,12 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* qkv, int 
         __syncthreads();
         row = rowbuf;
     }
+    if (pos < 0) {   // parked / padding row: zero query, no key or value
+        for (int i = threadIdx.x; i < Hq * hd; i += 256) q_out[(int64_t)n * Hq * hd + i] = from_f<T>(0.f);
+        if (k_out) for (int i = threadIdx.x; i < Hkv * hd; i += 256) k_out[(int64_t)n * Hkv * hd + i] = from_f<T>(0.f);
+        if (v_out) for (int i = threadIdx.x; i < Hkv * hd; i += 256) v_out[(int64_t)n * Hkv * hd + i] = from_f<T>(0.f);
+        return;
+    }
     const float2* rt = rope + (int64_t)pos * half;
     int64_t page = 0;
     int slot_tok = 0;
@@ -326,6 +360,10 @@ __global__ __launch_bounds__(1024) void rope_append_split_kernel(const float* pa
     const int pos = tok_pos[n];
     const int width = (Hq + 2 * Hkv) * hd;
     const float* row = part + (int64_t)n * width;
+    if (pos < 0) {   // parked row: zero query, nothing appended to the cache
+        for (int i = threadIdx.x; i < Hq * hd; i += 1024) q_out[(int64_t)n * Hq * hd + i] = from_f<T>(0.f);
+        return;
+    }
     const float2* rt = rope + (int64_t)pos * half;
     const int64_t page = bt[(int64_t)tok_slot[n] * mpps + pos / geo.PT];
     const int st = pos % geo.PT;
@@ -438,6 +476,10 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const T* q, const T* k
     const int hd = geo.hd, Hkv = geo.Hkv;
     const int n = blockIdx.x, h = blockIdx.y, g = h / (Hq / Hkv);
     const int pos = tok_pos[n], ctx = pos + 1;
+    if (ctx <= 0) {            // parked row (position -1): no keys, zeros
+        if (threadIdx.x < hd) out[((int64_t)n * Hq + h) * hd + threadIdx.x] = from_f<T>(0.f);
+        return;
+    }
     float* qs = sm;            // [hd]
     float* red = sm + hd;      // [16]
     float* part = red + 16;    // [256]
@@ -551,6 +593,22 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
     __shared__ float ws1[16], wsT[16];
     __shared__ int s_tok;
     const int b = blockIdx.x;
+    const int64_t orow = a.out_row ? a.out_row[b] : b;
+    if (finished[b] != 0) {
+        // a finished sequence keeps emitting eos_id with log-prob 0 and no longer advances
+        if (threadIdx.x == 0) {
+            last_tok[b] = a.eos_id >= 0 ? a.eos_id : 0;   // a parked row still feeds a valid id through the GEMMs
+            if (tok_out) tok_out[b] = a.eos_id;
+            if (logp_out) logp_out[b] = 0.f;
+            const int st = step_count[b];
+            step_count[b] = st + 1;
+            if (st < out_stride) {
+                if (out_ids) out_ids[orow * out_stride + st] = a.eos_id;
+                if (out_logp) out_logp[orow * out_stride + st] = 0.f;
+            }
+        }
+        return;
+    }
     const float* z = logits + (int64_t)b * ldz;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     ArgMax am = block_argmax(z, V, ared);
@@ -575,7 +633,7 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
     for (int i = 0; i < 16; ++i) { tot1 += ws1[i]; totT += wsT[i]; }
     const int n_gen = gen_count[b];
     if (!greedy) {
-        float u = hash_uniform(a.seed, (uint64_t)(a.seq_base + b), (uint64_t)n_gen);
+        float u = hash_uniform(a.seed, (uint64_t)(a.seq_base + (a.seq_id ? a.seq_id[b] : b)), (uint64_t)n_gen);
         float target = u * totT;
         float cum = 0.f;
         int wsel = -1;
@@ -612,13 +670,12 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int tok = s_tok;
-        float lp = z[tok] - mx - logf(tot1);
-        const bool fin = finished[b] != 0;
-        if (fin) { tok = a.eos_id; lp = 0.f; }
-        else {
-            gen_count[b] = n_gen + 1;
-            if (a.eos_id >= 0 && tok == a.eos_id) finished[b] = 1;
+        const int tok = s_tok;
+        const float lp = z[tok] - mx - logf(tot1);
+        gen_count[b] = n_gen + 1;
+        if ((a.eos_id >= 0 && tok == a.eos_id) || (a.gen_limit && n_gen + 1 >= a.gen_limit[b])) {
+            finished[b] = 1;
+            if (a.out_len) a.out_len[orow] = n_gen + 1;
         }
         last_tok[b] = tok;
         seq_len[b] = seq_len[b] + 1;
@@ -627,8 +684,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
         const int st = step_count[b];
         step_count[b] = st + 1;
         if (st < out_stride) {
-            if (out_ids) out_ids[(int64_t)b * out_stride + st] = tok;
-            if (out_logp) out_logp[(int64_t)b * out_stride + st] = lp;
+            if (out_ids) out_ids[orow * out_stride + st] = tok;
+            if (out_logp) out_logp[orow * out_stride + st] = lp;
         }
     }
 }

@@ -80,6 +80,11 @@ struct SampleArgs {
     int64_t seq_base;
     float temperature;
     int eos_id;
+    // per-slot indirections of the queue mode (all dev, all optional):
+    const int* out_row = nullptr;     // row of out_ids / out_logp that slot b writes (default b)
+    const int* seq_id = nullptr;      // sequence id of slot b for the uniform draw, added to seq_base (default b)
+    const int* gen_limit = nullptr;   // slot b finishes after this many generated tokens (default: never)
+    int* out_len = nullptr;           // out_len[out_row[b]] = tokens generated, written when slot b finishes
 };
 
 // basic kernels (rl_basic.hip)
@@ -87,13 +92,18 @@ void k_fill_i32(int* p, int v, int64_t n, hipStream_t s);
 void k_fill_f32(float* p, float v, int64_t n, hipStream_t s);
 void k_rope_table(float2* tab, int max_seq, int hd, float base, hipStream_t s);
 void k_set_pages(int* block_table, int mpps, const int* triples_host, int n_triples, hipStream_t s);
-void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, int* cur_tok, int* tok_pos,
-                  int* tok_slot, int B, hipStream_t s);
-void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_start, const int* row_len,
-                   const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot, int* tok_tgt, int nrows,
-                   hipStream_t s);
+void k_step_begin(const int* tok_in, const int* last_tok, const int* seq_len, const int* finished, int* cur_tok,
+                  int* tok_pos, int* tok_slot, int B, hipStream_t s);
+void k_pack_tokens(const int* ids, int ld_ids, const int* seq_first, const int* row_slot, const int* row_start,
+                   const int* row_len, const int* full_len, int align, int* tok_ids, int* tok_pos, int* tok_slot,
+                   int* tok_tgt, int nrows, hipStream_t s);
 void k_prefill_state(const int* ids, int ld_ids, const int* row_len, int* last_tok, int* seq_len, int* gen_count,
                      int* finished, int* step_count, int B, hipStream_t s);
+// State of n freshly prefilled slots: slot row_slot[i] starts sequence seq_first[i] (row of ids, also its output
+// row and sequence id) of prompt length row_len[i], limited to limit[i] generated tokens.
+void k_prefill_state_slots(const int* ids, int ld_ids, int n, const int* seq_first, const int* row_slot,
+                           const int* row_len, const int* limit, int* last_tok, int* seq_len, int* gen_count,
+                           int* finished, int* step_count, int* out_row, int* seq_id, int* gen_limit, hipStream_t s);
 void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, float* x, int* errflag, hipStream_t s);
 void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s);
 void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,

@@ -32,7 +32,8 @@ struct Layout {
     size_t x, h, qkv, q, kbuf, vbuf, attn, ffn, logits, rope, block_table;
     size_t last_tok, seq_len, gen_count, finished, cur_tok, step_count;
     size_t tok_ids, tok_pos, tok_slot, tok_tgt;
-    size_t seq_first, row_start, row_len, full_len, d_seq_len, d_prompt_len, errflag;
+    size_t seq_first, row_start, row_len, full_len, row_slot, d_seq_len, d_prompt_len, errflag;
+    size_t out_row, seq_id, gen_limit;   // queue mode: per-slot output row, sequence id, token limit
     size_t splitk, attn_part, attn_ml, lse_part, z_tgt, blocks;
     size_t total;
     int rows, logit_rows, mpps, nqkv, vt_cap, max_blocks;
@@ -87,6 +88,10 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.row_start = take((size_t)c.max_batch * 4);
     L.row_len = take((size_t)c.max_batch * 4);
     L.full_len = take((size_t)c.max_batch * 4);
+    L.row_slot = take((size_t)c.max_batch * 4);
+    L.out_row = take((size_t)c.max_batch * 4);
+    L.seq_id = take((size_t)c.max_batch * 4);
+    L.gen_limit = take((size_t)c.max_batch * 4);
     L.d_seq_len = take((size_t)c.max_batch * 4);
     L.d_prompt_len = take((size_t)c.max_batch * 4);
     L.errflag = take(256);
@@ -174,7 +179,9 @@ struct rl_ctx {
     hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     // sequences
     int B = 0;                       // live sequences (0 = no prefill yet)
-    std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len)
+    std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len; an upper bound in queue mode)
+    std::vector<int> cap;            // queue mode: most tokens slot b's cache will ever hold (0 = classic mode: max_seq, checked)
+    std::vector<char> parked;        // queue mode: slot is free or known to have finished: no pages, no growth
     std::vector<std::vector<int>> pages;
     std::vector<int> free_pages;
     // captured decode step (rollout_generate on a non-default stream, tuned kernels)
@@ -185,9 +192,11 @@ struct rl_ctx {
         int64_t base;
         float temp;
         hipStream_t s;
+        const void* out_len = nullptr;   // non-null: queue mode (per-slot output rows, ids, limits)
         bool operator==(const GraphKey& o) const {
             return B == o.B && G == o.G && impl == o.impl && eos == o.eos && out_ids == o.out_ids &&
-                   out_logp == o.out_logp && seed == o.seed && base == o.base && temp == o.temp && s == o.s;
+                   out_logp == o.out_logp && seed == o.seed && base == o.base && temp == o.temp && s == o.s &&
+                   out_len == o.out_len;
         }
     } gkey{};
     hipGraphExec_t gexec = nullptr;
@@ -224,6 +233,14 @@ static void release_all_pages(rl_ctx* c) {
     for (int64_t p = c->cfg.n_pages - 1; p >= 0; --p) c->free_pages.push_back((int)p);
     for (auto& v : c->pages) v.clear();
     std::fill(c->cached.begin(), c->cached.end(), 0);
+    std::fill(c->cap.begin(), c->cap.end(), 0);
+    std::fill(c->parked.begin(), c->parked.end(), 0);
+}
+
+static void release_slot_pages(rl_ctx* c, int b) {
+    for (int p : c->pages[b]) c->free_pages.push_back(p);
+    c->pages[b].clear();
+    c->cached[b] = 0;
 }
 
 // Make sure every live slot b can hold need[b] tokens; new block-table entries are pushed to the device.
@@ -462,6 +479,7 @@ static bool fast_path_supported(const rl_model_cfg& m) {
 // are marked; the plain path packs densely.
 struct Chunk {
     std::vector<int> rows_b, starts, lens, full;
+    std::vector<int> slots;   // cache slot of each row; empty = the row index itself
     int n = 0;          // rows in the list, padding included
     int max_ctx = 1;
     int nblocks = 0;    // 32-query blocks (tuned path)
@@ -494,6 +512,8 @@ static int pack_chunk(rl_ctx* c, const int* ids, int ld_ids, Chunk& ch, bool tar
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_start), ch.starts.data(), nb, hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_len), ch.lens.data(), nb, hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.full_len), ch.full.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_slot), (ch.slots.empty() ? ch.rows_b : ch.slots).data(), nb,
+                           hipMemcpyHostToDevice, s));
     std::vector<int4> blocks;
     if (c->impl == 1) {
         // one workgroup per 32-query block; long (late) blocks first so the tail of the grid is short work
@@ -510,8 +530,8 @@ static int pack_chunk(rl_ctx* c, const int* ids, int ld_ids, Chunk& ch, bool tar
     }
     // the host vectors may be reused by the caller right after this returns
     HIP_TRY(hipStreamSynchronize(s));
-    k_pack_tokens(ids, ld_ids, c->at<int>(L.seq_first), c->at<int>(L.row_start), c->at<int>(L.row_len),
-                  c->at<int>(L.full_len), pack_align(c), c->at<int>(L.tok_ids), c->at<int>(L.tok_pos),
+    k_pack_tokens(ids, ld_ids, c->at<int>(L.seq_first), c->at<int>(L.row_slot), c->at<int>(L.row_start),
+                  c->at<int>(L.row_len), c->at<int>(L.full_len), pack_align(c), c->at<int>(L.tok_ids), c->at<int>(L.tok_pos),
                   c->at<int>(L.tok_slot), targets ? c->at<int>(L.tok_tgt) : nullptr, (int)ch.rows_b.size(), s);
     return RL_OK;
 }
@@ -557,6 +577,8 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
     c->geo = KvGeom{cfg->n_kv_heads, cfg->head_dim, cfg->page_tokens, cfg->n_pages};
     c->impl = fast_path_supported(*cfg) ? 1 : 0;
     c->cached.assign(cfg->max_batch, 0);
+    c->cap.assign(cfg->max_batch, 0);
+    c->parked.assign(cfg->max_batch, 0);
     c->pages.assign(cfg->max_batch, {});
     release_all_pages(c);
     hipStream_t s = nullptr;
@@ -666,31 +688,44 @@ int rollout_prefill(rl_ctx* c, const int32_t* prompt_ids, const int32_t* prompt_
 }
 
 static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* tok_in, int32_t* tok_out,
-                            float* logp_out, int32_t* out_ids, float* out_logp, int out_stride, hipStream_t s) {
+                            float* logp_out, int32_t* out_ids, float* out_logp, int out_stride, hipStream_t s,
+                            int32_t* queue_out_len = nullptr) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const int B = c->B;
     std::vector<int> need(B);
     int max_ctx = 1;
     for (int b = 0; b < B; ++b) {
-        if (c->cached[b] + 1 > m.max_seq) return fail(RL_EINVAL, "sequence %d would exceed max_seq=%d", b, m.max_seq);
-        need[b] = c->cached[b] + 1;
+        if (c->parked[b]) { need[b] = c->cached[b]; continue; }
+        if (c->cap[b] > 0) {
+            // queue mode: the host's count is an upper bound (a row may have finished unseen); never past the row's cap
+            need[b] = std::min(c->cached[b] + 1, c->cap[b]);
+        } else {
+            if (c->cached[b] + 1 > m.max_seq) return fail(RL_EINVAL, "sequence %d would exceed max_seq=%d", b, m.max_seq);
+            need[b] = c->cached[b] + 1;
+        }
         max_ctx = std::max(max_ctx, need[b]);
     }
     int rc = ensure_pages(c, need, s);
     if (rc) return rc;
-    k_step_begin(tok_in, c->at<int>(L.last_tok), c->at<int>(L.seq_len), c->at<int>(L.cur_tok), c->at<int>(L.tok_pos),
-                 c->at<int>(L.tok_slot), B, s);
+    k_step_begin(tok_in, c->at<int>(L.last_tok), c->at<int>(L.seq_len), c->at<int>(L.finished), c->at<int>(L.cur_tok),
+                 c->at<int>(L.tok_pos), c->at<int>(L.tok_slot), B, s);
     k_embed(m.dtype, c->at<int>(L.cur_tok), B, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
             c->at<int>(L.errflag), s);
     if (!run_layers(c, c->policy, B, true, true, max_ctx, 0, s))
         k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
     lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
     SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
+    if (queue_out_len) {
+        a.out_row = c->at<int>(L.out_row);
+        a.seq_id = c->at<int>(L.seq_id);
+        a.gen_limit = c->at<int>(L.gen_limit);
+        a.out_len = queue_out_len;
+    }
     k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
              c->at<int>(L.gen_count), c->at<int>(L.finished), c->at<int>(L.step_count), tok_out, logp_out, out_ids,
              out_logp, out_stride, s);
-    for (int b = 0; b < B; ++b) c->cached[b] += 1;
+    for (int b = 0; b < B; ++b) c->cached[b] = need[b];
     return RL_OK;
 }
 
@@ -764,6 +799,162 @@ int rollout_generate(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prom
         }
     }
     if (out_len) k_out_len(c->at<int>(c->L.gen_count), out_len, B, s);
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+// ---- queue mode: more prompts than slots, per-prompt token limits, early stops (Section 3.2: generation
+// lengths vary widely, so work is handed out dynamically instead of in fixed batches).
+//
+// Prefill the prompts `rows` (rows of the [*, Pmax] id matrix) into the cache slots `slots` while the other
+// slots keep their state: cache tokens [0, P-1), then set the slot's state (last prompt token as next
+// input, counters zero, output row / sequence id = the prompt's row, its token limit).
+static int prefill_rows(rl_ctx* c, const int32_t* ids, int Pmax, const int32_t* plen, const int32_t* limit,
+                        const std::vector<int>& rows, const std::vector<int>& slots, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    const Layout& L = c->L;
+    const int n = (int)rows.size();
+    if (n == 0) return RL_OK;
+    std::vector<int> need(m.max_batch);
+    for (int b = 0; b < m.max_batch; ++b) need[b] = c->cached[b];
+    for (int i = 0; i < n; ++i) need[slots[i]] = plen[rows[i]] - 1;
+    int rc = ensure_pages(c, need, s);
+    if (rc) return rc;
+    const int al = pack_align(c);
+    for (int i0 = 0; i0 < n;) {
+        Chunk ch;
+        int i1 = i0;
+        while (i1 < n) {
+            const int len = plen[rows[i1]] - 1, alen = (len + al - 1) / al * al;
+            if (ch.n + alen > m.max_chunk_tokens && ch.n > 0) break;
+            ch.rows_b.push_back(rows[i1]);
+            ch.slots.push_back(slots[i1]);
+            ch.starts.push_back(ch.n);
+            ch.lens.push_back(len);
+            ch.full.push_back(len);
+            ch.n += alen;
+            ch.max_ctx = std::max(ch.max_ctx, len);
+            ++i1;
+        }
+        i0 = i1;
+        if (ch.n > 0) {
+            if ((rc = pack_chunk(c, ids, Pmax, ch, false, s))) return rc;
+            k_embed(m.dtype, c->at<int>(L.tok_ids), ch.n, c->policy.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+                    c->at<int>(L.errflag), s);
+            run_layers(c, c->policy, ch.n, false, true, ch.max_ctx, ch.nblocks, s);
+        }
+    }
+    std::vector<int> pl(n), lim(n);
+    for (int i = 0; i < n; ++i) { pl[i] = plen[rows[i]]; lim[i] = limit[rows[i]]; }
+    const size_t nb = (size_t)n * sizeof(int);
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.seq_first), rows.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_slot), slots.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.row_len), pl.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.full_len), lim.data(), nb, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));   // the host vectors go out of scope
+    k_prefill_state_slots(ids, Pmax, n, c->at<int>(L.seq_first), c->at<int>(L.row_slot), c->at<int>(L.row_len),
+                          c->at<int>(L.full_len), c->at<int>(L.last_tok), c->at<int>(L.seq_len), c->at<int>(L.gen_count),
+                          c->at<int>(L.finished), c->at<int>(L.step_count), c->at<int>(L.out_row), c->at<int>(L.seq_id),
+                          c->at<int>(L.gen_limit), s);
+    for (int i = 0; i < n; ++i) {
+        const int b = slots[i];
+        c->cached[b] = plen[rows[i]] - 1;
+        c->cap[b] = plen[rows[i]] - 1 + limit[rows[i]];
+        c->parked[b] = 0;
+    }
+    return RL_OK;
+}
+
+static const int kQueueBurst = 8;   // decode steps between two looks at the finished flags
+
+int rollout_generate_queue(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prompt_ids, const int32_t* prompt_len,
+                           const int32_t* gen_limit, int32_t Q, int32_t Pmax, int32_t Gmax, int32_t* out_ids,
+                           int32_t* out_len, float* out_logp, void* stream) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    int rc = check_sample(sample);
+    if (rc) return rc;
+    if (!prompt_ids || !prompt_len || !gen_limit || !out_ids || !out_len) return fail(RL_EINVAL, "NULL argument");
+    const rl_model_cfg& m = c->cfg;
+    if (Q < 1 || Pmax < 1 || Gmax < 1) return fail(RL_EINVAL, "Q, Pmax and Gmax must be >= 1");
+    for (int q = 0; q < Q; ++q) {
+        if (prompt_len[q] < 1 || prompt_len[q] > Pmax)
+            return fail(RL_EINVAL, "prompt_len[%d]=%d outside [1, Pmax]", q, prompt_len[q]);
+        if (gen_limit[q] < 1 || gen_limit[q] > Gmax)
+            return fail(RL_EINVAL, "gen_limit[%d]=%d outside [1, Gmax]", q, gen_limit[q]);
+        if (prompt_len[q] - 1 + gen_limit[q] > m.max_seq)
+            return fail(RL_EINVAL, "prompt_len[%d] - 1 + gen_limit = %d exceeds max_seq=%d", q,
+                        prompt_len[q] - 1 + gen_limit[q], m.max_seq);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const Layout& L = c->L;
+    // entries past a row's length read eos_id (-1 when there is none) / log-prob 0
+    k_fill_i32(out_ids, sample->eos_id, (int64_t)Q * Gmax, s);
+    k_fill_i32(out_len, 0, Q, s);
+    if (out_logp) k_fill_f32(out_logp, 0.f, (int64_t)Q * Gmax, s);
+    c->B = 0;
+    release_all_pages(c);
+    const int nslots = std::min<int>(Q, m.max_batch);
+    std::vector<int> slot_row(nslots, -1), rows, slots;
+    int next = 0, live = 0;
+    for (int b = 0; b < nslots; ++b) { rows.push_back(next); slots.push_back(b); slot_row[b] = next++; }
+    if ((rc = prefill_rows(c, prompt_ids, Pmax, prompt_len, gen_limit, rows, slots, s))) { rollout_reset(c); return rc; }
+    live = nslots;
+    c->B = nslots;
+    bool profiling = false;
+    for (int k = 0; k < RL_K_COUNT; ++k) profiling = profiling || c->prof_on[k] != 0;
+    const bool graph = c->impl == 1 && s != nullptr && c->use_graph && !profiling;
+    std::vector<int> fin(nslots), slen(nslots), need(nslots);
+    while (live > 0) {
+        // reserve the burst's pages up front: nothing is allocated between two looks at the flags
+        for (int b = 0; b < nslots; ++b)
+            need[b] = c->parked[b] ? c->cached[b] : std::min(c->cached[b] + kQueueBurst, c->cap[b]);
+        if ((rc = ensure_pages(c, need, s))) { rollout_reset(c); return rc; }
+        if (graph) {
+            rl_ctx::GraphKey key{nslots, Gmax, c->impl, sample->eos_id, out_ids, out_logp, sample->seed,
+                                 sample->seq_id_base, sample->temperature, s, out_len};
+            if (!c->gexec || !(key == c->gkey)) {
+                if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+                std::vector<int> saved = c->cached;
+                HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+                rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids, out_logp, Gmax, s, out_len);
+                hipGraph_t g = nullptr;
+                hipError_t e = hipStreamEndCapture(s, &g);
+                c->cached = saved;
+                if (rc) { if (g) (void)hipGraphDestroy(g); rollout_reset(c); return rc; }
+                if (e != hipSuccess) { rollout_reset(c); return fail(RL_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e)); }
+                e = hipGraphInstantiate(&c->gexec, g, nullptr, nullptr, 0);
+                (void)hipGraphDestroy(g);
+                if (e != hipSuccess) { c->gexec = nullptr; rollout_reset(c); return fail(RL_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+                c->gkey = key;
+            }
+            for (int n = 0; n < kQueueBurst; ++n) HIP_TRY(hipGraphLaunch(c->gexec, s));
+            for (int b = 0; b < nslots; ++b) c->cached[b] = need[b];
+        } else {
+            for (int n = 0; n < kQueueBurst; ++n)
+                if ((rc = decode_step_impl(c, sample, nullptr, nullptr, nullptr, out_ids, out_logp, Gmax, s, out_len))) {
+                    rollout_reset(c);
+                    return rc;
+                }
+        }
+        // which slots have finished, and how long the others' caches really are
+        HIP_TRY(hipMemcpyAsync(fin.data(), c->at<int>(L.finished), (size_t)nslots * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(slen.data(), c->at<int>(L.seq_len), (size_t)nslots * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        rows.clear();
+        slots.clear();
+        for (int b = 0; b < nslots; ++b) {
+            if (slot_row[b] < 0) continue;
+            if (!fin[b]) { c->cached[b] = slen[b]; continue; }
+            // finished: its pages go back to the pool; the slot takes the next queued prompt, if any
+            release_slot_pages(c, b);
+            c->parked[b] = 1;
+            slot_row[b] = -1;
+            --live;
+            if (next < Q) { rows.push_back(next); slots.push_back(b); slot_row[b] = next++; ++live; }
+        }
+        if ((rc = prefill_rows(c, prompt_ids, Pmax, prompt_len, gen_limit, rows, slots, s))) { rollout_reset(c); return rc; }
+    }
+    rollout_reset(c);   // nothing stays live after a queue run
     HIP_TRY(hipGetLastError());
     return RL_OK;
 }

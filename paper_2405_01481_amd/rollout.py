@@ -66,6 +66,7 @@ def lib():
         L.rollout_prefill.argtypes = [vp, vp, vp, i32, i32, vp]
         L.rollout_decode_step.argtypes = [vp, C.POINTER(rl_sample_cfg), vp, vp, vp, vp]
         L.rollout_generate.argtypes = [vp, C.POINTER(rl_sample_cfg), vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        L.rollout_generate_queue.argtypes = [vp, C.POINTER(rl_sample_cfg), vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
         L.score_logprobs_kl.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, f32,
                                         vp, vp, vp, vp, vp]
         L.rollout_check.argtypes = [vp, vp]
@@ -202,6 +203,14 @@ class Rollout:
         B, Pmax = prompt_ids.shape
         _chk(lib().rollout_generate(self.h, C.byref(sample), _ptr(prompt_ids), plp, B, Pmax, G, _ptr(out_ids),
                                     _ptr(out_len), _ptr(out_logp), _stream()))
+
+    def rollout_generate_queue(self, sample: rl_sample_cfg, prompt_ids: torch.Tensor, prompt_len, gen_limit, Gmax,
+                               out_ids, out_len, out_logp=None):
+        pl, plp = _host_i32(prompt_len)
+        gl, glp = _host_i32(gen_limit)
+        Q, Pmax = prompt_ids.shape
+        _chk(lib().rollout_generate_queue(self.h, C.byref(sample), _ptr(prompt_ids), plp, glp, Q, Pmax, Gmax,
+                                          _ptr(out_ids), _ptr(out_len), _ptr(out_logp), _stream()))
 
     def score_logprobs_kl(self, policy: Weights, reference, ids: torch.Tensor, seq_len, prompt_len, kl_coef,
                           logp_policy=None, logp_ref=None, kl=None, kl_penalty=None):

@@ -318,6 +318,75 @@ def test_reference_streamed_from_host_matches_resident(shape, impl):
     ro.close()
 
 
+@pytest.mark.parametrize("shape", [MINI128, MINI32F], ids=lambda s: s.name)
+def test_queue_mode_recycles_slots_and_matches_batch_generation(shape):
+    """rollout_generate_queue: 14 prompts through 4 slots with per-prompt token limits (long-tailed), a page
+    pool that only fits four live sequences (so pages must be recycled), on a side stream (captured step
+    for the tuned kernels).  Every row must equal, bit for bit, what rollout_generate gives the same
+    prompt in an ordinary batch with the same sequence id, satisfy the oracle along its trajectory, and
+    stop at its limit; then the same with an end-of-sequence id that some rows really emit."""
+    Q, slots, Pmax, Gmax = 14, 4, 40, 21
+    wp = synth.make_weights(shape, 1, DEV)
+    Wp = R.Weights(wp)
+    per_seq = (Pmax - 1 + Gmax + 15) // 16
+    cfg = R.make_cfg(shape, slots, Pmax + Gmax, n_pages=slots * per_seq, max_chunk_tokens=96)
+    ro = R.Rollout(cfg, Wp, DEV)
+    mp = O.Model(shape, synth.weights_for_oracle(wp))
+    ids, lens = synth.make_prompts(shape.vocab, Q, Pmax, 9, 51)
+    rng = np.random.default_rng(52)
+    limit = np.minimum(Gmax, 1 + rng.geometric(0.12, Q)).astype(np.int32)     # long tail, capped
+    limit[3], limit[7] = Gmax, 1
+    d_ids = torch.tensor(ids, device=DEV)
+    lt, cd = _tol(shape)
+    side = torch.cuda.Stream()
+
+    def run_queue(eos):
+        out = torch.full((Q, Gmax), -7, dtype=torch.int32, device=DEV)
+        olen = torch.full((Q,), -7, dtype=torch.int32, device=DEV)
+        olp = torch.full((Q, Gmax), 9.0, dtype=torch.float32, device=DEV)
+        with torch.cuda.stream(side):
+            ro.rollout_generate_queue(R.sample_cfg(6, 1.0, eos, 0), d_ids, lens, limit, Gmax, out, olen, olp)
+            side.synchronize()
+        ro.rollout_check()
+        return out.cpu().numpy(), olen.cpu().numpy(), olp.cpu().numpy()
+
+    g, glen, glp = run_queue(-1)
+    assert np.array_equal(glen, limit)
+    for q in range(Q):
+        assert np.all(g[q, limit[q]:] == -1) and np.all(glp[q, limit[q]:] == 0.0)
+        assert np.all(g[q, :limit[q]] >= 0)
+    # the same prompts in ordinary batches of four, sequence ids q
+    for q0 in range(0, Q, slots):
+        n = min(slots, Q - q0)
+        b_ids, _, b_lp = _generate(ro, ids[q0:q0 + n], lens[q0:q0 + n], Gmax, 1.0, seed=6, base=q0)
+        for i in range(n):
+            L = limit[q0 + i]
+            assert np.array_equal(b_ids[i, :L], g[q0 + i, :L]), (q0 + i)
+            assert np.array_equal(b_lp[i, :L], glp[q0 + i, :L]), (q0 + i)
+    # the oracle along each trajectory (rows of several lengths)
+    prompts = [ids[q, :lens[q]] for q in range(Q)]
+    for q in (0, 3, 7, 11, 13):
+        verify_rollout(mp, prompts, g, glp, 1.0, 6, 0, cd, lt, rows=[q], steps=range(limit[q]))
+
+    # an end-of-sequence id that really occurs: row 3's fifth token
+    eos = int(g[3, 4])
+    e, elen, elp = run_queue(eos)
+    for q in range(Q):
+        hit = np.where(g[q, :limit[q]] == eos)[0]
+        want = int(hit[0]) + 1 if len(hit) else int(limit[q])
+        assert elen[q] == want, (q, elen[q], want)
+        assert np.array_equal(e[q, :want], g[q, :want]) and np.array_equal(elp[q, :want], glp[q, :want])
+        assert np.all(e[q, want:] == eos) and np.all(elp[q, want:] == 0.0)
+    assert elen[3] == 5
+    # argument errors
+    bad = limit.copy(); bad[0] = Gmax + 1
+    with pytest.raises(R.RolloutError):
+        ro.rollout_generate_queue(R.sample_cfg(6, 1.0, -1, 0), d_ids, lens, bad, Gmax,
+                                  torch.zeros(Q, Gmax, dtype=torch.int32, device=DEV),
+                                  torch.zeros(Q, dtype=torch.int32, device=DEV))
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
