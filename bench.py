@@ -89,6 +89,69 @@ def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperatu
                       f"float64 numpy oracle with KV cache, {dt:.1f} s"}
 
 
+def response_limits(Q, cap, seed):
+    """Synthetic response lengths: log-normal body with a long tail, mean about 351 tokens (the mean the paper
+    reports for its 70B actor's first PPO steps, Section 5.1's 405B paragraph), clipped to [16, cap]."""
+    rng = np.random.default_rng(seed)
+    x = rng.lognormal(mean=np.log(351.0) - 0.5 * 0.8 ** 2, sigma=0.8, size=Q)
+    return np.clip(np.rint(x), 16, cap).astype(np.int32)
+
+
+def queue_bench(args, wl, shape, ro, B, Pmax, Pmin, dev):
+    """Useful generated tokens per second on a variable-length workload: dynamic slot refill against fixed
+    batches of B that each run until their longest row is done (what a fixed-batch engine does)."""
+    Q, Gcap = args.queue, args.gen or 1024
+    ids_np, plen = synth.make_prompts(shape.vocab, Q, Pmax, Pmin, wl.prompt_seed)
+    limit = response_limits(Q, Gcap, wl.sample_seed + 1)
+    ids = torch.tensor(ids_np, device=dev)
+    out = torch.zeros(Q, Gcap, dtype=torch.int32, device=dev)
+    olen = torch.zeros(Q, dtype=torch.int32, device=dev)
+    olp = torch.zeros(Q, Gcap, dtype=torch.float32, device=dev)
+    sc = R.sample_cfg(wl.sample_seed, wl.temperature)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(stream)
+    useful = int(limit.sum())
+
+    def run_queue():
+        ro.rollout_generate_queue(sc, ids, plen, limit, Gcap, out, olen, olp)
+
+    def run_fixed():
+        for q0 in range(0, Q, B):
+            n = min(B, Q - q0)
+            G = int(limit[q0:q0 + n].max())
+            sb = R.sample_cfg(wl.sample_seed, wl.temperature, -1, q0)
+            ro.rollout_generate(sb, ids[q0:q0 + n], plen[q0:q0 + n], G, out[q0:q0 + n, :G].contiguous(), None, None)
+
+    res = {}
+    for name, fn in (("queue", run_queue), ("fixed_batches", run_fixed)):
+        if args.warmup:
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / args.steps
+    ro.rollout_check()
+    assert np.array_equal(olen.cpu().numpy(), limit)
+    line = {
+        "metric": "useful generated tokens/s, variable-length responses (1 GPU)",
+        "value": useful / res["queue"], "unit": "generated tokens/s (prefill + decode, dynamic slot refill)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["queue"] * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, fp16 activations/KV, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": args.workload + "_queue", "shape": shape.name, "layers": shape.n_layers, "prompts": Q,
+                   "slots": B, "prompt": [int(plen.min()), int(plen.max())],
+                   "response_limit": {"mean": float(limit.mean()), "p50": float(np.median(limit)),
+                                      "max": int(limit.max()), "cap": Gcap}},
+        "fixed_batches_tok_s": useful / res["fixed_batches"], "fixed_batches_s": res["fixed_batches"],
+        "queue_s": res["queue"], "speedup_vs_fixed_batches": res["fixed_batches"] / res["queue"],
+    }
+    print(json.dumps(line))
+    ro.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +169,10 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run three device copies of 1 GiB (read 1 GiB, write 1 GiB each): the known-size "
                          "kernel that HBM-traffic counters of a rocprofv3 --pmc run are scaled by")
+    ap.add_argument("--queue", type=int, default=0, metavar="Q",
+                    help="variable-length generation instead of the headline step: Q prompts with response limits "
+                         "from a long-tailed distribution (mean about 351 tokens), run once through "
+                         "rollout_generate_queue and once as fixed batches that wait for their longest row")
     ap.add_argument("--ref-host", action="store_true",
                     help="keep the reference weights in pinned host memory and stream them layer by layer while "
                          "scoring (the 70B configuration's residency); reported in config.reference")
@@ -142,6 +209,8 @@ def main():
 
     wp = synth.make_weights(shape, wl.policy_seed, dev)
     wr = synth.make_weights(shape, wl.ref_seed, dev)
+    if args.queue and not args.gen:
+        G = 1024                     # cap of the synthetic response lengths
     Lmax = Pmax + G
     cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=max(Lmax, args.chunk))
     if args.ref_host:
@@ -156,6 +225,8 @@ def main():
     ro = R.Rollout(cfg, Wp, dev)
     if args.impl >= 0:
         ro.rollout_set_impl(args.impl)
+    if args.queue:
+        return queue_bench(args, wl, shape, ro, B, Pmax, Pmin, dev)
     ids_np, plen = synth.make_prompts(shape.vocab, B, Pmax, Pmin, wl.prompt_seed)
     ids = torch.tensor(ids_np, device=dev)
     out_ids = torch.zeros(B, G, dtype=torch.int32, device=dev)
