@@ -865,7 +865,8 @@ static int prefill_rows(rl_ctx* c, const int32_t* ids, int Pmax, const int32_t* 
     return RL_OK;
 }
 
-static const int kQueueBurst = 8;   // decode steps between two looks at the finished flags
+static const int kQueueBurst = 8;       // decode steps between two looks at the finished flags
+static const int kQueueRefillMin = 16;  // free slots to collect before a refill (fewer if fewer prompts wait)
 
 int rollout_generate_queue(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* prompt_ids, const int32_t* prompt_len,
                            const int32_t* gen_limit, int32_t Q, int32_t Pmax, int32_t Gmax, int32_t* out_ids,
@@ -894,7 +895,7 @@ int rollout_generate_queue(rl_ctx* c, const rl_sample_cfg* sample, const int32_t
     c->B = 0;
     release_all_pages(c);
     const int nslots = std::min<int>(Q, m.max_batch);
-    std::vector<int> slot_row(nslots, -1), rows, slots;
+    std::vector<int> slot_row(nslots, -1), rows, slots, free_slots;
     int next = 0, live = 0;
     for (int b = 0; b < nslots; ++b) { rows.push_back(next); slots.push_back(b); slot_row[b] = next++; }
     if ((rc = prefill_rows(c, prompt_ids, Pmax, prompt_len, gen_limit, rows, slots, s))) { rollout_reset(c); return rc; }
@@ -940,19 +941,32 @@ int rollout_generate_queue(rl_ctx* c, const rl_sample_cfg* sample, const int32_t
         HIP_TRY(hipMemcpyAsync(fin.data(), c->at<int>(L.finished), (size_t)nslots * 4, hipMemcpyDeviceToHost, s));
         HIP_TRY(hipMemcpyAsync(slen.data(), c->at<int>(L.seq_len), (size_t)nslots * 4, hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
-        rows.clear();
-        slots.clear();
         for (int b = 0; b < nslots; ++b) {
             if (slot_row[b] < 0) continue;
             if (!fin[b]) { c->cached[b] = slen[b]; continue; }
-            // finished: its pages go back to the pool; the slot takes the next queued prompt, if any
+            // finished: its pages go back to the pool and the slot waits, parked, for a queued prompt
             release_slot_pages(c, b);
             c->parked[b] = 1;
             slot_row[b] = -1;
             --live;
-            if (next < Q) { rows.push_back(next); slots.push_back(b); slot_row[b] = next++; ++live; }
+            free_slots.push_back(b);
         }
-        if ((rc = prefill_rows(c, prompt_ids, Pmax, prompt_len, gen_limit, rows, slots, s))) { rollout_reset(c); return rc; }
+        // Refill in groups: a prefill of one or two prompts runs the large-M kernels far below their rate,
+        // while an idle slot costs only its share of a decode step that streams the weights anyway.
+        const int waiting = Q - next;
+        if (waiting > 0 && ((int)free_slots.size() >= std::min(kQueueRefillMin, waiting) || live == 0)) {
+            rows.clear();
+            slots.clear();
+            while (next < Q && !free_slots.empty()) {
+                const int b = free_slots.back();
+                free_slots.pop_back();
+                rows.push_back(next);
+                slots.push_back(b);
+                slot_row[b] = next++;
+                ++live;
+            }
+            if ((rc = prefill_rows(c, prompt_ids, Pmax, prompt_len, gen_limit, rows, slots, s))) { rollout_reset(c); return rc; }
+        }
     }
     rollout_reset(c);   // nothing stays live after a queue run
     HIP_TRY(hipGetLastError());
