@@ -188,6 +188,14 @@ int score_logprobs_kl(rl_ctx* ctx, const rl_weights* policy, const rl_weights* r
  * if the stream is in error. */
 int rollout_check(rl_ctx* ctx, void* stream);
 
+/* Generate with another weight set from now on (Section 3.1 / 3.2: the actor's weights change every PPO
+ * step and the generation engine has to pick them up).  The library uses weights in place, so there is
+ * nothing to copy: values updated IN PLACE at the same addresses need no call at all; this call swaps the
+ * pointers (same shapes and dtype, location 0), drops all live sequences -- their caches belong to the old
+ * weights -- and the captured decode step.  The caller must have waited for work that uses the old set.
+ * Errors: RL_EINVAL. */
+int rollout_set_policy(rl_ctx* ctx, const rl_weights* policy);
+
 /* Forget all sequences and return every page to the pool. */
 int rollout_reset(rl_ctx* ctx);
 void rollout_destroy(rl_ctx* ctx);

@@ -622,6 +622,17 @@ int rollout_reset(rl_ctx* c) {
     return RL_OK;
 }
 
+int rollout_set_policy(rl_ctx* c, const rl_weights* policy) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    WeightsHost w;
+    int rc = copy_weights(c->cfg, policy, w, "policy");
+    if (rc) return rc;
+    c->policy = w;
+    // the captured decode step holds the old pointers; caches built with the old weights are void
+    if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return rollout_reset(c);
+}
+
 int rollout_set_impl(rl_ctx* c, int32_t impl) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     if (impl < 0 || impl > 2) return fail(RL_EINVAL, "impl must be 0, 1 or 2");

@@ -70,6 +70,7 @@ def lib():
         L.score_logprobs_kl.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, f32,
                                         vp, vp, vp, vp, vp]
         L.rollout_check.argtypes = [vp, vp]
+        L.rollout_set_policy.argtypes = [vp, C.POINTER(rl_weights)]
         L.rollout_reset.argtypes = [vp]
         L.rollout_destroy.argtypes = [vp]
         L.rollout_destroy.restype = None
@@ -223,6 +224,10 @@ class Rollout:
 
     def rollout_check(self):
         _chk(lib().rollout_check(self.h, _stream()))
+
+    def rollout_set_policy(self, policy: Weights):
+        _chk(lib().rollout_set_policy(self.h, C.byref(policy.struct)))
+        self.policy = policy            # keep the tensors alive
 
     def rollout_reset(self):
         _chk(lib().rollout_reset(self.h))

@@ -387,6 +387,48 @@ def test_queue_mode_recycles_slots_and_matches_batch_generation(shape):
     ro.close()
 
 
+def test_policy_weight_swap_and_in_place_update():
+    """The actor changes every PPO step: rollout_set_policy swaps the weight pointers, an in-place update of
+    the tensors needs no call; either way the next rollout (captured decode step included) must equal that
+    of a fresh context built on the new weights."""
+    shape, B, G = MINI128, 5, 9
+    wa, wb = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
+    Wa, Wb = R.Weights(wa), R.Weights(wb)
+    cfg = R.make_cfg(shape, B, 64)
+    ids, lens = synth.make_prompts(shape.vocab, B, 40, 20, 61)
+    side = torch.cuda.Stream()
+
+    def gen(ro):
+        with torch.cuda.stream(side):
+            r = _generate(ro, ids, lens, G, 1.0, seed=8)
+            side.synchronize()
+        return r
+
+    fresh_b = R.Rollout(cfg, Wb, DEV)
+    want_b = gen(fresh_b)
+    fresh_b.close()
+    ro = R.Rollout(cfg, Wa, DEV)
+    got_a = gen(ro)
+    ro.rollout_set_policy(Wb)
+    got_b = gen(ro)
+    assert np.array_equal(got_b[0], want_b[0]) and np.array_equal(got_b[2], want_b[2])
+    assert not np.array_equal(got_a[0], got_b[0])
+    # in place: overwrite Wb's tensors with A's values, no call; the captured graph must see them
+    for k in ("tok_embed", "final_norm", "lm_head"):
+        wb[k].copy_(wa[k])
+    for la, lb in zip(wa["layers"], wb["layers"]):
+        for k in la:
+            lb[k].copy_(la[k])
+    torch.cuda.synchronize()
+    got_a2 = gen(ro)
+    assert np.array_equal(got_a2[0], got_a[0]) and np.array_equal(got_a2[2], got_a[2])
+    ro.rollout_set_policy(Wa)                                # live sequences are dropped with the old weights
+    with pytest.raises(R.RolloutError) as e:
+        ro.rollout_decode_step(R.sample_cfg())
+    assert e.value.code == R.RL_ESTATE
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
