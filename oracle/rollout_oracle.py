@@ -282,3 +282,40 @@ def score_batch(m_policy: Model, m_ref: Model, ids, seq_len, prompt_len, kl_coef
         lr[b, :L] = score(m_ref, ids[b, :L])
         kl[b, :L] = kl_sampled(lp[b, :L], lr[b, :L], int(prompt_len[b]), L)
     return lp, lr, kl, kl_coef * kl
+
+
+# --------------------------------------------------------------------------
+# critic / reward-model head and the PPO reward (Section 2.2 steps 2-3, Section 3.1)
+# --------------------------------------------------------------------------
+def values(m: Model, value_head, tokens):
+    """Per-token scalar of a critic or reward model: the same decoder body with a [d] -> 1 head in
+    place of the LM head (Section 3.1: the critic is initialised from the reward model and "the reward
+    model and the critic" are served for inference).  v[t] = head . RMSNorm(x_t; g_final), the state
+    after reading token t.  A sequence-level reward is v[L-1]."""
+    x = forward_hidden(m, tokens)
+    h = rmsnorm(x, m.w["final_norm"], m.s.rms_eps)
+    return h @ np.asarray(value_head, F64)
+
+
+def values_batch(m: Model, value_head, ids, seq_len):
+    """[B, Lmax] with zeros past each row's length (the library call's convention)."""
+    ids = np.asarray(ids)
+    out = np.zeros(ids.shape, F64)
+    for b in range(ids.shape[0]):
+        L = int(seq_len[b])
+        out[b, :L] = values(m, value_head, ids[b, :L])
+    return out
+
+
+def ppo_rewards(kl, seq_reward, seq_len, prompt_len, kl_coef):
+    """Per-token PPO reward (Section 2.2 step 3: the reward-model score of the rollout, regularised by
+    the KL penalty towards the reference policy): r[b,t] = -kl_coef * kl[b,t] on response positions
+    [prompt_len, L), plus the sequence's scalar reward on its last token; 0 elsewhere."""
+    kl = np.asarray(kl, F64)
+    r = np.zeros_like(kl)
+    for b in range(kl.shape[0]):
+        L, P = int(seq_len[b]), int(prompt_len[b])
+        r[b, P:L] = -kl_coef * kl[b, P:L]
+        if L > P:
+            r[b, L - 1] += float(seq_reward[b])
+    return r

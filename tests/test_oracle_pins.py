@@ -382,3 +382,60 @@ def test_generator_is_deterministic_and_dtype_exact():
     assert abs(float(a["layers"][0]["attn_norm"].float().mean()) - 1.0) < 2e-2
     ids, lens = synth.make_prompts(100, 5, 20, 10, 3)
     assert ids.shape == (5, 20) and lens.min() >= 10 and lens.max() <= 20 and ids.max() < 100
+
+
+# --------------------------------------------------------------------------- value head and PPO reward
+def _embedding_only_model(shape, seed):
+    """A model whose layers contribute nothing (output and down projections zero): the residual stream
+    after the last layer is exactly the embedding row of each token."""
+    w = synth.weights_for_oracle(synth.make_weights(shape, seed, "cpu"))
+    for lw in w["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["w_down"] = np.zeros_like(lw["w_down"])
+    return O.Model(shape, w), w
+
+
+def test_value_head_closed_form_linearity_and_scale_invariance():
+    s = synth.TINY
+    m, w = _embedding_only_model(s, 5)
+    rng = np.random.default_rng(0)
+    toks = rng.integers(0, s.vocab, 7)
+    head = rng.standard_normal(s.d_model)
+    v = O.values(m, head, toks)
+    # closed form for this model: x_t = E[tok_t], v = sum_j x_j g_j head_j / sqrt(mean x^2 + eps)
+    E = np.asarray(w["tok_embed"], np.float64)[toks]
+    g = np.asarray(w["final_norm"], np.float64)
+    want = (E * g * head).sum(1) / np.sqrt((E * E).mean(1) + s.rms_eps)
+    assert np.allclose(v, want, rtol=1e-12, atol=1e-14)
+    # with the head 1/g the value is sum(x) / rms(x): independent of the gain
+    v1 = O.values(m, 1.0 / g, toks)
+    assert np.allclose(v1, E.sum(1) / np.sqrt((E * E).mean(1) + s.rms_eps), rtol=1e-12)
+    # linear in the head; zero head gives zero; one value per token, causal (a prefix gives a prefix)
+    full, _ = O.Model(s, synth.weights_for_oracle(synth.make_weights(s, 6, "cpu"))), None
+    h2 = rng.standard_normal(s.d_model)
+    a = O.values(full, head, toks)
+    b = O.values(full, h2, toks)
+    assert np.allclose(O.values(full, 2.0 * head - 3.0 * h2, toks), 2.0 * a - 3.0 * b, rtol=1e-10, atol=1e-12)
+    assert np.all(O.values(full, np.zeros(s.d_model), toks) == 0.0)
+    assert np.allclose(O.values(full, head, toks[:4]), a[:4], rtol=1e-10, atol=1e-12)
+    assert not np.allclose(a[1:], a[:-1])                       # really per token
+    # a change of a later token leaves earlier values alone
+    t2 = toks.copy(); t2[5] = (t2[5] + 1) % s.vocab
+    assert np.allclose(O.values(full, head, t2)[:5], a[:5], rtol=1e-10, atol=1e-12)
+    vb = O.values_batch(full, head, np.stack([toks, t2]), [7, 3])
+    assert np.allclose(vb[0], a) and np.all(vb[1, 3:] == 0.0) and np.allclose(vb[1, :3], a[:3], rtol=1e-10, atol=1e-12)
+
+
+def test_ppo_reward_assembly():
+    kl = np.array([[9.0, 9.0, 0.5, -0.25, 1.0, 9.0],
+                   [9.0, 0.1, 0.2, 9.0, 9.0, 9.0],
+                   [9.0, 9.0, 9.0, 9.0, 9.0, 9.0]])
+    lens, plens = [5, 3, 2], [2, 1, 2]
+    r = O.ppo_rewards(kl, [2.0, -1.0, 7.0], lens, plens, 0.1)
+    want = np.zeros_like(kl)
+    want[0, 2:5] = [-0.05, 0.025, -0.1 + 2.0]
+    want[1, 1:3] = [-0.01, -0.02 - 1.0]
+    assert np.allclose(r, want, atol=1e-15)                      # row 2 has no response: all zero
+    # total return of a row = its reward minus coef * sum of kl over the response
+    assert np.isclose(r[0].sum(), 2.0 - 0.1 * (0.5 - 0.25 + 1.0))
+    assert np.all(O.ppo_rewards(kl, [0, 0, 0], lens, plens, 0.0) == 0.0)
