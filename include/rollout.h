@@ -183,6 +183,27 @@ int score_logprobs_kl(rl_ctx* ctx, const rl_weights* policy, const rl_weights* r
                       float* logp_policy, float* logp_ref, float* kl, float* kl_penalty,
                       void* stream);
 
+/* Critic values / reward-model scores (Section 2.2 step 2 and Section 3.1: the reward model and the critic
+ * are decoders of the actor's kind with a scalar head, served for inference on the rollouts).  The same
+ * teacher-forced pass as score_logprobs_kl with a [d_model] -> 1 head in place of the LM head:
+ * values[b,t] = value_head . RMSNorm(x_t; final_norm) for t in [0, L_b), the state after reading token t;
+ * 0 beyond.  A sequence-level reward is values[b, L_b - 1].
+ * model: body weights of this context's shape (lm_head is not read and may be NULL; location 0 or 1);
+ * value_head: dev, [d_model] in the weight dtype; ids: dev int32 [B, Lmax]; seq_len: host int32 [B];
+ * values: dev fp32 [B, Lmax].  Errors: RL_EINVAL, RL_ENOSPACE. */
+int score_values(rl_ctx* ctx, const rl_weights* model, const void* value_head,
+                 const int32_t* ids, const int32_t* seq_len, int32_t B, int32_t Lmax,
+                 float* values, void* stream);
+
+/* Per-token PPO reward (Section 2.2 step 3: the reward-model score of the rollout regularised by the KL
+ * penalty; coefficient 0.003 in Section 3.3): rewards[b,t] = -kl_coef * kl[b,t] on response positions
+ * t in [prompt_len[b], L_b), plus seq_reward[b] on the last token t = L_b - 1; 0 elsewhere.
+ * kl, rewards: dev fp32 [B, Lmax] (kl as written by score_logprobs_kl); seq_reward: dev fp32 [B];
+ * seq_len, prompt_len: host int32 [B].  Errors: RL_EINVAL. */
+int ppo_rewards(rl_ctx* ctx, const float* kl, const float* seq_reward,
+                const int32_t* seq_len, const int32_t* prompt_len, int32_t B, int32_t Lmax,
+                float kl_coef, float* rewards, void* stream);
+
 /* Wait for `stream` and report device-side findings since the last check:
  * RL_EINVAL if a token id outside [0, vocab) was seen (it was clamped), RL_EHIP
  * if the stream is in error. */

@@ -743,6 +743,60 @@ void k_kl(const float* lp, const float* lr, const int* seq_len, const int* promp
     kl_kernel<<<grid, 256, 0, s>>>(lp, lr, seq_len, prompt_len, Lmax, coef, kl, pen);
 }
 
+// ---------------------------------------------------------------- value head of a critic / reward model
+// v[slot, pos] = head . RMSNorm(x_row; g) for every packed row with pos >= 0: the final norm and the
+// [d] -> 1 head in one pass over the fp32 residual stream (nothing is rounded to fp16 on the way).
+template <typename TW>
+__global__ __launch_bounds__(256) void value_head_kernel(const float* x, const TW* g, const TW* head, int d, float eps,
+                                                         const int* tok_slot, const int* tok_pos, float* out,
+                                                         int ld_out) {
+    __shared__ float red[16];
+    const int n = blockIdx.x;
+    const int pos = tok_pos[n];
+    if (pos < 0) return;
+    const float* xr = x + (int64_t)n * d;
+    float ss = 0.f, dot = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        const float v = xr[j];
+        ss += v * v;
+        dot += v * to_f(g[j]) * to_f(head[j]);
+    }
+    ss = block_sum(ss, red);
+    dot = block_sum(dot, red);
+    if (threadIdx.x == 0) out[(int64_t)tok_slot[n] * ld_out + pos] = dot / sqrtf(ss / (float)d + eps);
+}
+void k_value_head(int dtype, const float* x, const void* g, const void* head, int n, int d, float eps,
+                  const int* tok_slot, const int* tok_pos, float* out, int ld_out, hipStream_t s) {
+    if (n <= 0) return;
+    if (dtype == 0)
+        value_head_kernel<float><<<n, 256, 0, s>>>(x, (const float*)g, (const float*)head, d, eps, tok_slot, tok_pos, out, ld_out);
+    else
+        value_head_kernel<bf16_t><<<n, 256, 0, s>>>(x, (const bf16_t*)g, (const bf16_t*)head, d, eps, tok_slot, tok_pos, out, ld_out);
+}
+
+// ---------------------------------------------------------------- PPO reward per token
+// r[b,t] = -coef * kl[b,t] on response positions [prompt_len, L), plus seq_reward[b] at t = L-1; 0 elsewhere.
+__global__ void ppo_reward_kernel(const float* kl, const float* seq_reward, const int* seq_len, const int* prompt_len,
+                                  int Lmax, float coef, float* out) {
+    int b = blockIdx.y;
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= Lmax) return;
+    const int64_t o = (int64_t)b * Lmax + t;
+    const int L = seq_len[b], P = prompt_len[b];
+    float r = 0.f;
+    if (t >= P && t < L) {
+        r = -coef * kl[o];
+        if (t == L - 1) r += seq_reward[b];
+    }
+    out[o] = r;
+}
+void k_ppo_reward(const float* kl, const float* seq_reward, const int* seq_len, const int* prompt_len, int B, int Lmax,
+                  float coef, float* out, hipStream_t s) {
+    if (B <= 0 || Lmax <= 0) return;
+    dim3 grid((Lmax + 255) / 256, B);
+    ppo_reward_kernel<<<grid, 256, 0, s>>>(kl, seq_reward, seq_len, prompt_len, Lmax, coef, out);
+}
+
 // ---------------------------------------------------------------- log-prob from per-group (max, sum-exp) partials
 // One wave per row: combine the nparts pairs written by the LM-head GEMM epilogue into
 // log sum_v exp(z_v) and write logp = z_target - lse at [slot, pos + 1].

@@ -1011,8 +1011,18 @@ static void score_head(rl_ctx* c, const WeightsHost& W, float* x, int n, float* 
 }
 
 // One teacher-forced pass of one device-resident weight set over all sequences; writes logp_out [B, Lmax].
+// The head applied to the final residual stream of n packed rows: the LM head with log-sum-exp and target
+// gather (log-probs), or, with value_head != nullptr, a [d] -> 1 head (critic values / reward-model scores).
+static void apply_head(rl_ctx* c, const WeightsHost& W, const void* value_head, float* x, int n, float* out, int Lmax,
+                       hipStream_t s) {
+    if (!value_head) { score_head(c, W, x, n, out, Lmax, s); return; }
+    const rl_model_cfg& m = c->cfg;
+    k_value_head(m.dtype, x, W.final_norm, value_head, n, m.d_model, m.rms_eps, c->at<int>(c->L.tok_slot),
+                 c->at<int>(c->L.tok_pos), out, Lmax, s);
+}
+
 static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const int32_t* seq_len, int B, int Lmax,
-                      float* logp_out, hipStream_t s) {
+                      float* logp_out, hipStream_t s, const void* value_head = nullptr) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     k_fill_f32(logp_out, 0.f, (int64_t)B * Lmax, s);
@@ -1026,7 +1036,7 @@ static int score_pass(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const
         k_embed(m.dtype, c->at<int>(L.tok_ids), ch.n, W.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
                 c->at<int>(L.errflag), s);
         run_layers(c, W, ch.n, false, false, ch.max_ctx, ch.nblocks, s);
-        score_head(c, W, c->at<float>(L.x), ch.n, logp_out, Lmax, s);
+        apply_head(c, W, value_head, c->at<float>(L.x), ch.n, logp_out, Lmax, s);
     }
     return RL_OK;
 }
@@ -1083,7 +1093,7 @@ static int ensure_copy_stream(rl_ctx* c) {
 }
 
 static int score_pass_streamed(rl_ctx* c, const WeightsHost& W, const int32_t* ids, const int32_t* seq_len, int B,
-                               int Lmax, float* logp_out, hipStream_t s) {
+                               int Lmax, float* logp_out, hipStream_t s, const void* value_head = nullptr) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     const StageLayout S = make_stage_layout(m);
@@ -1153,7 +1163,7 @@ static int score_pass_streamed(rl_ctx* c, const WeightsHost& W, const int32_t* i
     // the LM head takes the embedding table's place once the gathers are done
     HIP_TRY(hipEventRecord(c->ev_glob_free, s));
     HIP_TRY(hipStreamWaitEvent(cs, c->ev_glob_free, 0));
-    HIP_TRY(hipMemcpyAsync(st + S.globals, W.lm_head, S.b_globals, hipMemcpyHostToDevice, cs));
+    if (!value_head) HIP_TRY(hipMemcpyAsync(st + S.globals, W.lm_head, S.b_globals, hipMemcpyHostToDevice, cs));
     HIP_TRY(hipEventRecord(c->ev_glob_copied, cs));
 
     for (int l = 0; l < m.n_layers; ++l) {
@@ -1172,7 +1182,7 @@ static int score_pass_streamed(rl_ctx* c, const WeightsHost& W, const int32_t* i
     HIP_TRY(hipStreamWaitEvent(s, c->ev_glob_copied, 0));
     for (size_t k = 0; k < chunks.size(); ++k) {
         if ((rc = pack_chunk(c, ids, Lmax, chunks[k], true, s))) return rc;
-        score_head(c, D, x_all + first[k] * m.d_model, chunks[k].n, logp_out, Lmax, s);
+        apply_head(c, D, value_head, x_all + first[k] * m.d_model, chunks[k].n, logp_out, Lmax, s);
     }
     return RL_OK;
 }
@@ -1225,6 +1235,47 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
         k_kl(logp_policy, logp_ref, c->at<int>(L.d_seq_len), c->at<int>(L.d_prompt_len), B, Lmax, kl_coef, kl,
              kl_penalty, s);
     }
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+int score_values(rl_ctx* c, const rl_weights* model, const void* value_head, const int32_t* ids,
+                 const int32_t* seq_len, int32_t B, int32_t Lmax, float* values, void* stream) {
+    if (!c || !model || !ids || !seq_len || !value_head || !values) return fail(RL_EINVAL, "NULL argument");
+    const rl_model_cfg& m = c->cfg;
+    if (B < 1 || B > m.max_batch) return fail(RL_EINVAL, "B=%d outside [1, max_batch=%d]", B, m.max_batch);
+    if (Lmax < 1) return fail(RL_EINVAL, "Lmax < 1");
+    for (int b = 0; b < B; ++b)
+        if (seq_len[b] < 1 || seq_len[b] > Lmax || seq_len[b] > m.max_seq)
+            return fail(RL_EINVAL, "seq_len[%d]=%d outside [1, min(Lmax, max_seq)]", b, seq_len[b]);
+    // the body's LM head is not used; a weight set without one is accepted
+    rl_weights w = *model;
+    if (!w.lm_head) w.lm_head = w.tok_embed;
+    WeightsHost wh;
+    int rc = copy_weights(m, &w, wh, "critic / reward model", true);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = wh.location == 1 ? score_pass_streamed(c, wh, ids, seq_len, B, Lmax, values, s, value_head)
+                          : score_pass(c, wh, ids, seq_len, B, Lmax, values, s, value_head);
+    if (rc) return rc;
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+int ppo_rewards(rl_ctx* c, const float* kl, const float* seq_reward, const int32_t* seq_len, const int32_t* prompt_len,
+                int32_t B, int32_t Lmax, float kl_coef, float* rewards, void* stream) {
+    if (!c || !kl || !seq_reward || !seq_len || !prompt_len || !rewards) return fail(RL_EINVAL, "NULL argument");
+    if (B < 1 || B > c->cfg.max_batch) return fail(RL_EINVAL, "B=%d outside [1, max_batch=%d]", B, c->cfg.max_batch);
+    if (Lmax < 1) return fail(RL_EINVAL, "Lmax < 1");
+    for (int b = 0; b < B; ++b)
+        if (seq_len[b] < 1 || seq_len[b] > Lmax || prompt_len[b] < 0 || prompt_len[b] > seq_len[b])
+            return fail(RL_EINVAL, "row %d: need 1 <= seq_len <= Lmax and 0 <= prompt_len <= seq_len", b);
+    hipStream_t s = (hipStream_t)stream;
+    const Layout& L = c->L;
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_seq_len), seq_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    k_ppo_reward(kl, seq_reward, c->at<int>(L.d_seq_len), c->at<int>(L.d_prompt_len), B, Lmax, kl_coef, rewards, s);
     HIP_TRY(hipGetLastError());
     return RL_OK;
 }

@@ -70,6 +70,8 @@ def lib():
         L.score_logprobs_kl.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, f32,
                                         vp, vp, vp, vp, vp]
         L.rollout_check.argtypes = [vp, vp]
+        L.score_values.argtypes = [vp, C.POINTER(rl_weights), vp, vp, vp, i32, i32, vp, vp]
+        L.ppo_rewards.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.rollout_set_policy.argtypes = [vp, C.POINTER(rl_weights)]
         L.rollout_reset.argtypes = [vp]
         L.rollout_destroy.argtypes = [vp]
@@ -221,6 +223,19 @@ class Rollout:
         ref = C.byref(reference.struct) if reference is not None else None
         _chk(lib().score_logprobs_kl(self.h, C.byref(policy.struct), ref, _ptr(ids), slp, plp, B, Lmax, kl_coef,
                                      _ptr(logp_policy), _ptr(logp_ref), _ptr(kl), _ptr(kl_penalty), _stream()))
+
+    def score_values(self, model: Weights, value_head: torch.Tensor, ids: torch.Tensor, seq_len, values):
+        sl, slp = _host_i32(seq_len)
+        B, Lmax = ids.shape
+        _chk(lib().score_values(self.h, C.byref(model.struct), _ptr(value_head), _ptr(ids), slp, B, Lmax,
+                                _ptr(values), _stream()))
+
+    def ppo_rewards(self, kl: torch.Tensor, seq_reward: torch.Tensor, seq_len, prompt_len, kl_coef, rewards):
+        sl, slp = _host_i32(seq_len)
+        pl, plp = _host_i32(prompt_len)
+        B, Lmax = kl.shape
+        _chk(lib().ppo_rewards(self.h, _ptr(kl), _ptr(seq_reward), slp, plp, B, Lmax, kl_coef, _ptr(rewards),
+                               _stream()))
 
     def rollout_check(self):
         _chk(lib().rollout_check(self.h, _stream()))

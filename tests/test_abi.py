@@ -15,12 +15,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     src = open(os.path.join(ROOT, "include", "rollout.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:rollout|score)_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b((?:rollout|score|ppo)_[a-z_]+)\s*\(", src)))
 
 
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"rollout_init", "rollout_decode_step", "rollout_generate", "score_logprobs_kl"} <= set(names)
+    assert {"ppo_rewards", "score_values", "rollout_generate_queue", "rollout_set_policy"} <= set(names)
     lib = R.lib()
     for n in names:
         assert hasattr(lib, n), n

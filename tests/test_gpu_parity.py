@@ -429,6 +429,41 @@ def test_policy_weight_swap_and_in_place_update():
     ro.close()
 
 
+@pytest.mark.parametrize("shape", [MINI32F, MINI128], ids=lambda s: s.name)
+def test_value_head_and_ppo_rewards(shape):
+    """Critic / reward-model pass (decoder body + scalar head) and the per-token PPO reward, against the
+    oracle: ragged sequences over several chunks, the head in the weight dtype, then rewards assembled
+    from the GPU's own KL and the reward model's last-token score."""
+    B = 6
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 72, chunk=150)
+    ids, lens, plens = synth.make_sequences(shape.vocab, B, 72, 9, 0.4, 83)
+    plens[2] = lens[2]                                      # no response: reward row stays zero
+    wd = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+    gen = torch.Generator(device="cpu").manual_seed(84)
+    head = (torch.randn(shape.d_model, generator=gen) * 0.05).to(wd).to(DEV)
+    d_ids = torch.tensor(ids, device=DEV)
+    vals = torch.full((B, 72), 9.0, dtype=torch.float32, device=DEV)
+    ro.score_values(Wr, head, d_ids, lens, vals)            # the "reward model": the second weight set's body
+    ro.rollout_check()
+    v = vals.cpu().numpy()
+    want = O.values_batch(mr, head.float().cpu().numpy().astype(np.float64), ids, lens)
+    vt = 1e-4 if shape.dtype == "fp32" else 2e-2
+    assert np.abs(v - want).max() < vt, np.abs(v - want).max()
+    assert np.all(v[want == 0.0] == 0.0)
+    # rewards from the GPU's KL and the last-token scores
+    lp, lr, kl, _ = [torch.tensor(a, device=DEV) for a in _score(ro, Wp, Wr, ids, lens, plens, 0.003)]
+    last = torch.tensor(np.array([v[b, lens[b] - 1] for b in range(B)], np.float32), device=DEV)
+    rew = torch.full((B, 72), 9.0, dtype=torch.float32, device=DEV)
+    ro.ppo_rewards(kl, last, lens, plens, 0.003, rew)
+    r = rew.cpu().numpy()
+    want_r = O.ppo_rewards(kl.cpu().numpy(), last.cpu().numpy(), lens, plens, 0.003)
+    assert np.abs(r - want_r).max() < 1e-6
+    assert np.all(r[2] == 0.0) and np.all(r[:, 71][lens < 72] == 0.0)
+    with pytest.raises(R.RolloutError):
+        ro.ppo_rewards(kl, last, lens, lens + 1, 0.003, rew)
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
