@@ -169,6 +169,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run three device copies of 1 GiB (read 1 GiB, write 1 GiB each): the known-size "
                          "kernel that HBM-traffic counters of a rocprofv3 --pmc run are scaled by")
+    ap.add_argument("--kl-exact", action="store_true",
+                    help="also time score_kl_exact (both bodies + the fused dual LM head) on the rollouts; extra key kl_exact_s")
     ap.add_argument("--queue", type=int, default=0, metavar="Q",
                     help="variable-length generation instead of the headline step: Q prompts with response limits "
                          "from a long-tailed distribution (mean about 351 tokens), run once through "
@@ -314,6 +316,16 @@ def main():
     sflops = 2 * score_flops(shape, seq_len)
     score_tflops = sflops / score_s / 1e12 if not args.no_score else None
 
+    kl_exact_s = None
+    if args.kl_exact and not args.ref_host:
+        klf = torch.zeros(B, Lmax, dtype=torch.float32, device=dev)
+        ro.score_kl_exact(Wp, Wr, full, seq_len, plen, klf)       # warm
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ro.score_kl_exact(Wp, Wr, full, seq_len, plen, klf)
+        torch.cuda.synchronize()
+        kl_exact_s = time.perf_counter() - t1
+
     # roofline of the dominant decode kernel class
     def avg_ms(name):
         p = prof[name]
@@ -352,6 +364,7 @@ def main():
                    "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
                    "reference": "pinned host, streamed" if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
+        "kl_exact_s": kl_exact_s,
         "decode_tok_s": B * G / decode_s, "generate_tok_s": B * G / gen_s,
         "decode_hbm_gbps": decode_gbps, "decode_hbm_frac": decode_gbps / HBM_PEAK_GBPS,
         "scored_tok_s": (2 * float(seq_len.sum()) / score_s) if not args.no_score else None,

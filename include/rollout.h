@@ -183,6 +183,19 @@ int score_logprobs_kl(rl_ctx* ctx, const rl_weights* policy, const rl_weights* r
                       float* logp_policy, float* logp_ref, float* kl, float* kl_penalty,
                       void* stream);
 
+/* Exact per-token KL between the two policies' next-token distributions, in one pass (the sampled term of
+ * score_logprobs_kl estimates this quantity from the one token that was drawn):
+ *   kl_full[b,t] = sum_v pi_policy(v | ids[b,<t]) * (log pi_policy(v | .) - log pi_ref(v | .))
+ * on response positions t in [max(prompt_len[b], 1), L_b); 0 elsewhere.  Both bodies run on each chunk of
+ * tokens; then ONE kernel forms both models' logits tile by tile and keeps, per row and column group, five
+ * running numbers (max and sum-exp of each model, and the policy-weighted sum of logit differences).
+ * Neither model's [tokens, vocab] logits or probabilities are written to memory.
+ * Arguments as for score_logprobs_kl; both weight sets device-resident (location 0); kl_full: dev fp32
+ * [B, Lmax].  Errors: RL_EINVAL, RL_ENOSPACE. */
+int score_kl_exact(rl_ctx* ctx, const rl_weights* policy, const rl_weights* reference,
+                   const int32_t* ids, const int32_t* seq_len, const int32_t* prompt_len,
+                   int32_t B, int32_t Lmax, float* kl_full, void* stream);
+
 /* Critic values / reward-model scores (Section 2.2 step 2 and Section 3.1: the reward model and the critic
  * are decoders of the actor's kind with a scalar head, served for inference on the rollouts).  The same
  * teacher-forced pass as score_logprobs_kl with a [d_model] -> 1 head in place of the LM head:

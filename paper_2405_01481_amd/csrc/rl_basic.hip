@@ -797,6 +797,77 @@ void k_ppo_reward(const float* kl, const float* seq_reward, const int* seq_len, 
     ppo_reward_kernel<<<grid, 256, 0, s>>>(kl, seq_reward, seq_len, prompt_len, Lmax, coef, out);
 }
 
+// ---------------------------------------------------------------- exact KL from per-group partials
+// One wave per row: combine the nparts quintuples (m_p, S_p, T, m_r, S_r) written by the dual LM-head GEMM
+// into KL(pi_policy || pi_ref) = T/S_p - lse_p + lse_r and write it at [slot, pos + 1] on response
+// positions (pos + 1 >= max(prompt_len, 1)); rows without a next token inside their sequence are skipped.
+__global__ __launch_bounds__(64) void kl_full_reduce_kernel(const float* part, int nparts, const int* tok_tgt,
+                                                            const int* tok_slot, const int* tok_pos,
+                                                            const int* prompt_len, float* out, int ld_out) {
+    const int r = blockIdx.x;
+    if (tok_tgt[r] < 0) return;
+    const int slot = tok_slot[r], t = tok_pos[r] + 1;
+    if (t < max(prompt_len[slot], 1)) return;
+    const float* p = part + (int64_t)r * nparts * 5;
+    float mp = -INFINITY, sp = 0.f, tt = 0.f, mr = -INFINITY, sr = 0.f;
+    for (int i = threadIdx.x; i < nparts; i += 64) {
+        const float m1 = p[i * 5], s1 = p[i * 5 + 1], t1 = p[i * 5 + 2], m2 = p[i * 5 + 3], s2 = p[i * 5 + 4];
+        const float mn = fmaxf(mp, m1), a0 = __expf(mp - mn), a1 = __expf(m1 - mn);
+        sp = sp * a0 + s1 * a1;
+        tt = tt * a0 + t1 * a1;
+        mp = mn;
+        const float mq = fmaxf(mr, m2);
+        sr = sr * __expf(mr - mq) + s2 * __expf(m2 - mq);
+        mr = mq;
+    }
+    const float Mp = wave_max(mp), Mr = wave_max(mr);
+    const float wp = __expf(mp - Mp);
+    sp = wave_sum(sp * wp);
+    tt = wave_sum(tt * wp);
+    sr = wave_sum(sr * __expf(mr - Mr));
+    if (threadIdx.x == 0) out[(int64_t)slot * ld_out + t] = tt / sp - (Mp + logf(sp)) + (Mr + logf(sr));
+}
+void k_kl_full_reduce(const float* part, int nparts, int nrows, const int* tok_tgt, const int* tok_slot,
+                      const int* tok_pos, const int* prompt_len, float* out, int ld_out, hipStream_t s) {
+    if (nrows <= 0) return;
+    kl_full_reduce_kernel<<<nrows, 64, 0, s>>>(part, nparts, tok_tgt, tok_slot, tok_pos, prompt_len, out, ld_out);
+}
+
+// The same from two materialised logit rows (plain path): one block per row.
+__global__ __launch_bounds__(1024) void kl_full_rows_kernel(const float* zp, const float* zr, int ldz, int V,
+                                                            const int* tok_tgt, const int* tok_slot,
+                                                            const int* tok_pos, const int* prompt_len, float* out,
+                                                            int ld_out) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    if (tok_tgt[r] < 0) return;
+    const int slot = tok_slot[r], t = tok_pos[r] + 1;
+    if (t < max(prompt_len[slot], 1)) return;
+    const float* a = zp + (int64_t)r * ldz;
+    const float* b = zr + (int64_t)r * ldz;
+    float mp = -INFINITY, mr = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += 1024) { mp = fmaxf(mp, a[i]); mr = fmaxf(mr, b[i]); }
+    mp = block_max(mp, red);
+    mr = block_max(mr, red);
+    float sp = 0.f, tt = 0.f, sr = 0.f;
+    for (int i = threadIdx.x; i < V; i += 1024) {
+        const float e = __expf(a[i] - mp);
+        sp += e;
+        tt += e * (a[i] - b[i]);
+        sr += __expf(b[i] - mr);
+    }
+    sp = block_sum(sp, red);
+    tt = block_sum(tt, red);
+    sr = block_sum(sr, red);
+    if (threadIdx.x == 0) out[(int64_t)slot * ld_out + t] = tt / sp - (mp + logf(sp)) + (mr + logf(sr));
+}
+void k_kl_full_rows(const float* zp, const float* zr, int ldz, int V, int nrows, const int* tok_tgt,
+                    const int* tok_slot, const int* tok_pos, const int* prompt_len, float* out, int ld_out,
+                    hipStream_t s) {
+    if (nrows <= 0) return;
+    kl_full_rows_kernel<<<nrows, 1024, 0, s>>>(zp, zr, ldz, V, tok_tgt, tok_slot, tok_pos, prompt_len, out, ld_out);
+}
+
 // ---------------------------------------------------------------- log-prob from per-group (max, sum-exp) partials
 // One wave per row: combine the nparts pairs written by the LM-head GEMM epilogue into
 // log sum_v exp(z_v) and write logp = z_target - lse at [slot, pos + 1].

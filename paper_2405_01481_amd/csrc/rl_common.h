@@ -127,6 +127,11 @@ void k_lse_gather(const float* logits, int ldz, int V, int nrows, const int* tok
 void k_kl(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int B, int Lmax, float coef,
           float* kl, float* pen, hipStream_t s);
 void k_out_len(const int* gen_count, int* out_len, int B, hipStream_t s);
+void k_kl_full_reduce(const float* part, int nparts, int nrows, const int* tok_tgt, const int* tok_slot,
+                      const int* tok_pos, const int* prompt_len, float* out, int ld_out, hipStream_t s);
+void k_kl_full_rows(const float* zp, const float* zr, int ldz, int V, int nrows, const int* tok_tgt,
+                    const int* tok_slot, const int* tok_pos, const int* prompt_len, float* out, int ld_out,
+                    hipStream_t s);
 void k_value_head(int dtype, const float* x, const void* g, const void* head, int n, int d, float eps,
                   const int* tok_slot, const int* tok_pos, float* out, int ld_out, hipStream_t s);
 void k_ppo_reward(const float* kl, const float* seq_reward, const int* seq_len, const int* prompt_len, int B, int Lmax,

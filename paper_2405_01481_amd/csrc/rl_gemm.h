@@ -2,7 +2,7 @@
 #pragma once
 #include "rl_common.h"
 
-enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4, MG_LSE = 5 };
+enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4, MG_LSE = 5, MG_KLFULL = 6 };
 
 struct GemmArgs {
     const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
@@ -33,6 +33,13 @@ struct GemmArgs {
     const int* tgt = nullptr;
     float2* lse_part = nullptr;
     float* z_tgt = nullptr;
+    // MG_KLFULL (both LM heads for the exact KL): the reference's logits A2 * W2^T are formed for the same
+    // tile as the policy's A * W^T; per row and 64-column group five floats go to kl_part[row][N/64][5]
+    // (see kl_epilogue).  No logits are stored.
+    const f16_t* A2 = nullptr;
+    int lda2 = 0;
+    const bf16_t* W2 = nullptr;
+    float* kl_part = nullptr;
     int vt_cap = 0;             // > 0: v_out is dim-major [Hkv][hd][vt_cap tokens]; 0: token-major [M][Hkv][hd]
     KvGeom geo{};
     // 256 x 256 workgroup tiles (splits == 1 only): 0 never, 1 when the grid fills the chip at one workgroup

@@ -425,8 +425,53 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 // Requires (k extent per split) % 128 == 0 and operand byte offsets below 4 GiB (checked by the launcher).
 constexpr int dma_waitcnt(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
 
-template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
-__global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
+// Exact-KL epilogue for one 32-row band: zp / zr are the policy's and the reference's logits of the same
+// (row, column) entries.  Per row and per wave (TN*32 columns) five numbers leave the kernel:
+//   m_p = max z_p, S_p = sum exp(z_p - m_p), T = sum exp(z_p - m_p) (z_p - z_r), m_r = max z_r, S_r = sum exp(z_r - m_r)
+// from which  KL(pi_p || pi_r) = T/S_p - (m_p + log S_p) + (m_r + log S_r)  once all column groups are combined.
+template <int BN, int TN, int WGN>
+__device__ __forceinline__ void kl_epilogue(floatx16 (&zp)[TN], floatx16 (&zr)[TN], const GemmArgs& a, int m_base,
+                                            int nb, int wn, int lane) {
+    const int lg = lane >> 5, lrow = lane & 31;
+    const int nparts = (a.N / BN) * WGN;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+        float mp = zp[0][r], mr = zr[0][r];
+#pragma unroll
+        for (int j = 1; j < TN; ++j) { mp = fmaxf(mp, zp[j][r]); mr = fmaxf(mr, zr[j][r]); }
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) {
+            mp = fmaxf(mp, __shfl_xor(mp, o, RL_WAVE));
+            mr = fmaxf(mr, __shfl_xor(mr, o, RL_WAVE));
+        }
+        float sp = 0.f, t = 0.f, sr = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const float e = __expf(zp[j][r] - mp);
+            sp += e;
+            t += e * (zp[j][r] - zr[j][r]);
+            sr += __expf(zr[j][r] - mr);
+        }
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) {
+            sp += __shfl_xor(sp, o, RL_WAVE);
+            t += __shfl_xor(t, o, RL_WAVE);
+            sr += __shfl_xor(sr, o, RL_WAVE);
+        }
+        if (lrow == 0 && m < a.M) {
+            float* o = a.kl_part + ((int64_t)m * nparts + nb * WGN + wn) * 5;
+            o[0] = mp; o[1] = sp; o[2] = t; o[3] = mr; o[4] = sr;
+        }
+    }
+}
+
+// The k loop of gemm_dma_kernel for one tile: acc = A[m0.., kbeg..] * W[tile nb]^T over nk k-tiles of 32.
+// Aop / Wop are the operands (row strides lda / a.K); ends with every staging load landed (vmcnt(0)).
+template <int EPI, int BM, int BN, int WGM, int WGN>
+__device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop, int lda, const bf16_t* Wop, int m0,
+                                             int nb, int kbeg, int nk, int wave, int lane, char* smem,
+                                             floatx16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
     constexpr int SLOTS = TM * TN, HS = SLOTS / 2;   // MFMAs per k-slice; slots of its first half
     constexpr int STAGE = (BM + BN) * 64;            // bytes per stage: A rows then W rows, 64 B each
@@ -435,16 +480,7 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
     constexpr int RPS = (TN + TM) / HS, CPS = 2 * TN / HS;   // fragment reads / conversion halves per slot
     static_assert(WGM * WGN == 4 && SLOTS % 2 == 0 && (TN + TM) % HS == 0 && (2 * TN) % HS == 0, "tile shape");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "whole 16-row blocks per wave and operand");
-    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A BM x 64 B | W BN x 64 B]
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM, ks = blockIdx.z;
-    int nb, mb;
-    if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
-    const int m0 = mb * BM;
-    const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
-    const int nk = (kend - kbeg) / 32;               // multiple of 4
     // Staging: load l of wave w fills the 1 KB block l*4 + w of a stage = 16 rows of A (l < BM/64) or W;
     // lane -> row + lane/4, physical chunk lane%4, which holds the row's logical chunk (lane%4) ^ ((row>>2)&3).
     unsigned g_off[LPT];
@@ -454,15 +490,15 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
         for (int l = 0; l < LPT; ++l) {
             if (l < BM / 64) {
                 const int r = (l * 4 + wave) * 16 + (lane >> 2);
-                g_off[l] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
+                g_off[l] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
             } else {
                 const int r = ((l - BM / 64) * 4 + wave) * 16 + (lane >> 2);
                 g_off[l] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u;
             }
         }
     }
-    const char* Ag = reinterpret_cast<const char*>(a.A + kbeg);
-    const char* Wg = reinterpret_cast<const char*>(a.W + kbeg);
+    const char* Ag = reinterpret_cast<const char*>(Aop + kbeg);
+    const char* Wg = reinterpret_cast<const char*>(Wop + kbeg);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 #define DG_LOAD(stage, kt, l)                                                                                   \
     {                                                                                                           \
@@ -481,7 +517,6 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
             fa[hp][sl] = hp * 2 * STAGE + (wm * TM * 32 + (lane & 31)) * 64 + ko;
             fw[hp][sl] = hp * 2 * STAGE + BM * 64 + (wn * TN * 32 + (lane & 31)) * 64 + ko;
         }
-    floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -562,6 +597,34 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
 #undef DG_LDW
 #undef DG_SLICE
 #undef DG_STEP
+}
+
+template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
+__global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
+    constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A BM x 64 B | W BN x 64 B]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM, ks = blockIdx.z;
+    int nb, mb;
+    if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
+    const int m0 = mb * BM;
+    const int kbeg = ks * a.k_per_split, kend = min(a.K, kbeg + a.k_per_split);
+    const int nk = (kend - kbeg) / 32;               // multiple of 4
+    floatx16 acc[TM][TN];
+    if (EPI == MG_KLFULL) {
+        // two GEMMs on the same tile, one after the other through the same LDS stages: reference logits
+        // first (kept in registers), then the policy's; the epilogue needs both for every (row, column)
+        floatx16 acc_r[TM][TN];
+        dma_mainloop<EPI, BM, BN, WGM, WGN>(a, a.A2, a.lda2, a.W2, m0, nb, kbeg, nk, wave, lane, smem, acc_r);
+        __syncthreads();   // every wave is done reading the stages before they are refilled
+        dma_mainloop<EPI, BM, BN, WGM, WGN>(a, a.A, a.lda, a.W, m0, nb, kbeg, nk, wave, lane, smem, acc);
+        kl_epilogue<BN, TN, WGN>(acc[0], acc_r[0], a, m0 + wm * TM * 32, nb, wn, lane);
+        if (TM > 1) kl_epilogue<BN, TN, WGN>(acc[TM > 1 ? 1 : 0], acc_r[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, lane);
+        return;
+    }
+    dma_mainloop<EPI, BM, BN, WGM, WGN>(a, a.A, a.lda, a.W, m0, nb, kbeg, nk, wave, lane, smem, acc);
     // written out: with the largest epilogue the unroller gives up on a loop over the bands
     mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, ks, lane);
     if (TM > 1) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, ks, lane);
@@ -721,6 +784,7 @@ static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
 }
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
+    if (epi == MG_KLFULL) return N % 128 == 0 && K % 128 == 0 && (uint64_t)N * K * 2 < (1ull << 32);
     if (K % BK != 0) return false;
     if (epi == MG_SWIGLU) return N % 64 == 0;
     if (epi == MG_QKV) return N % 128 == 0 && (hd == 64 || hd == 128);
@@ -776,6 +840,10 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
         case MG_QKV:
             if (big) launch_big<MG_QKV>(a, a.N / 256, s);
             else launch<128, 128, 2, 2, MG_QKV>(a, a.N / 128, 1, s);
+            break;
+        case MG_KLFULL:   // two accumulator sets per tile: 128 x 128 tiles on the LDS-staged kernel
+            a.k_per_split = a.K;
+            launch_dma<MG_KLFULL, 128, 128, 2, 2, 2>(a, a.N / 128, 1, s);
             break;
         default: break;
     }

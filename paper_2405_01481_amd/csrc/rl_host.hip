@@ -29,7 +29,7 @@ static int fail(int code, const char* fmt, ...) {
 
 // ---------------------------------------------------------------- workspace layout
 struct Layout {
-    size_t x, h, qkv, q, kbuf, vbuf, attn, ffn, logits, rope, block_table;
+    size_t x, h, h_keep, qkv, q, kbuf, vbuf, attn, ffn, logits, rope, block_table;
     size_t last_tok, seq_len, gen_count, finished, cur_tok, step_count;
     size_t tok_ids, tok_pos, tok_slot, tok_tgt;
     size_t seq_first, row_start, row_len, full_len, row_slot, d_seq_len, d_prompt_len, errflag;
@@ -64,6 +64,7 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.logit_rows = std::max(c.max_batch, std::min(rows, kLogitRowsScore));
     L.x = take((size_t)rows * c.d_model * 4);
     L.h = take((size_t)rows * c.d_model * e);
+    L.h_keep = take((size_t)rows * c.d_model * e);   // the policy's final hidden states while the reference runs (exact KL)
     L.qkv = take((size_t)rows * nqkv * 4);
     L.q = take((size_t)rows * qd * e);
     L.kbuf = take((size_t)rows * kd * e);
@@ -1234,6 +1235,81 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
         HIP_TRY(hipStreamSynchronize(s));
         k_kl(logp_policy, logp_ref, c->at<int>(L.d_seq_len), c->at<int>(L.d_prompt_len), B, Lmax, kl_coef, kl,
              kl_penalty, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+int score_kl_exact(rl_ctx* c, const rl_weights* policy, const rl_weights* reference, const int32_t* ids,
+                   const int32_t* seq_len, const int32_t* prompt_len, int32_t B, int32_t Lmax, float* kl_out,
+                   void* stream) {
+    if (!c || !ids || !seq_len || !prompt_len || !kl_out) return fail(RL_EINVAL, "NULL argument");
+    const rl_model_cfg& m = c->cfg;
+    if (B < 1 || B > m.max_batch) return fail(RL_EINVAL, "B=%d outside [1, max_batch=%d]", B, m.max_batch);
+    if (Lmax < 1) return fail(RL_EINVAL, "Lmax < 1");
+    for (int b = 0; b < B; ++b) {
+        if (seq_len[b] < 1 || seq_len[b] > Lmax || seq_len[b] > m.max_seq)
+            return fail(RL_EINVAL, "seq_len[%d]=%d outside [1, min(Lmax, max_seq)]", b, seq_len[b]);
+        if (prompt_len[b] < 0 || prompt_len[b] > seq_len[b])
+            return fail(RL_EINVAL, "prompt_len[%d]=%d outside [0, seq_len]", b, prompt_len[b]);
+    }
+    WeightsHost wp, wr;
+    int rc = copy_weights(m, policy, wp, "policy");
+    if (rc) return rc;
+    if ((rc = copy_weights(m, reference, wr, "reference"))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const Layout& L = c->L;
+    const size_t e = esz_of(m.dtype);
+    const bool fused = c->impl == 1 && k_gemm_mfma_supported(MG_KLFULL, m.vocab, m.d_model, m.head_dim);
+    k_fill_f32(kl_out, 0.f, (int64_t)B * Lmax, s);
+    HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    std::vector<int> len_of(seq_len, seq_len + B);
+    // rows per dual-head launch: the partials (5 floats per row and 64 columns) share the buffer of the
+    // log-sum-exp partials (2 floats); the plain path holds two logit blocks in the logits buffer
+    const int nparts = m.vocab / 64;
+    int kl_rows = fused ? (int)((size_t)L.rows * ((m.vocab + 63) / 64) * 2 / ((size_t)nparts * 5)) : L.logit_rows / 2;
+    if (kl_rows < 1) return fail(RL_ENOSPACE, "workspace too small for the exact-KL head");
+    int b0 = 0;
+    while (b0 < B) {
+        Chunk ch;
+        b0 = chunk_take(c, len_of, b0, B, ch);
+        const int n = ch.n;
+        if ((rc = pack_chunk(c, ids, Lmax, ch, true, s))) return rc;
+        // policy body, final norm; keep its hidden states while the reference body runs on the same rows
+        k_embed(m.dtype, c->at<int>(L.tok_ids), n, wp.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+                c->at<int>(L.errflag), s);
+        run_layers(c, wp, n, false, false, ch.max_ctx, ch.nblocks, s);
+        k_rmsnorm(m.dtype, c->at<float>(L.x), wp.final_norm, c->at<char>(L.h_keep), n, m.d_model, m.rms_eps, s);
+        k_embed(m.dtype, c->at<int>(L.tok_ids), n, wr.tok_embed, m.d_model, m.vocab, c->at<float>(L.x),
+                c->at<int>(L.errflag), s);
+        run_layers(c, wr, n, false, false, ch.max_ctx, ch.nblocks, s);
+        k_rmsnorm(m.dtype, c->at<float>(L.x), wr.final_norm, c->at<char>(L.h), n, m.d_model, m.rms_eps, s);
+        for (int r0 = 0; r0 < n; r0 += kl_rows) {
+            const int nr = std::min(kl_rows, n - r0);
+            const char* hp = c->at<char>(L.h_keep) + (size_t)r0 * m.d_model * e;
+            const char* hr = c->at<char>(L.h) + (size_t)r0 * m.d_model * e;
+            if (fused) {
+                // both LM heads in one tile kernel; neither model's logits reach memory
+                GemmArgs g;
+                g.M = nr; g.N = m.vocab; g.K = m.d_model;
+                g.A = (const f16_t*)hp; g.lda = m.d_model; g.W = (const bf16_t*)wp.lm_head;
+                g.A2 = (const f16_t*)hr; g.lda2 = m.d_model; g.W2 = (const bf16_t*)wr.lm_head;
+                g.kl_part = c->at<float>(L.lse_part);
+                mfma(c, RL_K_LMHEAD_SCORE, MG_KLFULL, g, 1, s);
+                k_kl_full_reduce(c->at<float>(L.lse_part), nparts, nr, c->at<int>(L.tok_tgt) + r0,
+                                 c->at<int>(L.tok_slot) + r0, c->at<int>(L.tok_pos) + r0, c->at<int>(L.d_prompt_len),
+                                 kl_out, Lmax, s);
+            } else {
+                float* zp = c->at<float>(L.logits);
+                float* zr = zp + (size_t)kl_rows * m.vocab;
+                gemm(c, RL_K_LMHEAD_SCORE, EPI_STORE_F32, hp, m.d_model, wp.lm_head, nullptr, nr, m.vocab, m.d_model, zp,
+                     nullptr, m.vocab, s);
+                gemm(c, RL_K_LMHEAD_SCORE, EPI_STORE_F32, hr, m.d_model, wr.lm_head, nullptr, nr, m.vocab, m.d_model, zr,
+                     nullptr, m.vocab, s);
+                k_kl_full_rows(zp, zr, m.vocab, m.vocab, nr, c->at<int>(L.tok_tgt) + r0, c->at<int>(L.tok_slot) + r0,
+                               c->at<int>(L.tok_pos) + r0, c->at<int>(L.d_prompt_len), kl_out, Lmax, s);
+            }
+        }
     }
     HIP_TRY(hipGetLastError());
     return RL_OK;

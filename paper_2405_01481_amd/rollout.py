@@ -70,6 +70,7 @@ def lib():
         L.score_logprobs_kl.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, f32,
                                         vp, vp, vp, vp, vp]
         L.rollout_check.argtypes = [vp, vp]
+        L.score_kl_exact.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, vp, vp]
         L.score_values.argtypes = [vp, C.POINTER(rl_weights), vp, vp, vp, i32, i32, vp, vp]
         L.ppo_rewards.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.rollout_set_policy.argtypes = [vp, C.POINTER(rl_weights)]
@@ -223,6 +224,13 @@ class Rollout:
         ref = C.byref(reference.struct) if reference is not None else None
         _chk(lib().score_logprobs_kl(self.h, C.byref(policy.struct), ref, _ptr(ids), slp, plp, B, Lmax, kl_coef,
                                      _ptr(logp_policy), _ptr(logp_ref), _ptr(kl), _ptr(kl_penalty), _stream()))
+
+    def score_kl_exact(self, policy: Weights, reference: Weights, ids: torch.Tensor, seq_len, prompt_len, kl_full):
+        sl, slp = _host_i32(seq_len)
+        pl, plp = _host_i32(prompt_len)
+        B, Lmax = ids.shape
+        _chk(lib().score_kl_exact(self.h, C.byref(policy.struct), C.byref(reference.struct), _ptr(ids), slp, plp, B,
+                                  Lmax, _ptr(kl_full), _stream()))
 
     def score_values(self, model: Weights, value_head: torch.Tensor, ids: torch.Tensor, seq_len, values):
         sl, slp = _host_i32(seq_len)

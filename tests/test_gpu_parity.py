@@ -464,6 +464,37 @@ def test_value_head_and_ppo_rewards(shape):
     ro.close()
 
 
+@pytest.mark.parametrize("shape", [MINI32F, MINI64, MINI128], ids=lambda s: s.name)
+def test_exact_kl_against_oracle(shape):
+    """score_kl_exact (both LM heads fused, no logits in memory on the tuned path; two logit blocks on the
+    plain path) against the oracle's full-vocabulary KL: ragged sequences over several chunks and several
+    dual-head launches per chunk; zero outside the response; identical models give (numerically) zero."""
+    B = 6
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 72, chunk=150)
+    ids, lens, plens = synth.make_sequences(shape.vocab, B, 72, 9, 0.4, 87)
+    lens[0], plens[0] = 1, 1
+    plens[1] = 0
+    plens[2] = lens[2]
+    out = torch.full((B, 72), 9.0, dtype=torch.float32, device=DEV)
+    ro.score_kl_exact(Wp, Wr, torch.tensor(ids, device=DEV), lens, plens, out)
+    ro.rollout_check()
+    got = out.cpu().numpy()
+    want = np.zeros((B, 72))
+    for b in range(B):
+        L, P = int(lens[b]), max(int(plens[b]), 1)
+        want[b, P:L] = O.kl_full(mp, mr, ids[b, :L])[P:L]
+    tol = 1e-4 if shape.dtype == "fp32" else 2e-2
+    err = np.abs(got - want).max()
+    print(shape.name, "exact KL: max", want.max(), "err", err)
+    assert err < tol
+    assert np.all(got[want == 0.0] == 0.0) and np.all(got >= -tol)
+    assert want.max() > 10 * tol                                   # the comparison has something to bite on
+    same = torch.full((B, 72), 9.0, dtype=torch.float32, device=DEV)
+    ro.score_kl_exact(Wp, Wp, torch.tensor(ids, device=DEV), lens, plens, same)
+    assert np.abs(same.cpu().numpy()).max() < (1e-5 if shape.dtype == "fp32" else 1e-3)
+    ro.close()
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
