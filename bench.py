@@ -175,6 +175,8 @@ def main():
                     help="variable-length generation instead of the headline step: Q prompts with response limits "
                          "from a long-tailed distribution (mean about 351 tokens), run once through "
                          "rollout_generate_queue and once as fixed batches that wait for their longest row")
+    ap.add_argument("--progress", action="store_true", help="phase markers with elapsed time on stderr")
+    ap.add_argument("--pin-gb", type=float, default=24.0, help="with --ref-host: most host memory to pin, in GB")
     ap.add_argument("--ref-host", action="store_true",
                     help="keep the reference weights in pinned host memory and stream them layer by layer while "
                          "scoring (the 70B configuration's residency); reported in config.reference")
@@ -210,20 +212,37 @@ def main():
         torch.cuda.empty_cache()
 
     wp = synth.make_weights(shape, wl.policy_seed, dev)
-    wr = synth.make_weights(shape, wl.ref_seed, dev)
     if args.queue and not args.gen:
         G = 1024                     # cap of the synthetic response lengths
     Lmax = Pmax + G
     cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=max(Lmax, args.chunk))
     if args.ref_host:
-        pin = lambda t: t.cpu().pin_memory()
-        wr = {**{k: pin(wr[k]) for k in ("tok_embed", "final_norm", "lm_head")},
-              "layers": [{k: pin(v) for k, v in lay.items()} for lay in wr["layers"]]}
+        # the reference never has to be device-resident: made one tensor at a time and moved to pinned host memory
+        host_bytes = {"pinned": 0, "pageable": 0}
+
+        def pin(t):
+            # pinned up to --pin-gb (transfers from pinned memory overlap with compute); pageable beyond that:
+            # a box may refuse to pin more, and a process does not reliably survive a refused allocation
+            h = t.cpu()
+            nb = h.numel() * h.element_size()
+            if host_bytes["pinned"] + nb <= args.pin_gb * 1e9:
+                host_bytes["pinned"] += nb
+                return h.pin_memory()
+            host_bytes["pageable"] += nb
+            return h
+
+        wr = {k: pin(v) for k, v in synth.make_globals(shape, wl.ref_seed, dev).items()}
+        wr["layers"] = []
+        for l in range(shape.n_layers):
+            wr["layers"].append({k: pin(v) for k, v in synth.make_layer(shape, wl.ref_seed, l, dev).items()})
         torch.cuda.empty_cache()
         staging = torch.empty(R.rollout_weight_staging_bytes(cfg), dtype=torch.uint8, device=dev)
         Wp, Wr = R.Weights(wp), R.Weights(wr, staging=staging)
     else:
+        wr = synth.make_weights(shape, wl.ref_seed, dev)
         Wp, Wr = R.Weights(wp), R.Weights(wr)
+    if args.progress:
+        print("[bench] weights ready", file=sys.stderr, flush=True)
     ro = R.Rollout(cfg, Wp, dev)
     if args.impl >= 0:
         ro.rollout_set_impl(args.impl)
@@ -250,14 +269,27 @@ def main():
                 full[b, :p] = ids[b, :p]
                 full[b, p:p + G] = out_ids[b]
 
+    t_start = time.perf_counter()
+
+    def note(msg):
+        # progress on stderr (the JSON line on stdout stays alone): long configurations are otherwise silent for minutes
+        if args.progress:
+            print("[bench %.0fs] %s" % (time.perf_counter() - t_start, msg), file=sys.stderr, flush=True)
+
     def one_step(timed):
         ev[0].record()
         ro.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)
         ev[1].record()
+        if args.progress:
+            ev[1].synchronize()
+            note("generated")
         if not args.no_score:
             assemble()
             ro.score_logprobs_kl(Wp, Wr, full, seq_len, plen, 0.003, *outs)
         ev[2].record()
+        if args.progress:
+            ev[2].synchronize()
+            note("scored")
 
     # a non-default stream: rollout_generate then replays its decode step as a captured HIP graph
     stream = torch.cuda.Stream()
@@ -362,7 +394,7 @@ def main():
         "config": {"workload": args.workload, "shape": shape.name, "layers": shape.n_layers, "batch": B,
                    "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
                    "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
-                   "reference": "pinned host, streamed" if args.ref_host else "device"},
+                   "reference": ("host, streamed (%.0f GB pinned, %.0f GB pageable)" % (host_bytes["pinned"] / 1e9, host_bytes["pageable"] / 1e9)) if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
         "kl_exact_s": kl_exact_s,
         "decode_tok_s": B * G / decode_s, "generate_tok_s": B * G / gen_s,
