@@ -375,7 +375,7 @@ def main():
         achieved = per_launch / (a_avg * 1e-3) / 1e9 if a_avg else None
     # HBM-side bytes per launch from hardware counters cannot be taken inside this process; the figure is the
     # one measured for this workload's decode GEMMs with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by
-    # what the counter reads for a 1 GiB device copy; summary in profiles/decode_gemm_hbm_traffic.md)
+    # what the counter reads for a 1 GiB device copy; the counter summary is kept under profiles/)
     traffic = None
     if g_tot >= a_tot and args.workload == "8b" and not args.layers and B == wl.batch and args.impl in (-1, 1, 2):
         traffic = 143.9e6

@@ -20,18 +20,6 @@ typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 #define BK 64
-#define LDS_STRIDE 72   // halfs per LDS row: 64 + 8 pad -> 144 B, conflict-free ds_read_b128
-
-__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w) {
-    union { uint4 u; fp16x2 p[4]; } o;
-    unsigned ws[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(ws[i] << 16), hi = __uint_as_float(ws[i] & 0xffff0000u);
-        o.p[i] = __builtin_amdgcn_cvt_pkrtz(lo, hi);   // exact: bf16 has 8 significant bits
-    }
-    return o.u;
-}
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ half8 bf16x8_to_half8(u32x4_t w) {
