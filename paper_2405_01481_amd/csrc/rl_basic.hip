@@ -562,9 +562,22 @@ __device__ __forceinline__ ArgMax argmax_combine(ArgMax a, ArgMax b) {
 }
 __device__ ArgMax block_argmax(const float* z, int V, ArgMax* red) {
     ArgMax a{-INFINITY, 0x7fffffff};
-    for (int i = threadIdx.x; i < V; i += blockDim.x) {
-        float v = z[i];
-        if (v > a.v) { a.v = v; a.i = i; }
+    if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0) {
+        // 16-byte loads; a thread meets its candidates in increasing index order, so "first strictly greater"
+        // keeps the lowest index among equals
+        const float4* z4 = reinterpret_cast<const float4*>(z);
+        for (int i = threadIdx.x; i < V / 4; i += blockDim.x) {
+            const float4 q = z4[i];
+            if (q.x > a.v) { a.v = q.x; a.i = 4 * i; }
+            if (q.y > a.v) { a.v = q.y; a.i = 4 * i + 1; }
+            if (q.z > a.v) { a.v = q.z; a.i = 4 * i + 2; }
+            if (q.w > a.v) { a.v = q.w; a.i = 4 * i + 3; }
+        }
+    } else {
+        for (int i = threadIdx.x; i < V; i += blockDim.x) {
+            float v = z[i];
+            if (v > a.v) { a.v = v; a.i = i; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -616,13 +629,23 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int l
     const bool greedy = !(a.temperature > 0.f);
     const float invT = greedy ? 1.0f : 1.0f / a.temperature;
     int seg = (V + 15) / 16;
-    seg = (seg + 63) / 64 * 64;
+    seg = (seg + 255) / 256 * 256;
     const int s0 = w * seg, s1 = min(V, s0 + seg);
     float c1 = 0.f, cT = 0.f;
-    for (int i = s0 + lane; i < s1; i += 64) {
-        float dz = z[i] - mx;
-        c1 += __expf(dz);
-        cT += __expf(dz * invT);
+    if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0) {
+        const float4* z4 = reinterpret_cast<const float4*>(z);
+        for (int i = s0 / 4 + lane; i < s1 / 4; i += 64) {
+            const float4 q = z4[i];
+            const float d0 = q.x - mx, d1 = q.y - mx, d2 = q.z - mx, d3 = q.w - mx;
+            c1 += (__expf(d0) + __expf(d1)) + (__expf(d2) + __expf(d3));
+            cT += (__expf(d0 * invT) + __expf(d1 * invT)) + (__expf(d2 * invT) + __expf(d3 * invT));
+        }
+    } else {
+        for (int i = s0 + lane; i < s1; i += 64) {
+            float dz = z[i] - mx;
+            c1 += __expf(dz);
+            cT += __expf(dz * invT);
+        }
     }
     c1 = wave_sum(c1);
     cT = wave_sum(cT);
