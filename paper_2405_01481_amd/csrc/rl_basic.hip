@@ -393,34 +393,55 @@ __global__ __launch_bounds__(1024) void rope_append_split_kernel(const float* pa
     const float2* rt = rope + (int64_t)pos * half;
     const int64_t page = bt[(int64_t)tok_slot[n] * mpps + pos / geo.PT];
     const int st = pos % geo.PT;
-    const int npairs = (Hq + 2 * Hkv) * half;
-    for (int i = threadIdx.x; i < npairs; i += 1024) {
-        const int head = i / half, j = i % half;
+    // a thread owns four consecutive pairs (j .. j+3, and their partners j + hd/2 ..): 16-byte loads of every
+    // split's partials, all requested before the first add
+    const int nquads = (Hq + 2 * Hkv) * half / 4;
+    for (int i = threadIdx.x; i < nquads; i += 1024) {
+        const int head = i / (half / 4), j = (i % (half / 4)) * 4;
         const int c0 = head * hd + j;
-        float p0[RL_MAX_SPLITS], p1[RL_MAX_SPLITS];
+        float a[4] = {0.f, 0.f, 0.f, 0.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
+        // eight splits at a time (their loads all in flight together), summed in split order
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float4 p0[8], p1[8];
 #pragma unroll
-        for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
-            if (sp < nsplit) { p0[sp] = row[sp * split_stride + c0]; p1[sp] = row[sp * split_stride + c0 + half]; }
-        float a = 0.f, b = 0.f;
+            for (int sp = 0; sp < 8; ++sp)
+                if (s0 + sp < nsplit) {
+                    p0[sp] = *reinterpret_cast<const float4*>(row + (s0 + sp) * split_stride + c0);
+                    p1[sp] = *reinterpret_cast<const float4*>(row + (s0 + sp) * split_stride + c0 + half);
+                }
 #pragma unroll
-        for (int sp = 0; sp < RL_MAX_SPLITS; ++sp)
-            if (sp < nsplit) { a += p0[sp]; b += p1[sp]; }
+            for (int sp = 0; sp < 8; ++sp)
+                if (s0 + sp < nsplit) {
+                    a[0] += p0[sp].x; a[1] += p0[sp].y; a[2] += p0[sp].z; a[3] += p0[sp].w;
+                    b[0] += p1[sp].x; b[1] += p1[sp].y; b[2] += p1[sp].z; b[3] += p1[sp].w;
+                }
+        }
         if (head < Hq + Hkv) {
-            float2 cs = rt[j];
-            float r0 = a * cs.x - b * cs.y, r1 = b * cs.x + a * cs.y;
-            a = r0; b = r1;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float2 cs = rt[j + t];
+                const float r0 = a[t] * cs.x - b[t] * cs.y, r1 = b[t] * cs.x + a[t] * cs.y;
+                a[t] = r0; b[t] = r1;
+            }
         }
         if (head < Hq) {
             T* o = q_out + (int64_t)n * Hq * hd + head * hd + j;
-            o[0] = from_f<T>(a); o[half] = from_f<T>(b);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { o[t] = from_f<T>(a[t]); o[half + t] = from_f<T>(b[t]); }
         } else if (head < Hq + Hkv) {
             const int g = head - Hq;
-            pool[geo.k_off(layer, page, g, st, j)] = from_f<T>(a);
-            pool[geo.k_off(layer, page, g, st, j + half)] = from_f<T>(b);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                pool[geo.k_off(layer, page, g, st, j + t)] = from_f<T>(a[t]);
+                pool[geo.k_off(layer, page, g, st, j + t + half)] = from_f<T>(b[t]);
+            }
         } else {
             const int g = head - Hq - Hkv;
-            pool[geo.v_off(layer, page, g, st, j)] = from_f<T>(a);
-            pool[geo.v_off(layer, page, g, st, j + half)] = from_f<T>(b);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                pool[geo.v_off(layer, page, g, st, j + t)] = from_f<T>(a[t]);
+                pool[geo.v_off(layer, page, g, st, j + t + half)] = from_f<T>(b[t]);
+            }
         }
     }
 }
