@@ -181,18 +181,33 @@ void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------ prefill / scoring: causal attention over packed sequences
-// Workgroup = (32-query block of one sequence, kv head g); wave w handles query head g*G + w,
-// so the waves of a workgroup stream the SAME keys and values (one trip through L2 for the
-// whole GQA group).  Per 32-key block: S^T (32 keys x 32 queries) by 32x32x16 MFMAs with K
-// rows as A and Q^T as B; base-2 online softmax per query (a lane owns one query column);
-// O^T += V^T P^T where the lane's own S^T registers, rounded to fp16, are the B operand and
-// V^T comes from the dim-major value buffer (two 8-byte loads per MFMA).
+// Workgroup = (32-query block of one sequence, kv head g); wave w handles query head g*G + w, so the
+// waves of a workgroup need the SAME keys and values.  Per 32-key block the K tile (32 keys x hd) and the
+// V^T tile (hd dims x 32 keys, from the dim-major value buffer) are staged ONCE per workgroup into LDS by
+// global -> LDS loads -- row-contiguous 16-byte pieces, whole rows per request; fetching the operands in
+// MFMA layout straight from memory instead makes every lane of a load touch a different row, and the
+// address path of the CU, not the MFMAs or the caches, then sets the pace -- and every wave reads its
+// operand fragments from there.  Two stages: the tile of block kb+1 is requested right after the barrier
+// that opens block kb.  16-byte chunks are XOR-swizzled on the source side of the loads (K: chunk ^ row%16
+// for 256-byte rows, chunk ^ (row/2)%8 for 128-byte rows; V^T: chunk ^ (row/4)%4) so that the fragment
+// reads spread over the banks.  The loads are issued from inline assembly and waited for by hand (the
+// compiler would otherwise make each of them complete at the next barrier).
+//   S^T (32 keys x 32 queries) by 32x32x16 MFMAs with K rows as A and Q^T as B; base-2 online softmax per
+//   query (a lane owns one query column); O^T += V^T P^T where the lane's own S^T registers, rounded to
+//   fp16, are the B operand.
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 template <int HD>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
     constexpr int KSTEPS = HD / 16, DB = HD / 32;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int KT = 32 * HD * 2;              // bytes of a K tile; the V^T tile is as large
+    constexpr int STG = 2 * KT;                  // one stage: K tile then V^T tile
+    constexpr int NI = 2 * KT / 1024;            // 1 KB load instructions per stage (K: first half)
+    constexpr int KCH = HD / 8;                  // 16-byte chunks per K row
+    constexpr int KRPI = 64 / KCH;               // K rows per load instruction
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STG];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 31, g2 = lane >> 5;
     const int4 blk = a.blocks[blockIdx.x];          // (row start, length, query block, -)
     const int start = blk.x, len = blk.y, qb = blk.z;
@@ -200,6 +215,30 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
     const int qi = qb * 32 + col;                   // this lane's query (position in the sequence)
     const int qrow = start + min(qi, len - 1);
     const int kvw = a.Hkv * HD;
+
+    // staging: instruction i of the stage (i = wave, wave + G, ...) moves 1 KB
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    const f16_t* kg = a.k + (int64_t)start * kvw + g * HD;               // K rows of this sequence, head g
+    const f16_t* vg = a.vT + (int64_t)g * HD * a.vt_cap + start;          // V^T rows (dims) of head g
+#define AP_STAGE(stage, kb)                                                                                      \
+    for (int i_ = wave; i_ < NI; i_ += G) {                                                                      \
+        const unsigned sa_ = lds_base + (stage) * STG + i_ * 1024;                                               \
+        unsigned off_;                                                                                           \
+        const f16_t* base_;                                                                                      \
+        if (i_ < NI / 2) {                       /* K: KRPI rows of KCH chunks */                                \
+            const int r_ = i_ * KRPI + lane / KCH, pc_ = lane % KCH;                                             \
+            const int lc_ = pc_ ^ (HD == 128 ? (r_ & 15) : ((r_ >> 1) & 7));                                     \
+            off_ = (unsigned)(((kb) * 32 + r_) * kvw + lc_ * 8) * 2u;                                            \
+            base_ = kg;                                                                                          \
+        } else {                                 /* V^T: 16 dims of 4 chunks (32 keys) */                        \
+            const int r_ = (i_ - NI / 2) * 16 + (lane >> 2), pc_ = lane & 3;                                     \
+            const int lc_ = pc_ ^ ((r_ >> 2) & 3);                                                               \
+            off_ = (unsigned)(r_ * a.vt_cap + (kb) * 32 + lc_ * 8) * 2u;                                         \
+            base_ = vg;                                                                                          \
+        }                                                                                                        \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                             \
+                     :: "s"(sa_), "v"(off_), "s"(base_) : "memory");                                             \
+    }
 
     half8 qf[KSTEPS];
 #pragma unroll
@@ -212,26 +251,37 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
     const float scale = a.scale * LOG2E;
+    // this lane's fragment addresses inside a stage
+    const int ksw = HD == 128 ? (col & 15) : ((col >> 1) & 7);
+    const int k_row = col * (HD * 2);                       // K row `col`
+    const int vsw = (col >> 2) & 3;                         // same for rows d*32 + col
 
+    AP_STAGE(0, 0)
     for (int kb = 0; kb <= qb; ++kb) {
-        const int krow0 = start + kb * 32;
+        const int st = kb & 1;
+        // the tile of block kb has landed (this wave's part: its only loads in flight); after the barrier
+        // every wave's part has, and every wave is done with the other stage
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        AP_STAGE(1 - st, min(kb + 1, qb))                   // the last trip re-requests its own block, unused
+        const char* kt = smem + st * STG;
+        const char* vt = kt + KT;
         // S^T = K Q^T
-        floatx16 st;
+        floatx16 stt;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st[r] = 0.f;
-        const f16_t* kp = a.k + (int64_t)(krow0 + col) * kvw + g * HD + g2 * 8;
+        for (int r = 0; r < 16; ++r) stt[r] = 0.f;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
-            half8 kf = *reinterpret_cast<const half8*>(kp + s * 16);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], st, 0, 0, 0);
+            const half8 kf = *reinterpret_cast<const half8*>(kt + k_row + (((s * 2 + g2) ^ ksw) * 16));
+            stt = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], stt, 0, 0, 0);
         }
         // register r of this lane is key kb*32 + 8*(r/4) + 4*g2 + r%4 for query qi
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = kb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
-            st[r] = (key <= qi) ? st[r] * scale : -INFINITY;
-            mx = fmaxf(mx, st[r]);
+            stt[r] = (key <= qi) ? stt[r] * scale : -INFINITY;
+            mx = fmaxf(mx, stt[r]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
         const float m_new = fmaxf(m_run, mx);        // finite: key kb*32 <= qi for every kb <= qb
@@ -240,27 +290,29 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float e = exp2f(st[r] - m_new);
+            float e = exp2f(stt[r] - m_new);
             ps += e;
             pf[r >> 3][r & 7] = (f16_t)e;
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
-        // O^T += V^T P^T
+        // O^T += V^T P^T: the lane needs keys kk*16 + 4*g2 .. +4 and kk*16 + 8 + 4*g2 .. +4 of dim d*32 + col
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-            const f16_t* vp = a.vT + ((int64_t)g * HD + d * 32 + col) * a.vt_cap + krow0 + 4 * g2;
+            const char* vr = vt + (d * 32 + col) * 64 + g2 * 8;
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                half4 lo = *reinterpret_cast<const half4*>(vp + kk * 16);
-                half4 hi = *reinterpret_cast<const half4*>(vp + kk * 16 + 8);
+                const half4 lo = *reinterpret_cast<const half4*>(vr + (((kk * 2) ^ vsw) * 16));
+                const half4 hi = *reinterpret_cast<const half4*>(vr + (((kk * 2 + 1) ^ vsw) * 16));
                 half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kk], o[d], 0, 0, 0);
             }
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the workgroup has ended
+#undef AP_STAGE
     l_run += __shfl_xor(l_run, 32, RL_WAVE);
     if (qi < len) {
         const float inv = 1.0f / l_run;
