@@ -228,7 +228,10 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         if (i_ < NI / 2) {                       /* K: KRPI rows of KCH chunks */                                \
             const int r_ = i_ * KRPI + lane / KCH, pc_ = lane % KCH;                                             \
             const int lc_ = pc_ ^ (HD == 128 ? (r_ & 15) : ((r_ >> 1) & 7));                                     \
-            off_ = (unsigned)(((kb) * 32 + r_) * kvw + lc_ * 8) * 2u;                                            \
+            /* tile row r_ holds key rho(r_): the middle two 4-row groups of every 16 are swapped, so that a */  \
+            /* lane's S^T registers 8kk .. 8kk+7 are eight CONSECUTIVE keys (one 16-byte V^T chunk)         */  \
+            const int key_ = (r_ & ~12) | ((r_ & 4) << 1) | ((r_ & 8) >> 1);                                     \
+            off_ = (unsigned)(((kb) * 32 + key_) * kvw + lc_ * 8) * 2u;                                          \
             base_ = kg;                                                                                          \
         } else {                                 /* V^T: 16 dims of 4 chunks (32 keys) */                        \
             const int r_ = (i_ - NI / 2) * 16 + (lane >> 2), pc_ = lane & 3;                                     \
@@ -275,11 +278,11 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
             const half8 kf = *reinterpret_cast<const half8*>(kt + k_row + (((s * 2 + g2) ^ ksw) * 16));
             stt = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], stt, 0, 0, 0);
         }
-        // register r of this lane is key kb*32 + 8*(r/4) + 4*g2 + r%4 for query qi
+        // register r of this lane is tile row 8*(r/4) + 4*g2 + r%4, which holds key kb*32 + 16*(r/8) + 8*g2 + r%8
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int key = kb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
+            const int key = kb * 32 + 16 * (r >> 3) + 8 * g2 + (r & 7);
             stt[r] = (key <= qi) ? stt[r] * scale : -INFINITY;
             mx = fmaxf(mx, stt[r]);
         }
@@ -296,17 +299,15 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
-        // O^T += V^T P^T: the lane needs keys kk*16 + 4*g2 .. +4 and kk*16 + 8 + 4*g2 .. +4 of dim d*32 + col
+        // O^T += V^T P^T: the lane needs keys kk*16 + 8*g2 .. +8 of dim d*32 + col: one 16-byte chunk
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-            const char* vr = vt + (d * 32 + col) * 64 + g2 * 8;
+            const char* vr = vt + (d * 32 + col) * 64;
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const half4 lo = *reinterpret_cast<const half4*>(vr + (((kk * 2) ^ vsw) * 16));
-                const half4 hi = *reinterpret_cast<const half4*>(vr + (((kk * 2 + 1) ^ vsw) * 16));
-                half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const half8 vf = *reinterpret_cast<const half8*>(vr + (((kk * 2 + g2) ^ vsw) * 16));
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kk], o[d], 0, 0, 0);
             }
         }
