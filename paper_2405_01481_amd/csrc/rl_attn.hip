@@ -278,32 +278,42 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
             const half8 kf = *reinterpret_cast<const half8*>(kt + k_row + (((s * 2 + g2) ^ ksw) * 16));
             stt = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], stt, 0, 0, 0);
         }
-        // register r of this lane is tile row 8*(r/4) + 4*g2 + r%4, which holds key kb*32 + 16*(r/8) + 8*g2 + r%8
-        float mx = -INFINITY;
+        // register r of this lane is tile row 8*(r/4) + 4*g2 + r%4, which holds key kb*32 + 16*(r/8) + 8*g2 + r%8.
+        // Only the diagonal block needs the causal mask; the running maximum is kept in raw (unscaled) units,
+        // so that exp2(scale * (s - m)) is one fused multiply-add and one exp2 per element.
+        if (kb == qb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = kb * 32 + 16 * (r >> 3) + 8 * g2 + (r & 7);
-            stt[r] = (key <= qi) ? stt[r] * scale : -INFINITY;
-            mx = fmaxf(mx, stt[r]);
+            for (int r = 0; r < 16; ++r) {
+                const int key = kb * 32 + 16 * (r >> 3) + 8 * g2 + (r & 7);
+                if (key > qi) stt[r] = -INFINITY;
+            }
         }
+        float mx = stt[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, stt[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
         const float m_new = fmaxf(m_run, mx);        // finite: key kb*32 <= qi for every kb <= qb
-        const float alpha = exp2f(m_run - m_new);
+        const float alpha = exp2f((m_run - m_new) * scale);
+        const float nms = -m_new * scale;
         half8 pf[2];
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float e = exp2f(stt[r] - m_new);
+            float e = exp2f(fmaf(stt[r], scale, nms));
             ps += e;
             pf[r >> 3][r & 7] = (f16_t)e;
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
+        // the accumulators are rescaled only when some query's maximum moved (rare after the first blocks)
+        const bool rescale = __any(alpha != 1.0f);
         // O^T += V^T P^T: the lane needs keys kk*16 + 8*g2 .. +8 of dim d*32 + col: one 16-byte chunk
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
+            if (rescale) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+            }
             const char* vr = vt + (d * 32 + col) * 64;
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
