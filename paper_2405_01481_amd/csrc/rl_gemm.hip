@@ -689,6 +689,8 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // 32-row bands of this wave that hold real rows (batches below 128 rows leave the upper bands idle)
+    const int nact = min(TM, max(0, (a.M - wm * TM * 32 + 31) / 32));
     for (int st = 0; st < depth - 1; ++st) RG_ISSUE(st, min(st, nk - 1))
     int fill = depth - 1, a_st = 0, w_st = 0;   // stage to refill next; stages holding tile kt
     for (int kt = 0; kt < nk; ++kt) {
@@ -708,11 +710,12 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
             _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                      \
                 bw[set][j] = *reinterpret_cast<const u32x4_t*>(smem + fw[sl] + wo + j * 4096);                  \
             _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                      \
-                af[set][i] = *reinterpret_cast<const half8*>(smem + fa[sl] + ao + i * 4096);                    \
+                if (i < nact) af[set][i] = *reinterpret_cast<const half8*>(smem + fa[sl] + ao + i * 4096);      \
         }
-        RG_READ(0, 0)
+        if (nact > 0) RG_READ(0, 0)
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl) {
+            if (nact == 0) break;   // every row of this wave is past M: it only stages and keeps the barriers
             if (sl < 3) RG_READ((sl + 1) & 1, sl + 1)
             __builtin_amdgcn_sched_barrier(0);
             half8 bf[TN];
@@ -722,7 +725,7 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[sl & 1][i], bf[j], acc[i][j], 0, 0, 0);
+                    if (i < nact) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[sl & 1][i], bf[j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
 #undef RG_READ
