@@ -175,6 +175,8 @@ def main():
                     help="variable-length generation instead of the headline step: Q prompts with response limits "
                          "from a long-tailed distribution (mean about 351 tokens), run once through "
                          "rollout_generate_queue and once as fixed batches that wait for their longest row")
+    ap.add_argument("--no-shadow", action="store_true",
+                    help="do not give the policy a buffer for the library's fp16 copy (decode GEMMs then convert on the fly)")
     ap.add_argument("--progress", action="store_true", help="phase markers with elapsed time on stderr")
     ap.add_argument("--pin-gb", type=float, default=24.0, help="with --ref-host: most host memory to pin, in GB")
     ap.add_argument("--ref-host", action="store_true",
@@ -216,6 +218,15 @@ def main():
         G = 1024                     # cap of the synthetic response lengths
     Lmax = Pmax + G
     cfg = R.make_cfg(shape, B, Lmax, max_chunk_tokens=max(Lmax, args.chunk))
+    def policy_shadow(cfg):
+        # a buffer for the library's fp16 copy of the policy, when a third of the free memory holds it (the KV pool,
+        # the workspace and, without --ref-host, the reference weights are still to come)
+        nb = R.rollout_weight_shadow_bytes(cfg)
+        free, _ = torch.cuda.mem_get_info()
+        if args.no_shadow or nb == 0 or nb > free // 3:
+            return None
+        return torch.empty(nb, dtype=torch.uint8, device=dev)
+
     if args.ref_host:
         # the reference never has to be device-resident: made one tensor at a time and moved to pinned host memory
         host_bytes = {"pinned": 0, "pageable": 0}
@@ -237,10 +248,10 @@ def main():
             wr["layers"].append({k: pin(v) for k, v in synth.make_layer(shape, wl.ref_seed, l, dev).items()})
         torch.cuda.empty_cache()
         staging = torch.empty(R.rollout_weight_staging_bytes(cfg), dtype=torch.uint8, device=dev)
-        Wp, Wr = R.Weights(wp), R.Weights(wr, staging=staging)
+        Wp, Wr = R.Weights(wp, shadow=policy_shadow(cfg)), R.Weights(wr, staging=staging)
     else:
         wr = synth.make_weights(shape, wl.ref_seed, dev)
-        Wp, Wr = R.Weights(wp), R.Weights(wr)
+        Wp, Wr = R.Weights(wp, shadow=policy_shadow(cfg)), R.Weights(wr)
     if args.progress:
         print("[bench] weights ready", file=sys.stderr, flush=True)
     ro = R.Rollout(cfg, Wp, dev)
@@ -278,6 +289,8 @@ def main():
 
     def one_step(timed):
         ev[0].record()
+        if Wp.shadow is not None:
+            ro.rollout_refresh_policy()      # a PPO step starts from updated weights: the fp16 copy is rebuilt, timed
         ro.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)
         ev[1].record()
         if args.progress:
@@ -394,6 +407,7 @@ def main():
         "config": {"workload": args.workload, "shape": shape.name, "layers": shape.n_layers, "batch": B,
                    "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
                    "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
+                   "policy_fp16_copy": Wp.shadow is not None,
                    "reference": ("host, streamed (%.0f GB pinned, %.0f GB pageable)" % (host_bytes["pinned"] / 1e9, host_bytes["pageable"] / 1e9)) if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
         "kl_exact_s": kl_exact_s,

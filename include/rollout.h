@@ -83,7 +83,12 @@ typedef struct rl_weights {
                                        overlap with compute -- and the set is streamed through `staging`.
                                        Accepted by score_logprobs_kl only; rollout_init wants location 0. */
     void* staging;                  /* location 1: dev buffer of rollout_weight_staging_bytes(cfg) bytes, 256-byte
-                                       aligned, scratch for the duration of the call.  Ignored for location 0. */
+                                       aligned, scratch for the duration of the call.
+                                       location 0: read only for the POLICY given to rollout_init / rollout_set_policy,
+                                       where it is optional (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg)
+                                       bytes, 256-byte aligned, owned by the context until it is destroyed or given
+                                       another policy, in which the library keeps an fp16 copy of the bf16 matrices for
+                                       the decode GEMMs (same results bit for bit, about a tenth faster decode). */
     size_t staging_bytes;
 } rl_weights;
 
@@ -99,6 +104,9 @@ typedef struct rl_sample_cfg {
  * (0 if cfg is NULL or invalid). */
 size_t rollout_workspace_bytes(const rl_model_cfg* cfg);
 size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg);
+/* Bytes of the optional fp16 copy of a device-resident bf16 policy (rl_weights.staging of the policy): the
+ * per-layer matrices and the LM head, i.e. about the size of the policy; 0 for fp32 configurations. */
+size_t rollout_weight_shadow_bytes(const rl_model_cfg* cfg);
 /* Bytes of rl_weights.staging for a host-resident weight set (location 1): two layers of weights, one
  * [vocab, d_model] table and the fp32 residual stream of max_batch sequences of max_seq tokens. */
 size_t rollout_weight_staging_bytes(const rl_model_cfg* cfg);
@@ -224,11 +232,17 @@ int rollout_check(rl_ctx* ctx, void* stream);
 
 /* Generate with another weight set from now on (Section 3.1 / 3.2: the actor's weights change every PPO
  * step and the generation engine has to pick them up).  The library uses weights in place, so there is
- * nothing to copy: values updated IN PLACE at the same addresses need no call at all; this call swaps the
+ * nothing to copy: values updated IN PLACE at the same addresses need no call at all (unless the policy has an
+ * fp16 copy: then rollout_refresh_policy); this call swaps the
  * pointers (same shapes and dtype, location 0), drops all live sequences -- their caches belong to the old
  * weights -- and the captured decode step.  The caller must have waited for work that uses the old set.
  * Errors: RL_EINVAL. */
 int rollout_set_policy(rl_ctx* ctx, const rl_weights* policy);
+
+/* The policy's values were updated IN PLACE: rebuild the fp16 copy (if the policy came with a buffer for one; the
+ * conversion is queued on `stream`) and drop all live sequences.  Without a copy this only drops the sequences.
+ * Errors: RL_EINVAL. */
+int rollout_refresh_policy(rl_ctx* ctx, void* stream);
 
 /* Forget all sequences and return every page to the pool. */
 int rollout_reset(rl_ctx* ctx);

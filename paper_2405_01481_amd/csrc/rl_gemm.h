@@ -8,6 +8,7 @@ struct GemmArgs {
     const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
     int lda = 0;
     const bf16_t* W = nullptr;  // [Wrows, K] row-major
+    int w_f16 = 0;              // decode GEMM only: W points at an fp16 copy made by k_bf16_to_f16 (no conversion in the kernel)
     int M = 0, N = 0, K = 0;    // N = output columns (MG_SWIGLU: d_ffn)
     int Wrows = 0;              // filled by the launcher
     int n_blocks_n = 0;         // filled by the launcher
@@ -58,3 +59,6 @@ int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode);
 bool k_gemm_decode_supported(int epi, int N, int K);   // K and tile columns multiples of 128
 int k_gemm_decode_splits_used(int K, int splits);
 void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s);
+// dst[i] = fp16(src[i]) for n bf16 values (n multiple of 8, both 16-byte aligned), bit for bit what the GEMM
+// kernels compute when they convert on the fly.
+void k_bf16_to_f16(const void* src, void* dst, int64_t n, hipStream_t s);

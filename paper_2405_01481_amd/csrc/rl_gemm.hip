@@ -634,7 +634,7 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
 // wait counts hold to the end; vmcnt(0) before the epilogue keeps loads from landing in LDS after the
 // workgroup has ended.  16-byte chunks of a row are XOR-swizzled with (row >> 1) & 7 on the source side
 // of the loads: fragment reads are bank-conflict free without padding.
-template <int EPI, int WGM, int WGN>
+template <int EPI, int WGM, int WGN, bool WF16>
 __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
     constexpr int BN = 128, DW = 5, DA = 3, ST = 16384;
     constexpr int TM = 128 / WGM / 32, TN = BN / WGN / 32;
@@ -720,7 +720,7 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
             __builtin_amdgcn_sched_barrier(0);
             half8 bf[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = bf16x8_to_half8(bw[sl & 1][j]);
+            for (int j = 0; j < TN; ++j) bf[j] = WF16 ? __builtin_bit_cast(half8, bw[sl & 1][j]) : bf16x8_to_half8(bw[sl & 1][j]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -854,18 +854,36 @@ int k_gemm_decode_splits_used(int K, int splits) {
     return (units + per - 1) / per;
 }
 
-template <int EPI, int WGM, int WGN>
-static void launch_ring(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
+template <int EPI, int WGM, int WGN, bool WF16>
+static void launch_ring_t(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
     constexpr int lds = 8 * 16384;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_ring_kernel<EPI, WGM, WGN>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute((const void*)gemm_ring_kernel<EPI, WGM, WGN, WF16>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
     dim3 grid(8 * ((n_blocks_n + 7) / 8), 1, splits);
-    gemm_ring_kernel<EPI, WGM, WGN><<<grid, 512, lds, s>>>(b);
+    gemm_ring_kernel<EPI, WGM, WGN, WF16><<<grid, 512, lds, s>>>(b);
+}
+template <int EPI, int WGM, int WGN>
+static void launch_ring(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
+    if (a.w_f16) launch_ring_t<EPI, WGM, WGN, true>(a, n_blocks_n, splits, s);
+    else launch_ring_t<EPI, WGM, WGN, false>(a, n_blocks_n, splits, s);
+}
+
+// fp16 copy of a bf16 weight tensor, by the conversion the kernels themselves apply (so that a GEMM on the copy
+// gives the same bits); n multiple of 8
+__global__ void bf16_to_f16_kernel(const u32x4_t* src, half8* dst, int64_t n8) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n8) dst[i] = bf16x8_to_half8(src[i]);
+}
+void k_bf16_to_f16(const void* src, void* dst, int64_t n, hipStream_t s) {
+    const int64_t n8 = n / 8;
+    if (n8 <= 0) return;
+    bf16_to_f16_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, s>>>((const u32x4_t*)src, (half8*)dst, n8);
 }
 
 void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {

@@ -59,6 +59,9 @@ def lib():
         L.rollout_workspace_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_kv_pool_bytes.restype = C.c_size_t
         L.rollout_kv_pool_bytes.argtypes = [C.POINTER(rl_model_cfg)]
+        L.rollout_weight_shadow_bytes.restype = C.c_size_t
+        L.rollout_weight_shadow_bytes.argtypes = [C.POINTER(rl_model_cfg)]
+        L.rollout_refresh_policy.argtypes = [vp, vp]
         L.rollout_weight_staging_bytes.restype = C.c_size_t
         L.rollout_weight_staging_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_init.argtypes = [C.POINTER(rl_model_cfg), C.POINTER(rl_weights), vp, C.c_size_t, vp, C.c_size_t,
@@ -112,6 +115,10 @@ def rollout_kv_pool_bytes(cfg: rl_model_cfg) -> int:
     return int(lib().rollout_kv_pool_bytes(C.byref(cfg)))
 
 
+def rollout_weight_shadow_bytes(cfg: rl_model_cfg) -> int:
+    return int(lib().rollout_weight_shadow_bytes(C.byref(cfg)))
+
+
 def rollout_weight_staging_bytes(cfg: rl_model_cfg) -> int:
     return int(lib().rollout_weight_staging_bytes(C.byref(cfg)))
 
@@ -123,9 +130,10 @@ class Weights:
 
     _LAYER = ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")
 
-    def __init__(self, w, staging=None):
+    def __init__(self, w, staging=None, shadow=None):
         self.tensors = w
         self.staging = staging
+        self.shadow = shadow
         n = len(w["layers"])
         self._arrays = {}
         s = rl_weights()
@@ -146,6 +154,11 @@ class Weights:
             s.location = 1
             s.staging = staging.data_ptr()
             s.staging_bytes = staging.numel() * staging.element_size()
+        elif shadow is not None:
+            # device-resident policy with a buffer for the library's fp16 copy (rollout_weight_shadow_bytes)
+            assert shadow.is_cuda
+            s.staging = shadow.data_ptr()
+            s.staging_bytes = shadow.numel() * shadow.element_size()
         self.struct = s
 
 
@@ -251,6 +264,9 @@ class Rollout:
     def rollout_set_policy(self, policy: Weights):
         _chk(lib().rollout_set_policy(self.h, C.byref(policy.struct)))
         self.policy = policy            # keep the tensors alive
+
+    def rollout_refresh_policy(self):
+        _chk(lib().rollout_refresh_policy(self.h, _stream()))
 
     def rollout_reset(self):
         _chk(lib().rollout_reset(self.h))

@@ -21,7 +21,8 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"rollout_init", "rollout_decode_step", "rollout_generate", "score_logprobs_kl"} <= set(names)
-    assert {"ppo_rewards", "score_values", "score_kl_exact", "rollout_generate_queue", "rollout_set_policy"} <= set(names)
+    assert {"ppo_rewards", "score_values", "score_kl_exact", "rollout_generate_queue", "rollout_set_policy",
+            "rollout_refresh_policy", "rollout_weight_shadow_bytes"} <= set(names)
     lib = R.lib()
     for n in names:
         assert hasattr(lib, n), n

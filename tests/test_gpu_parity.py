@@ -534,6 +534,51 @@ def test_random_ragged_batches_tuned_against_plain(seed):
     ro.close()
 
 
+def test_policy_fp16_copy_gives_identical_rollouts():
+    """A policy given with a buffer for the library's fp16 copy (decode GEMMs then read the copy instead of
+    converting bf16 weights on the fly): rollouts must be bit-identical to those without it, the copy must
+    follow an in-place update after rollout_refresh_policy, and a short buffer must be refused."""
+    shape, B, G = MINI128, 5, 9
+    wa, wb = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
+    cfg = R.make_cfg(shape, B, 64)
+    nbytes = R.rollout_weight_shadow_bytes(cfg)
+    assert nbytes > 0
+    shadow = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ids, lens = synth.make_prompts(shape.vocab, B, 40, 20, 71)
+    side = torch.cuda.Stream()
+
+    def gen(ro):
+        with torch.cuda.stream(side):
+            r = _generate(ro, ids, lens, G, 1.0, seed=9)
+            side.synchronize()
+        return r
+
+    plain_a = R.Rollout(cfg, R.Weights(wa), DEV)
+    want_a = gen(plain_a)
+    plain_a.close()
+    plain_b = R.Rollout(cfg, R.Weights(wb), DEV)
+    want_b = gen(plain_b)
+    plain_b.close()
+    ro = R.Rollout(cfg, R.Weights(wa, shadow=shadow), DEV)
+    got_a = gen(ro)
+    assert np.array_equal(got_a[0], want_a[0]) and np.array_equal(got_a[2], want_a[2])
+    # in place: A's tensors take B's values; the copy follows only after the refresh call
+    for k in ("tok_embed", "final_norm", "lm_head"):
+        wa[k].copy_(wb[k])
+    for la, lb in zip(wa["layers"], wb["layers"]):
+        for k in la:
+            la[k].copy_(lb[k])
+    torch.cuda.synchronize()
+    ro.rollout_refresh_policy()
+    got_b = gen(ro)
+    assert np.array_equal(got_b[0], want_b[0]) and np.array_equal(got_b[2], want_b[2])
+    ro.close()
+    with pytest.raises(R.RolloutError) as e:
+        R.Rollout(cfg, R.Weights(wb, shadow=shadow[:nbytes // 2]), DEV)
+    assert e.value.code == R.RL_ENOSPACE
+    assert R.rollout_weight_shadow_bytes(R.make_cfg(MINI32F, 2, 32)) == 0
+
+
 def test_long_context_decode_uses_split_kv():
     """Contexts of 200-300 tokens: the decode attention runs with several KV splits per
     (sequence, kv head) and merges them; ragged lengths leave partial and empty splits."""
