@@ -81,14 +81,15 @@ typedef struct rl_weights {
                                        1 = every tensor pointer above (globals and the entries of the per-layer
                                        arrays) is HOST memory -- pinned (hipHostMalloc) if the transfers are to
                                        overlap with compute -- and the set is streamed through `staging`.
-                                       Accepted by score_logprobs_kl only; rollout_init wants location 0. */
+                                       Accepted by score_logprobs_kl and score_values; rollout_init, rollout_set_policy
+                                       and score_kl_exact want location 0. */
     void* staging;                  /* location 1: dev buffer of rollout_weight_staging_bytes(cfg) bytes, 256-byte
                                        aligned, scratch for the duration of the call.
                                        location 0: read only for the POLICY given to rollout_init / rollout_set_policy,
                                        where it is optional (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg)
                                        bytes, 256-byte aligned, owned by the context until it is destroyed or given
                                        another policy, in which the library keeps an fp16 copy of the bf16 matrices for
-                                       the decode GEMMs (same results bit for bit, about a tenth faster decode). */
+                                       the decode GEMMs (same results bit for bit; those GEMMs run 5-10 % faster). */
     size_t staging_bytes;
 } rl_weights;
 
