@@ -55,8 +55,9 @@ typedef struct rl_model_cfg {
     float rope_base;          /* theta_j = rope_base^(-2j/head_dim) */
     float rms_eps;
     int32_t dtype;            /* RL_FP32: fp32 weights, activations and KV cache.  RL_BF16: bf16 weights;
-                                 activations between kernels and the KV cache are fp16 (11-bit significand),
-                                 accumulation and the residual stream fp32 */
+                                 activations between kernels and the KV cache are fp16 (11-bit significand; pairs
+                                 of fp16 values, about 22 bits, in the first layer: see
+                                 rollout_set_precise_layers), accumulation and the residual stream fp32 */
     int32_t max_batch;        /* most sequences alive at once */
     int32_t max_seq;          /* longest sequence, prompt + generated tokens */
     int32_t page_tokens;      /* tokens per KV page (16) */
@@ -83,14 +84,15 @@ typedef struct rl_weights {
                                        overlap with compute -- and the set is streamed through `staging`.
                                        Accepted by score_logprobs_kl and score_values; rollout_init, rollout_set_policy
                                        and score_kl_exact want location 0. */
-    void* staging;                  /* location 1: dev buffer of rollout_weight_staging_bytes(cfg) bytes, 256-byte
-                                       aligned, scratch for the duration of the call.
-                                       location 0: read only for the POLICY given to rollout_init / rollout_set_policy,
-                                       where it is optional (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg)
-                                       bytes, 256-byte aligned, owned by the context until it is destroyed or given
-                                       another policy, in which the library keeps an fp16 copy of the bf16 matrices for
-                                       the decode GEMMs (same results bit for bit; those GEMMs run 5-10 % faster). */
+    void* staging;                  /* location 1 only: dev buffer of rollout_weight_staging_bytes(cfg) bytes,
+                                       256-byte aligned, scratch for the duration of the call.  Ignored for location 0. */
     size_t staging_bytes;
+    void* fp16_copy;                /* read only for the POLICY given to rollout_init / rollout_set_policy, optional
+                                       (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg) bytes, 256-byte
+                                       aligned, owned by the context until it is destroyed or given another policy, in
+                                       which the library keeps an fp16 copy of the bf16 matrices for the decode GEMMs
+                                       (same results bit for bit; those GEMMs then skip the conversion). */
+    size_t fp16_copy_bytes;
 } rl_weights;
 
 typedef struct rl_sample_cfg {
@@ -105,7 +107,7 @@ typedef struct rl_sample_cfg {
  * (0 if cfg is NULL or invalid). */
 size_t rollout_workspace_bytes(const rl_model_cfg* cfg);
 size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg);
-/* Bytes of the optional fp16 copy of a device-resident bf16 policy (rl_weights.staging of the policy): the
+/* Bytes of the optional fp16 copy of a device-resident bf16 policy (rl_weights.fp16_copy of the policy): the
  * per-layer matrices and the LM head, i.e. about the size of the policy; 0 for fp32 configurations. */
 size_t rollout_weight_shadow_bytes(const rl_model_cfg* cfg);
 /* Bytes of rl_weights.staging for a host-resident weight set (location 1): two layers of weights, one
@@ -256,8 +258,18 @@ const char* rollout_last_error(void);
  * impl 1 = tuned gfx950 kernels where they exist (bf16 MFMA GEMMs, MFMA
  * attention, fused LM-head log-sum-exp).  Default 1 for bf16, 0 for fp32.
  * impl 2 = impl 1, except that the large-M GEMMs take their 256 x 256-tile kernel for every shape it
- * supports instead of only where the grid fills the chip (lets small test shapes reach that kernel). */
+ * supports instead of only where the grid fills the chip (lets small test shapes reach that kernel).
+ * Drops all live sequences (their caches were written by the other kernels). */
 int rollout_set_impl(rl_ctx* ctx, int32_t impl);
+
+/* Tuned bf16 path only: the first n layers (0 <= n <= 2, default 1) carry their activations -- GEMM inputs,
+ * q, k, v, softmax probabilities, attention output, FFN activation, and their share of the KV cache -- as PAIRS
+ * of fp16 values (hi + lo, about 22 significant bits) instead of single fp16 values; their GEMMs and attention
+ * take twice / three times the MFMA work.  Rounding in the first layer alone accounts for about nine tenths
+ * of the path's log-prob error variance against an unrounded evaluation, so n = 1 buys a three times smaller
+ * error for about 3 % more MFMA work at 32 layers.  n = 0 is the plain fp16 path.  Drops all live sequences.
+ * Errors: RL_EINVAL (n out of range, or n > 0 on a context that runs the plain kernels). */
+int rollout_set_precise_layers(rl_ctx* ctx, int32_t n);
 
 /* Kernel classes for timing. */
 enum {

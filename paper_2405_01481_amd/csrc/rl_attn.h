@@ -13,6 +13,9 @@ struct DecodeAttnArgs {
     int mpps = 0, layer = 0, Hq = 0, Hkv = 0;
     float scale = 0.f;               // 1 / sqrt(hd)
     KvGeom geo{};
+    // split = 1: q and out rows are fp16 pairs, [Hq * hd hi | Hq * hd lo]; the cache's lo planes of K and V are
+    // in layer `layer_lo` of the pool
+    int split = 0, layer_lo = 0;
 };
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s);
 
@@ -26,5 +29,8 @@ struct PrefillAttnArgs {
     const int4* blocks = nullptr;  // per workgroup: (first row of the sequence, its length, query block, 0)
     int Hq = 0, Hkv = 0, hd = 0, vt_cap = 0;
     float scale = 0.f;
+    // split = 1: fp16 pairs.  q, k and out rows are twice as wide, [hi heads | lo heads]; the lo plane of vT
+    // follows the hi plane ([2][Hkv, hd, vt_cap])
+    int split = 0;
 };
 void k_attn_prefill(const PrefillAttnArgs& a, int nblocks, hipStream_t s);

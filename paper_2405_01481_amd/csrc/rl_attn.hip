@@ -24,8 +24,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // from the split's page range; query heads g*G .. g*G+G-1 are the MFMA columns 0..G-1
 // (columns >= G are zero padding).  Per-wave results are merged through LDS; with more
 // than one split the workgroup writes an unnormalised partial (o, m, l) per head.
-template <int HD, int PT>
-__global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
+// SP: queries, keys and values are fp16 pairs (value = hi + lo; the lo planes of the cache live in layer
+// a.layer_lo, the lo halves of a query row after its hi halves).  Scores take the three leading terms
+// k_hi q_hi + k_lo q_hi + k_hi q_lo, the probabilities are split the same way for the second contraction, and
+// the output leaves as a pair: the layer then carries about 22 significant bits instead of 11.
+template <int HD, int PT, bool SP>
+__global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttnArgs a) {
     static_assert(PT == 16, "page tile is one 16-row MFMA block");
     constexpr int KS = HD / 32;    // k-steps of the 16x16x32 S^T MFMAs
     constexpr int DB = HD / 16;    // 16-dim blocks of O^T
@@ -43,13 +47,20 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
     const f16_t* kbase = a.pool + a.geo.k_off(a.layer, 0, g, 0, 0) + col * HD + g4 * 8;
     const f16_t* vbase = a.pool + a.geo.v_off(a.layer, 0, g, 0, 0) + col * PT + g4 * 4;
     const int64_t page_stride = a.geo.page_elems();
+    const int64_t lo_off = SP ? (int64_t)(a.layer_lo - a.layer) * a.geo.layer_elems() : 0;   // hi plane -> lo plane
+    const int qrow = (SP ? 2 : 1) * a.Hq * HD;       // elements per query / output row
 
     // Q^T operand: lane (head col, k-group g4) holds q[head][s*32 + g4*8 .. +8)
-    half8 qf[KS];
+    half8 qf[KS], ql[SP ? KS : 1];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        if (col < G) qf[s] = *reinterpret_cast<const half8*>(a.q + ((int64_t)b * a.Hq + g * G + col) * HD + s * 32 + g4 * 8);
+        const f16_t* qp = a.q + (int64_t)b * qrow + (g * G + col) * HD + s * 32 + g4 * 8;
+        if (col < G) qf[s] = *reinterpret_cast<const half8*>(qp);
         else qf[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (SP) {
+            if (col < G) ql[s] = *reinterpret_cast<const half8*>(qp + a.Hq * HD);
+            else ql[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
     }
     const float scale = a.scale * LOG2E;       // softmax in base 2
     float m_run = -INFINITY, l_run = 0.f;
@@ -59,30 +70,41 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
 
     // One page per iteration; the next page's K and V tiles are requested before the current
     // page is consumed, so a wave always has a page in flight.
-    half8 kf[KS], kn[KS];
-    half4 vf[DB], vn[DB];
+    half8 kf[KS], kn[KS], kfl[SP ? KS : 1], knl[SP ? KS : 1];
+    half4 vf[DB], vn[DB], vfl[SP ? DB : 1], vnl[SP ? DB : 1];
     int p = pbeg + wave;
+#define AD_FETCH(pg)                                                                                             \
+    {                                                                                                            \
+        _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                                         \
+            kn[s] = *reinterpret_cast<const half8*>(kbase + (pg) * page_stride + s * 32);                        \
+            if (SP) knl[s] = *reinterpret_cast<const half8*>(kbase + lo_off + (pg) * page_stride + s * 32);      \
+        }                                                                                                        \
+        _Pragma("unroll") for (int d = 0; d < DB; ++d) {                                                         \
+            vn[d] = *reinterpret_cast<const half4*>(vbase + (pg) * page_stride + d * 16 * PT);                   \
+            if (SP) vnl[d] = *reinterpret_cast<const half4*>(vbase + lo_off + (pg) * page_stride + d * 16 * PT); \
+        }                                                                                                        \
+    }
     if (p < pend) {
         const int64_t pg = bt[p];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kn[s] = *reinterpret_cast<const half8*>(kbase + pg * page_stride + s * 32);
-#pragma unroll
-        for (int d = 0; d < DB; ++d) vn[d] = *reinterpret_cast<const half4*>(vbase + pg * page_stride + d * 16 * PT);
+        AD_FETCH(pg)
     }
     for (; p < pend; p += 4) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) kf[s] = kn[s];
+        for (int s = 0; s < KS; ++s) { kf[s] = kn[s]; if (SP) kfl[s] = knl[s]; }
 #pragma unroll
-        for (int d = 0; d < DB; ++d) vf[d] = vn[d];
+        for (int d = 0; d < DB; ++d) { vf[d] = vn[d]; if (SP) vfl[d] = vnl[d]; }
         {
             const int pn = min(p + 4, pend - 1);          // the last iteration re-reads a valid page, unused
             const int64_t pg = bt[pn];
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kn[s] = *reinterpret_cast<const half8*>(kbase + pg * page_stride + s * 32);
-#pragma unroll
-            for (int d = 0; d < DB; ++d) vn[d] = *reinterpret_cast<const half4*>(vbase + pg * page_stride + d * 16 * PT);
+            AD_FETCH(pg)
         }
         floatx4 s0 = {0.f, 0.f, 0.f, 0.f};
+        if (SP) {   // the two small terms first, the leading one last
+#pragma unroll
+            for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfl[s], qf[s], s0, 0, 0, 0);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], ql[s], s0, 0, 0, 0);
+        }
 #pragma unroll
         for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], qf[s], s0, 0, 0, 0);
         // lane holds keys p*16 + g4*4 + i of head `col`
@@ -97,22 +119,28 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
         const float m_new = fmaxf(m_run, mx);       // finite: the first key of page p is always valid
         const float alpha = exp2f(m_run - m_new);
-        half4 pf0;
+        half4 pf0, pl0;
         float ps = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float e0 = exp2f(s0[i] - m_new);
             ps += e0;
             pf0[i] = (f16_t)e0;
+            if (SP) pl0[i] = (f16_t)(e0 - (float)pf0[i]);
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
             acc[d] *= alpha;
+            if (SP) {
+                acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vfl[d], pf0, acc[d], 0, 0, 0);
+                acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf[d], pl0, acc[d], 0, 0, 0);
+            }
             acc[d] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf[d], pf0, acc[d], 0, 0, 0);
         }
     }
+#undef AD_FETCH
     // wave totals: l over the four key groups
     l_run += __shfl_xor(l_run, 16, RL_WAVE);
     l_run += __shfl_xor(l_run, 32, RL_WAVE);
@@ -139,7 +167,11 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
         }
         const int64_t head = (int64_t)b * a.Hq + g * G + hh;
         if (nsplit == 1) {
-            a.out[head * HD + d] = l > 0.f ? (f16_t)(o / l) : (f16_t)0.f;   // parked row (position -1): no keys, zeros
+            const float r = l > 0.f ? o / l : 0.f;                          // parked row (position -1): no keys, zeros
+            f16_t* op = a.out + (int64_t)b * qrow + (g * G + hh) * HD + d;
+            const f16_t hi = (f16_t)r;
+            op[0] = hi;
+            if (SP) op[a.Hq * HD] = (f16_t)(r - (float)hi);
         } else {
             a.part_o[(head * nsplit + split) * HD + d] = o;
             if (d == 0) {
@@ -151,9 +183,10 @@ __global__ __launch_bounds__(256, 4) void attn_decode_kernel(DecodeAttnArgs a) {
 }
 
 // Merge of split partials: out = sum_s w_s o_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+// split: the output row holds fp16 pairs, [Hq heads of hi | Hq heads of lo].
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, const float* part_ml, f16_t* out,
-                                                        int nsplit) {
+                                                        int nsplit, int Hq, int split) {
     const int64_t head = blockIdx.x;
     const int d = threadIdx.x;
     float mt = -INFINITY;
@@ -166,17 +199,26 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, con
         o += wt * part_o[(head * nsplit + s) * HD + d];
         l += wt * part_ml[(head * nsplit + s) * 2 + 1];
     }
-    out[head * HD + d] = l > 0.f ? (f16_t)(o / l) : (f16_t)0.f;
+    const float r = l > 0.f ? o / l : 0.f;
+    const f16_t hi = (f16_t)r;
+    f16_t* op = out + (head / Hq) * (int64_t)((split ? 2 : 1) * Hq * HD) + (head % Hq) * HD + d;
+    op[0] = hi;
+    if (split) op[Hq * HD] = (f16_t)(r - (float)hi);
 }
 
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
     if (B <= 0) return;
     dim3 grid(B, a.Hkv, nsplit);
-    if (a.geo.hd == 128) attn_decode_kernel<128, 16><<<grid, 256, 0, s>>>(a);
-    else attn_decode_kernel<64, 16><<<grid, 256, 0, s>>>(a);
+    if (a.split) {
+        if (a.geo.hd == 128) attn_decode_kernel<128, 16, true><<<grid, 256, 0, s>>>(a);
+        else attn_decode_kernel<64, 16, true><<<grid, 256, 0, s>>>(a);
+    } else {
+        if (a.geo.hd == 128) attn_decode_kernel<128, 16, false><<<grid, 256, 0, s>>>(a);
+        else attn_decode_kernel<64, 16, false><<<grid, 256, 0, s>>>(a);
+    }
     if (nsplit > 1) {
-        if (a.geo.hd == 128) attn_merge_kernel<128><<<B * a.Hq, 128, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit);
-        else attn_merge_kernel<64><<<B * a.Hq, 64, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit);
+        if (a.geo.hd == 128) attn_merge_kernel<128><<<B * a.Hq, 128, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit, a.Hq, a.split);
+        else attn_merge_kernel<64><<<B * a.Hq, 64, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit, a.Hq, a.split);
     }
 }
 
@@ -197,15 +239,21 @@ void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
 //   fp16, are the B operand.
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int HD>
+// SP: q, k, v are fp16 pairs (value = hi + lo; rows of q, k and the output are [hi heads | lo heads], the lo plane
+// of V^T follows the hi plane).  A stage then holds four tiles (K hi, V^T hi, K lo, V^T lo), the scores take the
+// three leading terms k_hi q_hi + k_lo q_hi + k_hi q_lo, and the probabilities are split the same way for the
+// second contraction: three MFMAs where the plain kernel has one.
+template <int HD, bool SP>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
     constexpr int KSTEPS = HD / 16, DB = HD / 32;
-    constexpr int KT = 32 * HD * 2;              // bytes of a K tile; the V^T tile is as large
-    constexpr int STG = 2 * KT;                  // one stage: K tile then V^T tile
-    constexpr int NI = 2 * KT / 1024;            // 1 KB load instructions per stage (K: first half)
+    constexpr int KT = 32 * HD * 2;              // bytes of a K tile; a V^T tile is as large
+    constexpr int NT = SP ? 4 : 2;               // tiles of a stage: K, V^T (hi), then K, V^T (lo)
+    constexpr int STG = NT * KT;
+    constexpr int NIT = KT / 1024;               // 1 KB load instructions per tile
+    constexpr int NI = NT * NIT;
     constexpr int KCH = HD / 8;                  // 16-byte chunks per K row
     constexpr int KRPI = 64 / KCH;               // K rows per load instruction
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STG];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [2 stages][STG]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 31, g2 = lane >> 5;
@@ -214,7 +262,8 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
     const int g = blockIdx.y, G = a.Hq / a.Hkv, h = g * G + wave;
     const int qi = qb * 32 + col;                   // this lane's query (position in the sequence)
     const int qrow = start + min(qi, len - 1);
-    const int kvw = a.Hkv * HD;
+    const int kvw = (SP ? 2 : 1) * a.Hkv * HD;      // elements per K row
+    const int qw = (SP ? 2 : 1) * a.Hq * HD;        // elements per query / output row
 
     // staging: instruction i of the stage (i = wave, wave + G, ...) moves 1 KB
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
@@ -223,30 +272,34 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
 #define AP_STAGE(stage, kb)                                                                                      \
     for (int i_ = wave; i_ < NI; i_ += G) {                                                                      \
         const unsigned sa_ = lds_base + (stage) * STG + i_ * 1024;                                               \
+        const int t_ = i_ / NIT, ii_ = i_ % NIT;                                                                 \
         unsigned off_;                                                                                           \
         const f16_t* base_;                                                                                      \
-        if (i_ < NI / 2) {                       /* K: KRPI rows of KCH chunks */                                \
-            const int r_ = i_ * KRPI + lane / KCH, pc_ = lane % KCH;                                             \
+        if ((t_ & 1) == 0) {                     /* K: KRPI rows of KCH chunks */                                \
+            const int r_ = ii_ * KRPI + lane / KCH, pc_ = lane % KCH;                                            \
             const int lc_ = pc_ ^ (HD == 128 ? (r_ & 15) : ((r_ >> 1) & 7));                                     \
             /* tile row r_ holds key rho(r_): the middle two 4-row groups of every 16 are swapped, so that a */  \
             /* lane's S^T registers 8kk .. 8kk+7 are eight CONSECUTIVE keys (one 16-byte V^T chunk)         */  \
             const int key_ = (r_ & ~12) | ((r_ & 4) << 1) | ((r_ & 8) >> 1);                                     \
             off_ = (unsigned)(((kb) * 32 + key_) * kvw + lc_ * 8) * 2u;                                          \
-            base_ = kg;                                                                                          \
+            base_ = kg + (t_ >> 1) * a.Hkv * HD;                                                                 \
         } else {                                 /* V^T: 16 dims of 4 chunks (32 keys) */                        \
-            const int r_ = (i_ - NI / 2) * 16 + (lane >> 2), pc_ = lane & 3;                                     \
+            const int r_ = ii_ * 16 + (lane >> 2), pc_ = lane & 3;                                               \
             const int lc_ = pc_ ^ ((r_ >> 2) & 3);                                                               \
             off_ = (unsigned)(r_ * a.vt_cap + (kb) * 32 + lc_ * 8) * 2u;                                         \
-            base_ = vg;                                                                                          \
+            base_ = vg + (int64_t)(t_ >> 1) * a.Hkv * HD * a.vt_cap;                                             \
         }                                                                                                        \
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                             \
                      :: "s"(sa_), "v"(off_), "s"(base_) : "memory");                                             \
     }
 
-    half8 qf[KSTEPS];
+    half8 qf[KSTEPS], ql[SP ? KSTEPS : 1];
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-        qf[s] = *reinterpret_cast<const half8*>(a.q + ((int64_t)qrow * a.Hq + h) * HD + s * 16 + g2 * 8);
+    for (int s = 0; s < KSTEPS; ++s) {
+        const f16_t* qp = a.q + (int64_t)qrow * qw + h * HD + s * 16 + g2 * 8;
+        qf[s] = *reinterpret_cast<const half8*>(qp);
+        if (SP) ql[s] = *reinterpret_cast<const half8*>(qp + a.Hq * HD);
+    }
     floatx16 o[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d)
@@ -273,6 +326,16 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         floatx16 stt;
 #pragma unroll
         for (int r = 0; r < 16; ++r) stt[r] = 0.f;
+        if (SP) {   // the two small terms first, the leading one last
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const int fo = k_row + (((s * 2 + g2) ^ ksw) * 16);
+                const half8 kl = *reinterpret_cast<const half8*>(kt + 2 * KT + fo);
+                const half8 kf = *reinterpret_cast<const half8*>(kt + fo);
+                stt = __builtin_amdgcn_mfma_f32_32x32x16_f16(kl, qf[s], stt, 0, 0, 0);
+                stt = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, ql[s], stt, 0, 0, 0);
+            }
+        }
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
             const half8 kf = *reinterpret_cast<const half8*>(kt + k_row + (((s * 2 + g2) ^ ksw) * 16));
@@ -295,13 +358,15 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         const float m_new = fmaxf(m_run, mx);        // finite: key kb*32 <= qi for every kb <= qb
         const float alpha = exp2f((m_run - m_new) * scale);
         const float nms = -m_new * scale;
-        half8 pf[2];
+        half8 pf[2], pl[SP ? 2 : 1];
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float e = exp2f(fmaf(stt[r], scale, nms));
             ps += e;
-            pf[r >> 3][r & 7] = (f16_t)e;
+            const f16_t eh = (f16_t)e;
+            pf[r >> 3][r & 7] = eh;
+            if (SP) pl[r >> 3][r & 7] = (f16_t)(e - (float)eh);
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
@@ -317,7 +382,13 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
             const char* vr = vt + (d * 32 + col) * 64;
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const half8 vf = *reinterpret_cast<const half8*>(vr + (((kk * 2 + g2) ^ vsw) * 16));
+                const int fo = ((kk * 2 + g2) ^ vsw) * 16;
+                const half8 vf = *reinterpret_cast<const half8*>(vr + fo);
+                if (SP) {
+                    const half8 vl = *reinterpret_cast<const half8*>(vr + 2 * KT + fo);
+                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vl, pf[kk], o[d], 0, 0, 0);
+                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pl[SP ? kk : 0], o[d], 0, 0, 0);
+                }
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kk], o[d], 0, 0, 0);
             }
         }
@@ -327,23 +398,43 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
     l_run += __shfl_xor(l_run, 32, RL_WAVE);
     if (qi < len) {
         const float inv = 1.0f / l_run;
-        f16_t* op = a.out + ((int64_t)(start + qi) * a.Hq + h) * HD;
+        f16_t* op = a.out + (int64_t)(start + qi) * qw + h * HD;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                half4 w4;
+                half4 w4, l4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w4[i] = (f16_t)(o[d][4 * j + i] * inv);
+                for (int i = 0; i < 4; ++i) {
+                    const float r = o[d][4 * j + i] * inv;
+                    w4[i] = (f16_t)r;
+                    if (SP) l4[i] = (f16_t)(r - (float)w4[i]);
+                }
                 *reinterpret_cast<half4*>(op + d * 32 + 8 * j + 4 * g2) = w4;
+                if (SP) *reinterpret_cast<half4*>(op + a.Hq * HD + d * 32 + 8 * j + 4 * g2) = l4;
             }
     }
 }
 
+template <int HD, bool SP>
+static void launch_prefill(const PrefillAttnArgs& a, int nblocks, hipStream_t s) {
+    constexpr int lds = 2 * (SP ? 4 : 2) * 32 * HD * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)attn_prefill_kernel<HD, SP>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    dim3 grid(nblocks, a.Hkv);
+    attn_prefill_kernel<HD, SP><<<grid, 64 * (a.Hq / a.Hkv), lds, s>>>(a);
+}
+
 void k_attn_prefill(const PrefillAttnArgs& a, int nblocks, hipStream_t s) {
     if (nblocks <= 0) return;
-    dim3 grid(nblocks, a.Hkv);
-    const int threads = 64 * (a.Hq / a.Hkv);
-    if (a.hd == 128) attn_prefill_kernel<128><<<grid, threads, 0, s>>>(a);
-    else attn_prefill_kernel<64><<<grid, threads, 0, s>>>(a);
+    if (a.hd == 128) {
+        if (a.split) launch_prefill<128, true>(a, nblocks, s);
+        else launch_prefill<128, false>(a, nblocks, s);
+    } else {
+        if (a.split) launch_prefill<64, true>(a, nblocks, s);
+        else launch_prefill<64, false>(a, nblocks, s);
+    }
 }

@@ -167,13 +167,23 @@ void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, floa
     else embed_kernel<bf16_t><<<n, 256, 0, s>>>(ids, (const bf16_t*)E, d, V, x, errflag);
 }
 
+// Store v as T at o[0]; with split also what the rounding left over, as T, at o[lo_off]: the pair hi + lo
+// carries about 22 significant bits when T is fp16.
+template <typename T>
+__device__ __forceinline__ void put_pair(T* o, int64_t lo_off, float v, int split) {
+    const T hi = from_f<T>(v);
+    o[0] = hi;
+    if (split) o[lo_off] = from_f<T>(v - to_f(hi));
+}
+
 // ---------------------------------------------------------------- RMSNorm: out = x * rsqrt(mean(x^2) + eps) * g
+// split: the output row is twice as wide, [d values rounded to T | d remainders] (fp16 pairs).
 template <typename T, typename TW>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* g, T* out, int d, float eps) {
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* g, T* out, int d, float eps, int split) {
     __shared__ float red[16];
     int n = blockIdx.x;
     const float* xr = x + (int64_t)n * d;
-    T* o = out + (int64_t)n * d;
+    T* o = out + (int64_t)n * d * (split ? 2 : 1);
     if (d % 4 == 0 && d <= 8192) {
         // the row is read once, 16 bytes per lane, and kept in registers between the two passes
         float4 keep[8];
@@ -192,10 +202,10 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* 
         for (int it = 0; it < 8; ++it) {
             const int j = (it * 256 + threadIdx.x) * 4;
             if (j < d) {
-                o[j] = from_f<T>(keep[it].x * rs * to_f(g[j]));
-                o[j + 1] = from_f<T>(keep[it].y * rs * to_f(g[j + 1]));
-                o[j + 2] = from_f<T>(keep[it].z * rs * to_f(g[j + 2]));
-                o[j + 3] = from_f<T>(keep[it].w * rs * to_f(g[j + 3]));
+                put_pair(o + j, d, keep[it].x * rs * to_f(g[j]), split);
+                put_pair(o + j + 1, d, keep[it].y * rs * to_f(g[j + 1]), split);
+                put_pair(o + j + 2, d, keep[it].z * rs * to_f(g[j + 2]), split);
+                put_pair(o + j + 3, d, keep[it].w * rs * to_f(g[j + 3]), split);
             }
         }
         return;
@@ -204,12 +214,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* 
     for (int j = threadIdx.x; j < d; j += 256) { float v = xr[j]; ss += v * v; }
     ss = block_sum(ss, red);
     float rs = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int j = threadIdx.x; j < d; j += 256) o[j] = from_f<T>(xr[j] * rs * to_f(g[j]));
+    for (int j = threadIdx.x; j < d; j += 256) put_pair(o + j, d, xr[j] * rs * to_f(g[j]), split);
 }
-void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s) {
+void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s, int split) {
     if (n <= 0) return;
-    if (dtype == 0) rmsnorm_kernel<float, float><<<n, 256, 0, s>>>(x, (const float*)g, (float*)out, d, eps);
-    else rmsnorm_kernel<f16_t, bf16_t><<<n, 256, 0, s>>>(x, (const bf16_t*)g, (f16_t*)out, d, eps);
+    if (dtype == 0) rmsnorm_kernel<float, float><<<n, 256, 0, s>>>(x, (const float*)g, (float*)out, d, eps, 0);
+    else rmsnorm_kernel<f16_t, bf16_t><<<n, 256, 0, s>>>(x, (const bf16_t*)g, (f16_t*)out, d, eps, split);
 }
 
 // ---------------------------------------------------------------- plain tiled GEMM  C = A[M,K] * W[N,K]^T
@@ -381,13 +391,17 @@ template <typename T>
 __global__ __launch_bounds__(1024) void rope_append_split_kernel(const float* part, int nsplit, int64_t split_stride,
                                                                  const int* tok_pos, const int* tok_slot,
                                                                  const float2* rope, T* q_out, T* pool, int layer,
-                                                                 KvGeom geo, const int* bt, int mpps, int Hq) {
+                                                                 KvGeom geo, const int* bt, int mpps, int Hq,
+                                                                 int split, int layer_lo) {
     const int n = blockIdx.x, hd = geo.hd, half = hd / 2, Hkv = geo.Hkv;
     const int pos = tok_pos[n];
     const int width = (Hq + 2 * Hkv) * hd;
     const float* row = part + (int64_t)n * width;
+    // split: q rows are fp16 pairs [Hq hd hi | Hq hd lo]; the lo planes of k and v go to layer_lo of the pool
+    const int qw = (split ? 2 : 1) * Hq * hd;
+    const int64_t lo_off = split ? (int64_t)(layer_lo - layer) * geo.layer_elems() : 0;
     if (pos < 0) {   // parked row: zero query, nothing appended to the cache
-        for (int i = threadIdx.x; i < Hq * hd; i += 1024) q_out[(int64_t)n * Hq * hd + i] = from_f<T>(0.f);
+        for (int i = threadIdx.x; i < qw; i += 1024) q_out[(int64_t)n * qw + i] = from_f<T>(0.f);
         return;
     }
     const float2* rt = rope + (int64_t)pos * half;
@@ -425,36 +439,37 @@ __global__ __launch_bounds__(1024) void rope_append_split_kernel(const float* pa
             }
         }
         if (head < Hq) {
-            T* o = q_out + (int64_t)n * Hq * hd + head * hd + j;
+            T* o = q_out + (int64_t)n * qw + head * hd + j;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) { o[t] = from_f<T>(a[t]); o[half + t] = from_f<T>(b[t]); }
+            for (int t = 0; t < 4; ++t) { put_pair(o + t, Hq * hd, a[t], split); put_pair(o + half + t, Hq * hd, b[t], split); }
         } else if (head < Hq + Hkv) {
             const int g = head - Hq;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                pool[geo.k_off(layer, page, g, st, j + t)] = from_f<T>(a[t]);
-                pool[geo.k_off(layer, page, g, st, j + t + half)] = from_f<T>(b[t]);
+                put_pair(pool + geo.k_off(layer, page, g, st, j + t), lo_off, a[t], split);
+                put_pair(pool + geo.k_off(layer, page, g, st, j + t + half), lo_off, b[t], split);
             }
         } else {
             const int g = head - Hq - Hkv;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                pool[geo.v_off(layer, page, g, st, j + t)] = from_f<T>(a[t]);
-                pool[geo.v_off(layer, page, g, st, j + t + half)] = from_f<T>(b[t]);
+                put_pair(pool + geo.v_off(layer, page, g, st, j + t), lo_off, a[t], split);
+                put_pair(pool + geo.v_off(layer, page, g, st, j + t + half), lo_off, b[t], split);
             }
         }
     }
 }
 void k_rope_append_split(int dtype, const float* part, int nsplit, int64_t split_stride, int n, const int* tok_pos,
                          const int* tok_slot, const float2* rope, void* q_out, void* pool, int layer, KvGeom geo,
-                         const int* block_table, int mpps, int Hq, hipStream_t s) {
+                         const int* block_table, int mpps, int Hq, hipStream_t s, int split, int layer_lo) {
     if (n <= 0) return;
     if (dtype == 0)
         rope_append_split_kernel<float><<<n, 1024, 0, s>>>(part, nsplit, split_stride, tok_pos, tok_slot, rope,
-                                                           (float*)q_out, (float*)pool, layer, geo, block_table, mpps, Hq);
+                                                           (float*)q_out, (float*)pool, layer, geo, block_table, mpps, Hq, 0, layer);
     else
         rope_append_split_kernel<f16_t><<<n, 1024, 0, s>>>(part, nsplit, split_stride, tok_pos, tok_slot, rope,
-                                                           (f16_t*)q_out, (f16_t*)pool, layer, geo, block_table, mpps, Hq);
+                                                           (f16_t*)q_out, (f16_t*)pool, layer, geo, block_table, mpps, Hq,
+                                                           split, layer_lo);
 }
 
 // ---------------------------------------------------------------- split-K reduce + residual add + RMSNorm
@@ -463,7 +478,7 @@ void k_rope_append_split(int dtype, const float* part, int nsplit, int64_t split
 // before adding them (in split order), so the row costs about one memory round trip.
 template <typename T, typename TW>
 __global__ __launch_bounds__(1024) void resid_norm_kernel(float* x, const float* part, int nsplit, int64_t split_stride,
-                                                          const TW* g, T* out, int d, float eps) {
+                                                          const TW* g, T* out, int d, float eps, int split) {
     __shared__ float red[16];
     const int n = blockIdx.x;
     float* xr = x + (int64_t)n * d;
@@ -489,26 +504,26 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* x, const float*
     }
     ss = block_sum(ss, red);
     const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-    T* o = out + (int64_t)n * d;
+    T* o = out + (int64_t)n * d * (split ? 2 : 1);   // split: [d values rounded to T | d remainders]
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int j = (it * 1024 + threadIdx.x) * 4;
         if (j < d) {
-            o[j + 0] = from_f<T>(keep[it].x * rs * to_f(g[j + 0]));
-            o[j + 1] = from_f<T>(keep[it].y * rs * to_f(g[j + 1]));
-            o[j + 2] = from_f<T>(keep[it].z * rs * to_f(g[j + 2]));
-            o[j + 3] = from_f<T>(keep[it].w * rs * to_f(g[j + 3]));
+            put_pair(o + j + 0, d, keep[it].x * rs * to_f(g[j + 0]), split);
+            put_pair(o + j + 1, d, keep[it].y * rs * to_f(g[j + 1]), split);
+            put_pair(o + j + 2, d, keep[it].z * rs * to_f(g[j + 2]), split);
+            put_pair(o + j + 3, d, keep[it].w * rs * to_f(g[j + 3]), split);
         }
     }
 }
 // d must be a multiple of 4 and at most 8192; nsplit at most RL_MAX_SPLITS.
 void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
-                  int n, int d, float eps, hipStream_t s) {
+                  int n, int d, float eps, hipStream_t s, int split) {
     if (n <= 0) return;
     if (dtype == 0)
-        resid_norm_kernel<float, float><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const float*)g, (float*)out, d, eps);
+        resid_norm_kernel<float, float><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const float*)g, (float*)out, d, eps, 0);
     else
-        resid_norm_kernel<f16_t, bf16_t><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const bf16_t*)g, (f16_t*)out, d, eps);
+        resid_norm_kernel<f16_t, bf16_t><<<n, 1024, 0, s>>>(x, part, nsplit, split_stride, (const bf16_t*)g, (f16_t*)out, d, eps, split);
 }
 
 // ---------------------------------------------------------------- plain attention

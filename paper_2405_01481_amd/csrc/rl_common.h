@@ -105,7 +105,8 @@ void k_prefill_state_slots(const int* ids, int ld_ids, int n, const int* seq_fir
                            const int* row_len, const int* limit, int* last_tok, int* seq_len, int* gen_count,
                            int* finished, int* step_count, int* out_row, int* seq_id, int* gen_limit, hipStream_t s);
 void k_embed(int dtype, const int* ids, int n, const void* E, int d, int V, float* x, int* errflag, hipStream_t s);
-void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s);
+// split = 1 (bf16 configurations only): the output row is a row of fp16 pairs, [d hi | d lo], value = hi + lo
+void k_rmsnorm(int dtype, const float* x, const void* g, void* out, int n, int d, float eps, hipStream_t s, int split = 0);
 void k_gemm_simple(int dtype, int epi, const void* A, int lda, const void* W, const void* W2, int M, int N, int K,
                    float* outF, void* outT, int ldc, hipStream_t s);
 void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride, int n, const int* tok_pos,
@@ -113,9 +114,9 @@ void k_rope_append(int dtype, const float* qkv, int nsplit, int64_t split_stride
                    int layer, KvGeom geo, const int* block_table, int mpps, int Hq, hipStream_t s);
 void k_rope_append_split(int dtype, const float* part, int nsplit, int64_t split_stride, int n, const int* tok_pos,
                          const int* tok_slot, const float2* rope, void* q_out, void* pool, int layer, KvGeom geo,
-                         const int* block_table, int mpps, int Hq, hipStream_t s);
+                         const int* block_table, int mpps, int Hq, hipStream_t s, int split = 0, int layer_lo = 0);
 void k_resid_norm(int dtype, float* x, const float* part, int nsplit, int64_t split_stride, const void* g, void* out,
-                  int n, int d, float eps, hipStream_t s);
+                  int n, int d, float eps, hipStream_t s, int split = 0);
 void k_attn_simple(int dtype, const void* q, const void* kc, const void* vc, const void* pool, int layer, KvGeom geo,
                    const int* block_table, int mpps, const int* tok_pos, const int* tok_slot, void* out, int n,
                    int Hq, int max_ctx, hipStream_t s);

@@ -10,6 +10,15 @@ struct GemmArgs {
     const bf16_t* W = nullptr;  // [Wrows, K] row-major
     int w_f16 = 0;              // decode GEMM only: W points at an fp16 copy made by k_bf16_to_f16 (no conversion in the kernel)
     int M = 0, N = 0, K = 0;    // N = output columns (MG_SWIGLU: d_ffn)
+    // Activations carried as fp16 pairs (value = hi + lo, about 22 significant bits): A is [M, 2 Kw] with the hi
+    // halves of a row in columns [0, Kw) and the lo halves in [Kw, 2 Kw), K = 2 Kw, and the k index into W wraps
+    // at Kw, i.e. C = A_hi W^T + A_lo W^T in one pass.  Kw = 0: plain operand, W has K columns.
+    int Kw = 0;
+    // Epilogues that emit fp16 activations (MG_SWIGLU, MG_QKV, MG_STORE_F16) write such pairs: hi where the
+    // plain value would go, lo one plane further (next to it in the row for row-major outputs, whose leading
+    // dimensions are then twice as wide; the cache's lo planes live in layer `layer_lo`).
+    int split_out = 0;
+    int layer_lo = 0;
     int Wrows = 0;              // filled by the launcher
     int n_blocks_n = 0;         // filled by the launcher
     int k_per_split = 0;        // filled by the launcher

@@ -30,6 +30,16 @@ __device__ __forceinline__ half8 bf16x8_to_half8(u32x4_t w) {
     return half8{(f16_t)p0[0], (f16_t)p0[1], (f16_t)p1[0], (f16_t)p1[1], (f16_t)p2[0], (f16_t)p2[1], (f16_t)p3[0], (f16_t)p3[1]};
 }
 
+// k index into W for k index `k` of an A operand carried as fp16 pairs ([hi | lo] along K, K = 2 Kw): both
+// halves multiply the same W columns.  For a plain operand Kw = K and nothing wraps.
+__device__ __forceinline__ int wrap_k(int k, int Kw) { return k >= Kw ? k - Kw : k; }
+
+// fp16 pair of a float: hi = fp16(v), lo = fp16(v - hi); hi + lo carries about 22 significant bits.
+__device__ __forceinline__ void split_f16(float v, f16_t& hi, f16_t& lo) {
+    hi = (f16_t)v;
+    lo = (f16_t)(v - (float)hi);
+}
+
 // Which row of W feeds LDS row r of the B tile of column-block nb.
 //  EPI_SWIGLU: the tile holds BN/2 gate rows and the matching BN/2 up rows, interleaved in
 //              blocks of 32 so that a wave's adjacent 32-column MFMA tiles are (gate, up).
@@ -118,44 +128,55 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 if (m4 >= a.M) continue;
                 int p[4];
                 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-                half4 h0, h1;
                 bool all = true;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     p[t] = m4 + t < a.M ? a.tok_pos[m4 + t] : -1;     // < 0: padding row, stored as zero
                     all = all && p[t] >= 0;
-                    h0[t] = p[t] >= 0 ? (f16_t)acc[j][4 * rq + t] : (f16_t)0.f;
-                    h1[t] = p[t] >= 0 ? (f16_t)acc[j + 1][4 * rq + t] : (f16_t)0.f;
                 }
-                if (a.v_out && a.vt_cap > 0) {
-                    f16_t* o0 = a.v_out + ((int64_t)g * hd + jj) * a.vt_cap + m4;
-                    f16_t* o1 = o0 + (int64_t)half * a.vt_cap;
-                    if (m4 + 3 < a.M) {
-                        *reinterpret_cast<half4*>(o0) = h0;
-                        *reinterpret_cast<half4*>(o1) = h1;
-                    } else {
+                // plane 0: the values rounded to fp16; plane 1 (split_out): what the rounding left over
+                auto emit = [&](const int pl) {
+                    half4 h0, h1;
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            if (m4 + t < a.M) { o0[t] = h0[t]; o1[t] = h1[t]; }
+                    for (int t = 0; t < 4; ++t) {
+                        const float f0 = p[t] >= 0 ? acc[j][4 * rq + t] : 0.f, f1 = p[t] >= 0 ? acc[j + 1][4 * rq + t] : 0.f;
+                        const f16_t r0 = (f16_t)f0, r1 = (f16_t)f1;
+                        h0[t] = pl == 0 ? r0 : (f16_t)(f0 - (float)r0);
+                        h1[t] = pl == 0 ? r1 : (f16_t)(f1 - (float)r1);
                     }
-                }
-                if (a.pool) {
-                    if (all && p[0] % 4 == 0 && p[3] == p[0] + 3) {   // four tokens of one sequence: same page, adjacent slots
-                        const int64_t page = a.block_table[(int64_t)a.tok_slot[m4] * a.mpps + p[0] / a.geo.PT];
-                        const int st = p[0] % a.geo.PT;
-                        *reinterpret_cast<half4*>(a.pool + a.geo.v_off(a.layer, page, g, st, jj)) = h0;
-                        *reinterpret_cast<half4*>(a.pool + a.geo.v_off(a.layer, page, g, st, jj + half)) = h1;
-                    } else {
+                    if (a.v_out && a.vt_cap > 0) {
+                        f16_t* o0 = a.v_out + ((int64_t)(pl * a.Hkv + g) * hd + jj) * a.vt_cap + m4;
+                        f16_t* o1 = o0 + (int64_t)half * a.vt_cap;
+                        if (m4 + 3 < a.M) {
+                            *reinterpret_cast<half4*>(o0) = h0;
+                            *reinterpret_cast<half4*>(o1) = h1;
+                        } else {
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            if (p[t] >= 0) {
-                                const int64_t page = a.block_table[(int64_t)a.tok_slot[m4 + t] * a.mpps + p[t] / a.geo.PT];
-                                const int st = p[t] % a.geo.PT;
-                                a.pool[a.geo.v_off(a.layer, page, g, st, jj)] = h0[t];
-                                a.pool[a.geo.v_off(a.layer, page, g, st, jj + half)] = h1[t];
-                            }
+                            for (int t = 0; t < 4; ++t)
+                                if (m4 + t < a.M) { o0[t] = h0[t]; o1[t] = h1[t]; }
+                        }
                     }
-                }
+                    if (a.pool) {
+                        const int lay = pl == 0 ? a.layer : a.layer_lo;
+                        if (all && p[0] % 4 == 0 && p[3] == p[0] + 3) {   // four tokens of one sequence: same page, adjacent slots
+                            const int64_t page = a.block_table[(int64_t)a.tok_slot[m4] * a.mpps + p[0] / a.geo.PT];
+                            const int st = p[0] % a.geo.PT;
+                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page, g, st, jj)) = h0;
+                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page, g, st, jj + half)) = h1;
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                if (p[t] >= 0) {
+                                    const int64_t page = a.block_table[(int64_t)a.tok_slot[m4 + t] * a.mpps + p[t] / a.geo.PT];
+                                    const int st = p[t] % a.geo.PT;
+                                    a.pool[a.geo.v_off(lay, page, g, st, jj)] = h0[t];
+                                    a.pool[a.geo.v_off(lay, page, g, st, jj + half)] = h1[t];
+                                }
+                        }
+                    }
+                };
+                emit(0);
+                if (a.split_out) emit(1);
             }
         }
     }
@@ -181,7 +202,17 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 for (int j = 0; j < TN; j += 2) {
                     int n = nb * (BN / 2) + (wn * TN + j) / 2 * 32 + lrow;
                     float g = acc[j][r], u = acc[j + 1][r];
-                    if (n < a.N) a.outH[(int64_t)m * a.ldc + n] = (f16_t)(g / (1.0f + __expf(-g)) * u);
+                    const float act = g / (1.0f + __expf(-g)) * u;
+                    if (n < a.N) {
+                        if (a.split_out) {
+                            f16_t hi, lo;
+                            split_f16(act, hi, lo);
+                            a.outH[(int64_t)m * a.ldc + n] = hi;
+                            a.outH[(int64_t)m * a.ldc + a.N + n] = lo;
+                        } else {
+                            a.outH[(int64_t)m * a.ldc + n] = (f16_t)act;
+                        }
+                    }
                 }
             } else if (EPI == MG_LSE) {
                 // this wave's TN*32 columns of row m: running (max, sum of exponentials) over the
@@ -230,25 +261,37 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                         float r0 = v0 * cs.x - v1 * cs.y, r1 = v1 * cs.x + v0 * cs.y;
                         v0 = r0; v1 = r1;
                     }
+                    // fp16 pairs (split_out): rows of q and k are twice as wide, [hi heads | lo heads]
+                    const int S = a.split_out ? 2 : 1;
+                    f16_t h0, l0, h1, l1;
+                    split_f16(v0, h0, l0);
+                    split_f16(v1, h1, l1);
                     if (head < Hq) {
-                        f16_t* o = a.q_out + (int64_t)m * Hq * hd + head * hd + jj;
-                        o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                        f16_t* o = a.q_out + (int64_t)m * Hq * hd * S + head * hd + jj;
+                        o[0] = h0; o[half] = h1;
+                        if (a.split_out) { o[Hq * hd] = l0; o[Hq * hd + half] = l1; }
                     } else if (head < Hq + Hkv) {
                         int g = head - Hq;
                         if (a.k_out) {
-                            f16_t* o = a.k_out + ((int64_t)m * Hkv + g) * hd + jj;
-                            o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                            f16_t* o = a.k_out + ((int64_t)m * Hkv * S + g) * hd + jj;
+                            o[0] = h0; o[half] = h1;
+                            if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
                         }
                         if (a.pool && !pad) {
                             int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
                             int st = pos % a.geo.PT;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = (f16_t)v0;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = (f16_t)v1;
+                            a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = h0;
+                            a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = h1;
+                            if (a.split_out) {
+                                a.pool[a.geo.k_off(a.layer_lo, page, g, st, jj)] = l0;
+                                a.pool[a.geo.k_off(a.layer_lo, page, g, st, jj + half)] = l1;
+                            }
                         }
                     } else if (a.v_out && a.vt_cap <= 0) {   // token-major V (dim-major V and the pages: packed path above)
                         int g = head - Hq - Hkv;
-                        f16_t* o = a.v_out + ((int64_t)m * Hkv + g) * hd + jj;
-                        o[0] = (f16_t)v0; o[half] = (f16_t)v1;
+                        f16_t* o = a.v_out + ((int64_t)m * Hkv * S + g) * hd + jj;
+                        o[0] = h0; o[half] = h1;
+                        if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
                     }
                 }
             }
@@ -289,7 +332,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < W_CH; ++i) {
         int c = tid + i * 256, r = c / CPR, kc = c % CPR;
         int wr = w_row_of<EPI, BN>(r, nb, a);
-        w_src[i] = a.W + (int64_t)min(wr, a.Wrows - 1) * a.K + kc * 8;
+        w_src[i] = a.W + (int64_t)min(wr, a.Wrows - 1) * a.Kw + kc * 8;
         w_dst[i] = r * LSTR + kc * 8;
     }
 
@@ -304,7 +347,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
         _Pragma("unroll") for (int i_ = 0; i_ < A_CH; ++i_)                                      \
             ra##sl[i_] = *reinterpret_cast<const u32x4_t*>(a_src[i_] + kbeg + (kt) * BKT);        \
         _Pragma("unroll") for (int i_ = 0; i_ < W_CH; ++i_)                                      \
-            rw##sl[i_] = *reinterpret_cast<const u32x4_t*>(w_src[i_] + kbeg + (kt) * BKT);        \
+            rw##sl[i_] = *reinterpret_cast<const u32x4_t*>(w_src[i_] + wrap_k(kbeg + (kt) * BKT, a.Kw));  \
     }
 #define MG_PARK(sl, buf)                                                                         \
     {                                                                                            \
@@ -384,8 +427,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
 #undef MG_STEP_PARK
 #undef MG_STEP_LAST
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) mg_epilogue<EPI, BN, TN, WGN>(acc[i], a, m0 + wm * TM * 32 + i * 32, nb, wn, ks, lane);
+    // written out: with the largest epilogue the unroller gives up on a loop over the bands
+    static_assert(TM <= 2, "bands written out below");
+    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, ks, lane);
+    if (TM > 1) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, ks, lane);
 }
 
 // ------------------------------------------------------------------ tile GEMM with global -> LDS staging
@@ -455,7 +500,7 @@ __device__ __forceinline__ void kl_epilogue(floatx16 (&zp)[TN], floatx16 (&zr)[T
 }
 
 // The k loop of gemm_dma_kernel for one tile: acc = A[m0.., kbeg..] * W[tile nb]^T over nk k-tiles of 32.
-// Aop / Wop are the operands (row strides lda / a.K); ends with every staging load landed (vmcnt(0)).
+// Aop / Wop are the operands (row strides lda / a.Kw); ends with every staging load landed (vmcnt(0)).
 template <int EPI, int BM, int BN, int WGM, int WGN>
 __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop, int lda, const bf16_t* Wop, int m0,
                                              int nb, int kbeg, int nk, int wave, int lane, char* smem,
@@ -481,17 +526,18 @@ __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop
                 g_off[l] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
             } else {
                 const int r = ((l - BM / 64) * 4 + wave) * 16 + (lane >> 2);
-                g_off[l] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u;
+                g_off[l] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.Kw + lc * 8) * 2u;
             }
         }
     }
     const char* Ag = reinterpret_cast<const char*>(Aop + kbeg);
-    const char* Wg = reinterpret_cast<const char*>(Wop + kbeg);
+    const char* Wg = reinterpret_cast<const char*>(Wop);
+    const int kw0 = kbeg / 32, nkw = a.Kw / 32;   // W k-tile of A k-tile kt: kw0 + kt, wrapping at nkw
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 #define DG_LOAD(stage, kt, l)                                                                                   \
     {                                                                                                           \
         const unsigned sa_ = lds_base + (stage) * STAGE + ((l) * 4 + wave) * 1024;                              \
-        const char* g_ = ((l) < BM / 64 ? Ag : Wg) + (size_t)(kt) * 64;                                         \
+        const char* g_ = (l) < BM / 64 ? Ag + (size_t)(kt) * 64 : Wg + (size_t)wrap_k(kw0 + (kt), nkw) * 64;    \
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
                      :: "s"(sa_), "v"(g_off[l]), "s"(g_) : "memory");                                           \
     }
@@ -657,16 +703,17 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int r = (t * 4 + w4) * 8 + (lane >> 3);
-            g_off[t] = isW ? ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.K + lc * 8) * 2u
+            g_off[t] = isW ? ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.Kw + lc * 8) * 2u
                            : ((unsigned)min(r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
         }
     }
-    const char* gbase = isW ? reinterpret_cast<const char*>(a.W + kbeg) : reinterpret_cast<const char*>(a.A + kbeg);
+    const char* gbase = isW ? reinterpret_cast<const char*>(a.W) : reinterpret_cast<const char*>(a.A + kbeg);
+    const int kw0 = kbeg / 64, nkw = a.Kw / 64;   // W k-tile of A k-tile kt: kw0 + kt, wrapping at nkw
     const int depth = isW ? DW : DA;
     const unsigned ring = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem + (isW ? 0 : DW * ST) + w4 * 1024;
 #define RG_ISSUE(stage, kt)                                                                                     \
     {                                                                                                           \
-        const char* g_ = gbase + (size_t)(kt) * 128;                                                            \
+        const char* g_ = gbase + (size_t)(isW ? wrap_k(kw0 + (kt), nkw) : (kt)) * 128;                          \
         _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                         \
             const unsigned sa_ = ring + (stage) * ST + t * 4096;                                                \
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                        \
@@ -787,19 +834,20 @@ static bool use_big(int epi, const GemmArgs& a, int splits) {
     if (!a.big_mode || splits != 1) return false;
     const int out_cols = epi == MG_SWIGLU ? 2 * a.N : a.N;   // tile columns
     if (out_cols % 256 != 0 || a.K % 128 != 0) return false;
-    if ((uint64_t)a.M * a.lda * 2 >= (1ull << 32) || (uint64_t)a.Wrows * a.K * 2 >= (1ull << 32)) return false;
+    if ((uint64_t)a.M * a.lda * 2 >= (1ull << 32) || (uint64_t)a.Wrows * a.Kw * 2 >= (1ull << 32)) return false;
     const int64_t tiles = (int64_t)((a.M + 255) / 256) * (out_cols / 256);
     return a.big_mode >= 2 || tiles >= 512;   // one workgroup per CU: at least two rounds of 256
 }
 
 int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
     GemmArgs a;
-    a.M = M; a.N = N; a.K = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
+    a.M = M; a.N = N; a.K = K; a.Kw = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
     return use_big(MG_LSE, a, 1) ? N / 128 : N / 64;
 }
 
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return;
+    if (a.Kw <= 0) a.Kw = a.K;
     if (splits < 1) splits = 1;
     int kt = a.K / BK;
     int per = (kt + splits - 1) / splits;
@@ -888,6 +936,7 @@ void k_bf16_to_f16(const void* src, void* dst, int64_t n, hipStream_t s) {
 
 void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0 || a.M > 128) return;
+    if (a.Kw <= 0) a.Kw = a.K;
     if (epi == MG_SWIGLU) splits = 1;
     const int units = a.K / 128;
     if (splits < 1) splits = 1;

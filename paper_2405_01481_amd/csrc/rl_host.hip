@@ -45,6 +45,16 @@ static size_t esz_of(int dtype) { return dtype == RL_FP32 ? 4 : 2; }
 static const int kLogitRowsScore = 512;    // rows of logits materialised at a time by the plain scoring path
 static const int kMaxSplitK = 16;
 static const int kMaxAttnSplits = 16;
+// bf16 configurations: the first layers can carry their activations (GEMM inputs, q, k, v, softmax
+// probabilities, attention output, FFN activation, and their part of the KV cache) as fp16 pairs
+// (value = hi + lo, about 22 significant bits) instead of single fp16 values.  Rounding in the FIRST layer
+// accounts for about nine tenths of the log-prob error variance of the fp16 path against an unrounded
+// evaluation (measured per rounding point and per layer on the 1B, 8B and 70B shapes): every later layer adds
+// to a residual stream that the first layer's output dominates.  The pool and the workspace are sized for
+// kMaxPreciseLayers such layers; kDefaultPreciseLayers are used unless rollout_set_precise_layers says otherwise.
+static const int kMaxPreciseLayers = 2;
+static const int kDefaultPreciseLayers = 1;
+static int precise_cap(const rl_model_cfg& c) { return c.dtype == RL_BF16 ? std::min(kMaxPreciseLayers, c.n_layers) : 0; }
 
 static Layout make_layout(const rl_model_cfg& c) {
     Layout L{};
@@ -55,6 +65,7 @@ static Layout make_layout(const rl_model_cfg& c) {
         return o;
     };
     const size_t e = esz_of(c.dtype);
+    const size_t pw = precise_cap(c) > 0 ? 2 : 1;   // activation rows hold fp16 pairs in the precise layers
     // token rows of one pass; sequences are packed at multiples of 32 rows on the tuned path
     const int rows = (std::max(c.max_chunk_tokens, c.max_batch) + 31) / 32 * 32 + 32;
     const int nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -64,15 +75,15 @@ static Layout make_layout(const rl_model_cfg& c) {
     L.mpps = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
     L.logit_rows = std::max(c.max_batch, std::min(rows, kLogitRowsScore));
     L.x = take((size_t)rows * c.d_model * 4);
-    L.h = take((size_t)rows * c.d_model * e);
+    L.h = take((size_t)rows * c.d_model * e * pw);
     L.h_keep = take((size_t)rows * c.d_model * e);   // the policy's final hidden states while the reference runs (exact KL)
     L.qkv = take((size_t)rows * nqkv * 4);
-    L.q = take((size_t)rows * qd * e);
-    L.kbuf = take((size_t)rows * kd * e);
+    L.q = take((size_t)rows * qd * e * pw);
+    L.kbuf = take((size_t)rows * kd * e * pw);
     L.vt_cap = rows;
-    L.vbuf = take((size_t)rows * kd * e);
-    L.attn = take((size_t)rows * qd * e);
-    L.ffn = take((size_t)rows * c.d_ffn * e);
+    L.vbuf = take((size_t)rows * kd * e * pw);
+    L.attn = take((size_t)rows * qd * e * pw);
+    L.ffn = take((size_t)rows * c.d_ffn * e * pw);
     L.logits = take((size_t)L.logit_rows * c.vocab * 4);
     L.rope = take((size_t)c.max_seq * (c.head_dim / 2) * sizeof(float2));
     L.block_table = take((size_t)c.max_batch * L.mpps * 4);
@@ -134,6 +145,8 @@ struct WeightsHost {
     int location = 0;            // 0: device pointers; 1: host pointers, streamed through `staging`
     char* staging = nullptr;     // dev
     size_t staging_bytes = 0;
+    char* fp16_copy = nullptr;   // dev, optional (policy only)
+    size_t fp16_copy_bytes = 0;
 };
 
 static int copy_weights(const rl_model_cfg& c, const rl_weights* w, WeightsHost& out, const char* what,
@@ -145,6 +158,8 @@ static int copy_weights(const rl_model_cfg& c, const rl_weights* w, WeightsHost&
     out.location = w->location;
     out.staging = (char*)w->staging;
     out.staging_bytes = w->staging_bytes;
+    out.fp16_copy = (char*)w->fp16_copy;
+    out.fp16_copy_bytes = w->fp16_copy_bytes;
     if (!w->tok_embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
         !w->w_gate_up || !w->w_down)
         return fail(RL_EINVAL, "%s weights: NULL member", what);
@@ -174,6 +189,7 @@ struct rl_ctx {
     WeightsHost policy;
     KvGeom geo;
     int impl = 0;
+    int precise = 0;                 // layers [0, precise) carry fp16-pair activations (tuned path only)
     int big_mode = 1;                // GemmArgs::big_mode of every tuned GEMM
     // optional fp16 copy of the policy's matrices for the decode GEMMs (caller's buffer): bf16 pointer -> copy
     std::unordered_map<const void*, const void*> shadow_of;
@@ -291,13 +307,17 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblo
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     ProfScope ps(c, paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL, s);
+    const int sp = c->impl == 1 && l < c->precise;
     if (paged && c->impl == 1) {
         DecodeAttnArgs a;
         a.q = c->at<f16_t>(L.q); a.pool = (const f16_t*)c->pool; a.block_table = c->at<int>(L.block_table);
         a.tok_pos = c->at<int>(L.tok_pos); a.out = c->at<f16_t>(L.attn); a.part_o = c->at<float>(L.attn_part);
         a.part_ml = c->at<float>(L.attn_ml); a.mpps = L.mpps; a.layer = l; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads;
         a.scale = 1.0f / sqrtf((float)m.head_dim); a.geo = c->geo;
-        int nsplit = (1024 + n * m.n_kv_heads - 1) / (n * m.n_kv_heads);
+        a.split = sp; a.layer_lo = m.n_layers + l;
+        // the split count is a property of the context (most sequences, longest sequence), never of the live batch:
+        // a row's reduction order, and with it its bits, must not depend on its batch-mates
+        int nsplit = (1024 + m.max_batch * m.n_kv_heads - 1) / (m.max_batch * m.n_kv_heads);
         nsplit = std::max(1, std::min(std::min(nsplit, kMaxAttnSplits), std::max(1, L.mpps / 8)));
         k_attn_decode(a, n, nsplit, s);
         return;
@@ -307,6 +327,7 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblo
         a.q = c->at<f16_t>(L.q); a.k = c->at<f16_t>(L.kbuf); a.vT = c->at<f16_t>(L.vbuf); a.out = c->at<f16_t>(L.attn);
         a.blocks = c->at<int4>(L.blocks); a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim;
         a.vt_cap = L.vt_cap; a.scale = 1.0f / sqrtf((float)m.head_dim);
+        a.split = sp;
         k_attn_prefill(a, nblocks, s);
         return;
     }
@@ -391,55 +412,66 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
     const int* bt = c->at<int>(L.block_table);
     const float2* rope = c->at<float2>(L.rope);
     const int gcls = paged ? RL_K_GEMM_DECODE : RL_K_GEMM_PREFILL;
-    if (paged) k_rmsnorm(1, x, W.attn_norm[0], h, n, m.d_model, m.rms_eps, s);
+    // A precise layer (index below c->precise) reads and writes its activations as fp16 pairs: the GEMMs see
+    // [hi | lo] rows of twice the width whose k index wraps on the weights' side, the fp16-producing epilogues
+    // and the norm kernels write pairs, and attention works on pairs (the lo planes of the cache are layer
+    // n_layers + l of the pool).
+    auto pair_in = [](GemmArgs& g, int width, int sp) {   // A operand of `width` columns, pairs if sp
+        g.lda = sp ? 2 * width : width;
+        g.K = g.lda;
+        g.Kw = width;
+    };
+    if (paged) k_rmsnorm(1, x, W.attn_norm[l0], h, n, m.d_model, m.rms_eps, s, l0 < c->precise);
     for (int l = l0; l < l1; ++l) {
+        const int sp = l < c->precise, sp_next = l + 1 < c->precise && l + 1 < m.n_layers;
         GemmArgs g;
         g.M = n;
         if (paged) {
             // weight-streaming GEMMs, split over K; consumers reduce the partial sums
-            g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
+            g.A = h; pair_in(g, m.d_model, sp); g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv;
             g.outF = part; g.ldc = L.nqkv; g.split_stride = (int64_t)n * L.nqkv;
-            int sp = decode_splits(n, L.nqkv, m.d_model);
-            mfma(c, gcls, MG_STORE_F32, g, sp, s);
-            k_rope_append_split(1, part, sp, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
-                                m.n_q_heads, s);
+            int ks = decode_splits(n, L.nqkv, g.K);
+            mfma(c, gcls, MG_STORE_F32, g, ks, s);
+            k_rope_append_split(1, part, ks, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
+                                m.n_q_heads, s, sp, m.n_layers + l);
             attention(c, l, n, true, max_ctx, 0, s);
             g = GemmArgs();
-            g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
+            g.M = n; g.A = att; pair_in(g, qd, sp); g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
-            sp = decode_splits(n, m.d_model, qd);
-            mfma(c, gcls, MG_STORE_F32, g, sp, s);
-            k_resid_norm(1, x, part, sp, g.split_stride, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
+            ks = decode_splits(n, m.d_model, g.K);
+            mfma(c, gcls, MG_STORE_F32, g, ks, s);
+            k_resid_norm(1, x, part, ks, g.split_stride, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s, sp);
             g = GemmArgs();
-            g.M = n; g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn; g.K = m.d_model;
-            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = m.d_ffn;
+            g.M = n; g.A = h; pair_in(g, m.d_model, sp); g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn;
+            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = sp ? 2 * m.d_ffn : m.d_ffn; g.split_out = sp;
             mfma(c, gcls, MG_SWIGLU, g, 1, s);
             g = GemmArgs();
-            g.M = n; g.A = ffn; g.lda = m.d_ffn; g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model; g.K = m.d_ffn;
+            g.M = n; g.A = ffn; pair_in(g, m.d_ffn, sp); g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
-            sp = decode_splits(n, m.d_model, m.d_ffn);
-            mfma(c, gcls, MG_STORE_F32, g, sp, s);
+            ks = decode_splits(n, m.d_model, g.K);
+            mfma(c, gcls, MG_STORE_F32, g, ks, s);
             const void* next = (l + 1 < m.n_layers) ? W.attn_norm[l + 1] : W.final_norm;
-            k_resid_norm(1, x, part, sp, g.split_stride, next, h, n, m.d_model, m.rms_eps, s);
+            k_resid_norm(1, x, part, ks, g.split_stride, next, h, n, m.d_model, m.rms_eps, s, sp_next);
         } else {
-            k_rmsnorm(1, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s);
-            g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv; g.K = m.d_model;
+            k_rmsnorm(1, x, W.attn_norm[l], h, n, m.d_model, m.rms_eps, s, sp);
+            g.A = h; pair_in(g, m.d_model, sp); g.W = (const bf16_t*)W.wqkv[l]; g.N = L.nqkv;
             g.tok_pos = tpos; g.tok_slot = tslot; g.rope = rope; g.q_out = q; g.k_out = kb; g.v_out = vb;
             g.pool = write_pages ? (f16_t*)c->pool : nullptr; g.block_table = bt; g.mpps = L.mpps; g.layer = l;
             g.Hq = m.n_q_heads; g.Hkv = m.n_kv_heads; g.hd = m.head_dim; g.geo = c->geo; g.vt_cap = L.vt_cap;
+            g.split_out = sp; g.layer_lo = m.n_layers + l;
             mfma(c, gcls, MG_QKV, g, 1, s);
             attention(c, l, n, false, max_ctx, nblocks, s);
             g = GemmArgs();
-            g.M = n; g.A = att; g.lda = qd; g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model; g.K = qd;
+            g.M = n; g.A = att; pair_in(g, qd, sp); g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model;
             g.outF = x; g.ldc = m.d_model;
             mfma(c, gcls, MG_RESID, g, 1, s);
-            k_rmsnorm(1, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s);
+            k_rmsnorm(1, x, W.ffn_norm[l], h, n, m.d_model, m.rms_eps, s, sp);
             g = GemmArgs();
-            g.M = n; g.A = h; g.lda = m.d_model; g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn; g.K = m.d_model;
-            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = m.d_ffn;
+            g.M = n; g.A = h; pair_in(g, m.d_model, sp); g.W = (const bf16_t*)W.w_gate_up[l]; g.N = m.d_ffn;
+            g.up_offset = m.d_ffn; g.outH = ffn; g.ldc = sp ? 2 * m.d_ffn : m.d_ffn; g.split_out = sp;
             mfma(c, gcls, MG_SWIGLU, g, 1, s);
             g = GemmArgs();
-            g.M = n; g.A = ffn; g.lda = m.d_ffn; g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model; g.K = m.d_ffn;
+            g.M = n; g.A = ffn; pair_in(g, m.d_ffn, sp); g.W = (const bf16_t*)W.w_down[l]; g.N = m.d_model;
             g.outF = x; g.ldc = m.d_model;
             mfma(c, gcls, MG_RESID, g, 1, s);
         }
@@ -560,14 +592,14 @@ static int build_shadow(rl_ctx* c, hipStream_t s) {
     c->shadow_of.clear();
     const rl_model_cfg& m = c->cfg;
     const WeightsHost& W = c->policy;
-    if (!W.staging || m.dtype != RL_BF16 || W.location != 0) return RL_OK;
-    if (W.staging_bytes < shadow_bytes_of(m))
-        return fail(RL_ENOSPACE, "policy fp16 copy: %zu bytes given, %zu needed", W.staging_bytes, shadow_bytes_of(m));
-    if (((uintptr_t)W.staging & 255) != 0) return fail(RL_EINVAL, "policy fp16 copy buffer must be 256-byte aligned");
+    if (!W.fp16_copy || m.dtype != RL_BF16 || W.location != 0) return RL_OK;
+    if (W.fp16_copy_bytes < shadow_bytes_of(m))
+        return fail(RL_ENOSPACE, "policy fp16 copy: %zu bytes given, %zu needed", W.fp16_copy_bytes, shadow_bytes_of(m));
+    if (((uintptr_t)W.fp16_copy & 255) != 0) return fail(RL_EINVAL, "policy fp16 copy buffer must be 256-byte aligned");
     auto al = [](size_t b) { return (b + 255) / 256 * 256; };
     const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
     const size_t nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
-    char* p = W.staging;
+    char* p = W.fp16_copy;
     auto put = [&](const void* src, size_t elems) {
         k_bf16_to_f16(src, p, (int64_t)elems, s);
         c->shadow_of[src] = p;
@@ -601,8 +633,9 @@ size_t rollout_weight_shadow_bytes(const rl_model_cfg* cfg) {
 
 size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg) {
     if (validate_cfg(cfg) != RL_OK) return 0;
-    return (size_t)cfg->n_layers * 2 * (size_t)cfg->n_pages * cfg->n_kv_heads * cfg->page_tokens * cfg->head_dim *
-           esz_of(cfg->dtype);
+    // the precise layers keep a second plane (the lo halves of their fp16 pairs) as layers n_layers, n_layers + 1, ...
+    return (size_t)(cfg->n_layers + precise_cap(*cfg)) * 2 * (size_t)cfg->n_pages * cfg->n_kv_heads *
+           cfg->page_tokens * cfg->head_dim * esz_of(cfg->dtype);
 }
 
 int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* workspace, size_t workspace_bytes,
@@ -629,6 +662,7 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
     if (rc) { delete c; return rc; }
     c->geo = KvGeom{cfg->n_kv_heads, cfg->head_dim, cfg->page_tokens, cfg->n_pages};
     c->impl = fast_path_supported(*cfg) ? 1 : 0;
+    c->precise = c->impl == 1 ? std::min(kDefaultPreciseLayers, precise_cap(*cfg)) : 0;
     c->cached.assign(cfg->max_batch, 0);
     c->cap.assign(cfg->max_batch, 0);
     c->parked.assign(cfg->max_batch, 0);
@@ -706,7 +740,19 @@ int rollout_set_impl(rl_ctx* c, int32_t impl) {
         return fail(RL_EINVAL, "impl 1 / 2 need bf16 weights and GEMM widths that are multiples of 128 (K of 64)");
     c->impl = impl >= 1 ? 1 : 0;
     c->big_mode = impl == 2 ? 2 : 1;
-    return RL_OK;
+    c->precise = c->impl == 1 ? std::min(kDefaultPreciseLayers, precise_cap(c->cfg)) : 0;
+    if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return rollout_reset(c);
+}
+
+int rollout_set_precise_layers(rl_ctx* c, int32_t n) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    if (n < 0 || n > precise_cap(c->cfg))
+        return fail(RL_EINVAL, "precise layers: %d outside [0, %d] for this configuration", n, precise_cap(c->cfg));
+    if (n > 0 && c->impl != 1) return fail(RL_EINVAL, "precise layers need the tuned kernels (impl 1 or 2)");
+    c->precise = n;
+    if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return rollout_reset(c);
 }
 
 int rollout_check(rl_ctx* c, void* stream) {

@@ -36,7 +36,8 @@ class rl_model_cfg(C.Structure):
 class rl_weights(C.Structure):
     _fields_ = [("tok_embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")] + \
-               [("location", C.c_int32), ("staging", C.c_void_p), ("staging_bytes", C.c_size_t)]
+               [("location", C.c_int32), ("staging", C.c_void_p), ("staging_bytes", C.c_size_t),
+                ("fp16_copy", C.c_void_p), ("fp16_copy_bytes", C.c_size_t)]
 
 
 class rl_sample_cfg(C.Structure):
@@ -81,6 +82,7 @@ def lib():
         L.rollout_destroy.argtypes = [vp]
         L.rollout_destroy.restype = None
         L.rollout_set_impl.argtypes = [vp, i32]
+        L.rollout_set_precise_layers.argtypes = [vp, i32]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
         _lib = L
@@ -157,8 +159,8 @@ class Weights:
         elif shadow is not None:
             # device-resident policy with a buffer for the library's fp16 copy (rollout_weight_shadow_bytes)
             assert shadow.is_cuda
-            s.staging = shadow.data_ptr()
-            s.staging_bytes = shadow.numel() * shadow.element_size()
+            s.fp16_copy = shadow.data_ptr()
+            s.fp16_copy_bytes = shadow.numel() * shadow.element_size()
         self.struct = s
 
 
@@ -273,6 +275,9 @@ class Rollout:
 
     def rollout_set_impl(self, impl: int):
         _chk(lib().rollout_set_impl(self.h, impl))
+
+    def rollout_set_precise_layers(self, n: int):
+        _chk(lib().rollout_set_precise_layers(self.h, n))
 
     def rollout_profile_enable(self, kernel_class: int, every: int):
         _chk(lib().rollout_profile_enable(self.h, kernel_class, int(every)))

@@ -130,10 +130,9 @@ def test_8b_bench_configuration_full_length_row():
     layers, chunks of 16384 tokens, decode replayed as a captured graph -- so the 256 x 256 GEMM tiles,
     the ring decode GEMM at 128 rows and the paged attention at contexts up to 1023 are the kernels
     that run), checked on one full row: the oracle is teacher-forced over the row's 1024 tokens under
-    both models.  At this depth and length the fp16 activation rounding floor (about 7e-3 rms on a
-    log-prob; measured: 6.7e-3 for both models, 1 and 3 positions of 1023 beyond 2e-2, max 2.4e-2) puts
-    a few positions in a thousand beyond 2e-2, so the bar here is on the distribution: rms, the fraction
-    beyond 2e-2, and a hard cap; sampled tokens are held to the usual bracket (measured slack 5e-5)."""
+    both models.  The bar is the contract's: every scored position of the row within 2e-2 of the
+    oracle for the policy's and the reference's log-probs, the generation log-probs and the KL term;
+    every sampled token inside the oracle's CDF bracket."""
     wl = synth.WORKLOADS["8b"]
     s, B, P, G = wl.shape, wl.batch, wl.prompt_max, wl.gen
     row = 77
@@ -191,9 +190,8 @@ def test_8b_bench_configuration_full_length_row():
           "gen logp max", gen_err.max(), "kl max", kl_err.max())
     for name in stats:
         rms, frac, mx = stats[name]
-        assert rms < 1e-2 and frac < 0.01 and mx < 4e-2, (name, stats[name])
+        assert mx <= 2e-2, (name, stats[name])
     assert viol.max() < 1e-3                                 # every sampled token inside the oracle's CDF bracket
-    assert np.mean(gen_err > 2e-2) < 0.01 and gen_err.max() < 4e-2
-    # the KL term is the difference of two such log-probs: sqrt(2) times the spread
-    assert np.sqrt(np.mean(kl_err ** 2)) < 1.4e-2 and np.mean(kl_err > 2e-2) < 0.08 and kl_err.max() < 6e-2
+    assert gen_err.max() <= 2e-2
+    assert kl_err.max() <= 2e-2
     assert np.all(kl_g[:P] == 0.0) and lp_g[0] == 0.0

@@ -618,3 +618,78 @@ def test_captured_decode_graph_replays_match_eager():
     prompts = [ids[b, :lens[b]] for b in range(B)]
     verify_rollout(mp, prompts, graph[0], graph[2], 1.0, 9, 0, 1e-3, 2e-2)
     ro.close()
+
+
+PREC2 = synth.ModelShape("prec2", 2, 512, 8, 2, 128, 1024, 3072, 500000.0, "bf16", 0.02)
+PREC2_64 = synth.ModelShape("prec2_64", 2, 256, 8, 2, 64, 512, 2048, 10000.0, "bf16", 0.03)
+
+
+@pytest.mark.parametrize("shape,impl", [(PREC2, 1), (PREC2, 2), (PREC2_64, 1)], ids=["hd128", "hd128-bigtiles", "hd64"])
+def test_precise_layers_shrink_the_error(shape, impl):
+    """Layers carried as fp16 pairs (hi + lo): a two-layer model with BOTH layers precise keeps about 22
+    bits everywhere but at the final norm's output, so its error against the oracle must fall far below
+    the plain fp16 path's -- a wrong or missing lo term anywhere (GEMM k-wrap, q/k/v pairs, the three-term
+    attention products, the lo planes of the cache, the pair-writing epilogues) would leave it where it
+    was or make it worse.  Scoring (large-M kernels, ragged rows over several chunks) and generation
+    (decode kernels, paged lo planes, split-KV at contexts of 150-250 tokens) are both checked."""
+    B, G = 4, 8
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 272, chunk=384)
+    ro.rollout_set_impl(impl)
+    seqs, slens, plens = synth.make_sequences(shape.vocab, B, 200, 70, 0.4, 31)
+    want = O.score_batch(mp, mr, seqs, slens, plens, 0.1)
+    ids, lens = synth.make_prompts(shape.vocab, B, 250, 150, 32)
+    lens[1] = 9
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    rms, gen = {}, {}
+    for n in (0, 1, 2):
+        ro.rollout_set_precise_layers(n)
+        got = _score(ro, Wp, Wr, seqs, slens, plens, 0.1)
+        check_scores(*got, want, 2e-2, 0.1)
+        mask = want[0] != 0.0
+        rms[n] = float(np.sqrt(np.mean((got[0] - want[0])[mask] ** 2)))
+        g_ids, _, g_lp = _generate(ro, ids, lens, G, 1.0, seed=17)
+        st = verify_rollout(mp, prompts, g_ids, g_lp, 1.0, 17, 0, 1e-3, 2e-2)
+        # teacher-forced policy log-probs of the generated tokens, for an rms over all B * G of them
+        full = np.zeros((B, 250 + G), np.int32)
+        for b in range(B):
+            full[b, :lens[b]] = prompts[b]
+            full[b, lens[b]:lens[b] + G] = g_ids[b]
+        e = []
+        for b in range(B):
+            lp = O.score(mp, full[b, :lens[b] + G])
+            e.append(g_lp[b] - lp[lens[b]:lens[b] + G])
+        gen[n] = float(np.sqrt(np.mean(np.concatenate(e) ** 2)))
+    # What is left with both layers precise is the one rounding that stays single fp16, the final norm's output
+    # in front of the LM head: against the oracle with exactly that rounding applied, the remainder is the pairs'
+    # own residue and fp32 accumulation.
+    emul = np.zeros_like(want[0])
+    for b in range(B):
+        t = seqs[b, :slens[b]].astype(np.int64)
+        hf = O.rmsnorm(O.forward_hidden(mp, t), mp.w["final_norm"], shape.rms_eps).astype(np.float16).astype(np.float64)
+        lsm = O.log_softmax(hf @ np.asarray(mp.w["lm_head"], np.float64).T)
+        emul[b, 1:slens[b]] = lsm[np.arange(slens[b] - 1), t[1:]]
+    floor = float(np.sqrt(np.mean((got[0] - emul)[mask] ** 2)))
+    print(shape.name, "impl", impl, "scoring rms by precise layers", rms, "generation logp rms", gen,
+          "precise-2 rms against the oracle with the final-norm rounding", floor)
+    assert rms[2] < 0.5 * rms[0] and gen[2] < 0.4 * gen[0], (rms, gen)
+    assert rms[1] < rms[0] and gen[1] < gen[0], (rms, gen)
+    assert floor < 0.15 * rms[0], (floor, rms)
+    with pytest.raises(R.RolloutError):
+        ro.rollout_set_precise_layers(3)
+    ro.close()
+
+
+def test_split_kv_rows_do_not_depend_on_batch_size():
+    """Long maximum length, so the decode attention splits the keys of a (sequence, kv head) over several
+    workgroups: the number of splits must come from the context's limits, not from how many sequences are
+    live, or a row generated alone would be reduced in another order than the same row in a batch."""
+    shape = MINI128
+    B, G = 4, 10
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 640)
+    ids, lens = synth.make_prompts(shape.vocab, B, 600, 300, 71)
+    a_ids, _, a_lp = _generate(ro, ids, lens, G, 1.0, seed=23)
+    for b in range(B):
+        o, _, l = _generate(ro, ids[b:b + 1], lens[b:b + 1], G, 1.0, seed=23, base=b)
+        assert np.array_equal(o[0], a_ids[b]) and np.allclose(l[0], a_lp[b], atol=1e-6), b
+    verify_rollout(mp, [ids[b, :lens[b]] for b in range(B)], a_ids, a_lp, 1.0, 23, 0, 1e-3, 2e-2, rows=[0, 3])
+    ro.close()
