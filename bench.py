@@ -177,6 +177,10 @@ def main():
                          "rollout_generate_queue and once as fixed batches that wait for their longest row")
     ap.add_argument("--no-shadow", action="store_true",
                     help="do not give the policy a buffer for the library's fp16 copy (decode GEMMs then convert on the fly)")
+    ap.add_argument("--decode-tile-rows", type=int, default=None,
+                    help="measurement switch: decode GEMMs above this many rows use the 128 x 128 tile kernel (library default -1 = never)")
+    ap.add_argument("--precise-layers", type=int, default=None,
+                    help="measurement switch: layers carried as fp16 pairs (library default 1)")
     ap.add_argument("--progress", action="store_true", help="phase markers with elapsed time on stderr")
     ap.add_argument("--pin-gb", type=float, default=24.0, help="with --ref-host: most host memory to pin, in GB")
     ap.add_argument("--ref-host", action="store_true",
@@ -257,6 +261,10 @@ def main():
     ro = R.Rollout(cfg, Wp, dev)
     if args.impl >= 0:
         ro.rollout_set_impl(args.impl)
+    if args.decode_tile_rows is not None:
+        R.rollout_set_decode_tile_rows(args.decode_tile_rows)
+    if args.precise_layers is not None:
+        ro.rollout_set_precise_layers(args.precise_layers)
     if args.queue:
         return queue_bench(args, wl, shape, ro, B, Pmax, Pmin, dev)
     ids_np, plen = synth.make_prompts(shape.vocab, B, Pmax, Pmin, wl.prompt_seed)

@@ -271,6 +271,10 @@ int rollout_set_impl(rl_ctx* ctx, int32_t impl);
  * Errors: RL_EINVAL (n out of range, or n > 0 on a context that runs the plain kernels). */
 int rollout_set_precise_layers(rl_ctx* ctx, int32_t n);
 
+/* Measurement switch (process-wide): decode-step GEMMs of more than `rows` rows run on the 128 x 128 tile kernel
+ * instead of the LDS-ring weight streamer (default: a negative value = ring kernel for every batch). */
+int rollout_set_decode_tile_rows(int32_t rows);
+
 /* Kernel classes for timing. */
 enum {
     RL_K_GEMM_DECODE = 0,   /* weight-streaming GEMMs of a decode step */

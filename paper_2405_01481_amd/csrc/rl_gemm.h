@@ -68,6 +68,9 @@ int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode);
 bool k_gemm_decode_supported(int epi, int N, int K);   // K and tile columns multiples of 128
 int k_gemm_decode_splits_used(int K, int splits);
 void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s);
+// Measurement switch: k_gemm_decode takes the 128 x 128 tile kernel above this many rows (default 64; < 0: never).
+void k_gemm_decode_tile_above(int rows);
+
 // dst[i] = fp16(src[i]) for n bf16 values (n multiple of 8, both 16-byte aligned), bit for bit what the GEMM
 // kernels compute when they convert on the fly.
 void k_bf16_to_f16(const void* src, void* dst, int64_t n, hipStream_t s);

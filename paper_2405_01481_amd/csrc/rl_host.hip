@@ -745,6 +745,11 @@ int rollout_set_impl(rl_ctx* c, int32_t impl) {
     return rollout_reset(c);
 }
 
+int rollout_set_decode_tile_rows(int32_t rows) {
+    k_gemm_decode_tile_above(rows);
+    return RL_OK;
+}
+
 int rollout_set_precise_layers(rl_ctx* c, int32_t n) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     if (n < 0 || n > precise_cap(c->cfg))

@@ -82,6 +82,7 @@ def lib():
         L.rollout_destroy.argtypes = [vp]
         L.rollout_destroy.restype = None
         L.rollout_set_impl.argtypes = [vp, i32]
+        L.rollout_set_decode_tile_rows.argtypes = [i32]
         L.rollout_set_precise_layers.argtypes = [vp, i32]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -286,6 +287,10 @@ class Rollout:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().rollout_profile_read(self.h, kernel_class, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+
+def rollout_set_decode_tile_rows(rows: int):
+    _chk(lib().rollout_set_decode_tile_rows(int(rows)))
 
 
 def sample_cfg(seed=0, temperature=0.0, eos_id=-1, seq_id_base=0) -> rl_sample_cfg:

@@ -64,3 +64,57 @@ def check_scores(lp_gpu, lr_gpu, kl_gpu, pen_gpu, oracle_out, tol, kl_coef):
     assert np.all(lp_gpu[lp == 0.0] == 0.0) and np.all(lr_gpu[lr == 0.0] == 0.0)
     assert np.all(kl_gpu[(lp == 0.0)] == 0.0)
     return errs
+
+
+class LazyModel(O.Model):
+    """The oracle's model with its layers handed over one at a time (float64 arrays of the same values, made
+    from the torch tensors the GPU path holds), so that an 80-layer model never has to sit in host memory as
+    float64.  `conv` turns a torch tensor into such an array."""
+
+    def __init__(self, shape, w_torch, conv):
+        super().__init__(shape, {k: conv(v, np.float32) for k, v in w_torch.items() if k != "layers"})
+        self._wt, self._conv, self._at, self._cur = w_torch["layers"], conv, -1, None
+
+    def layer(self, l):
+        if l != self._at:
+            self._cur = None
+            self._cur = {k: self._conv(v, np.float64) for k, v in self._wt[l].items()}
+            self._at = l
+        return self._cur
+
+
+def check_row(model, seq, P, seed, row, gpu_logp_row, gen_ids_row=None, gen_logp_row=None, tol=2e-2, cdf_delta=1e-3,
+              upto=None):
+    """One full row against the oracle, teacher-forced over the row's own tokens: every scored position of
+    gpu_logp_row (positions 1 .. len-1, or 1 .. upto-1) within tol; if the row's generated tokens are given, each
+    inside the oracle's CDF bracket for the shared uniform (temperature 1), and the generation log-probs within
+    tol.  Returns (oracle log-probs, stats)."""
+    seq = np.asarray(seq, np.int64)
+    n = len(seq) if upto is None else upto
+    z = O.forward_logits(model, seq[:n - 1])
+    want = np.zeros(n)
+    stats = {}
+    viol = []
+    for t in range(n - 1):
+        lsm = O.log_softmax(z[t])
+        want[t + 1] = lsm[seq[t + 1]]
+        if gen_ids_row is not None and t >= P - 1 and t - (P - 1) < len(gen_ids_row):
+            k = t - (P - 1)
+            c = np.cumsum(np.exp(lsm))
+            u = O.hash_uniform(seed, row, k)
+            g = int(gen_ids_row[k])
+            lo = c[g - 1] if g > 0 else 0.0
+            viol.append(max(lo - u, u - c[g], 0.0))
+    err = np.abs(np.asarray(gpu_logp_row[:n], np.float64) - want)
+    stats["rms"] = float(np.sqrt(np.mean(err[1:] ** 2)))
+    stats["max"] = float(err.max())
+    assert err.max() <= tol, f"row {row}: log-prob error {err.max():.3e} at position {int(err.argmax())}"
+    if viol:
+        stats["cdf_viol_max"] = float(np.max(viol))
+        assert np.max(viol) < cdf_delta, f"row {row}: sampled token outside the oracle's CDF bracket by {np.max(viol):.3e}"
+    if gen_logp_row is not None:
+        G = len(gen_logp_row)
+        ge = np.abs(np.asarray(gen_logp_row, np.float64)[:max(0, n - P)] - want[P:P + G])
+        stats["gen_max"] = float(ge.max(initial=0.0))
+        assert ge.max(initial=0.0) <= tol, f"row {row}: generation log-prob error {ge.max():.3e}"
+    return want, stats
