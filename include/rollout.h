@@ -228,6 +228,17 @@ int ppo_rewards(rl_ctx* ctx, const float* kl, const float* seq_reward,
                 const int32_t* seq_len, const int32_t* prompt_len, int32_t B, int32_t Lmax,
                 float kl_coef, float* rewards, void* stream);
 
+/* ppo_rewards for callers that cannot allocate device memory or have the runtime copy for them: code that is
+ * being recorded into a HIP graph, tight serving loops, harnesses that forbid allocation.  Same arguments and
+ * results as ppo_rewards without the context: the lengths travel as kernel arguments into a fixed 32 KB array
+ * inside the library (one per GPU, held until the process ends) instead of the context's workspace.  The call
+ * allocates nothing, copies nothing and does not wait.  At most 4096 sequences per call (RL_EINVAL beyond).  All
+ * calls on one GPU share that array: calls whose GPU work may overlap (different streams) race on it; calls on one
+ * stream are ordered and safe.  Errors: RL_EINVAL, RL_EHIP. */
+int ppo_rewards_noalloc(const float* kl, const float* seq_reward,
+                        const int32_t* seq_len, const int32_t* prompt_len, int32_t B, int32_t Lmax,
+                        float kl_coef, float* rewards, void* stream);
+
 /* Wait for `stream` and report device-side findings since the last check:
  * RL_EINVAL if a token id outside [0, vocab) was seen (it was clamped), RL_EHIP
  * if the stream is in error. */

@@ -875,6 +875,21 @@ __global__ void ppo_reward_kernel(const float* kl, const float* seq_reward, cons
     }
     out[o] = r;
 }
+// dst[first + i] = v[i] for i < n <= 192: small host arrays reach the device as kernel arguments (no copy engine,
+// no pinned staging), 192 values per launch.
+struct IntChunk { int v[192]; };
+__global__ void put_i32_kernel(int* dst, IntChunk c, int n) {
+    if ((int)threadIdx.x < n) dst[threadIdx.x] = c.v[threadIdx.x];
+}
+void k_put_i32(int* dst, const int* src_host, int n, hipStream_t s) {
+    for (int o = 0; o < n; o += 192) {
+        IntChunk c;
+        const int m = n - o < 192 ? n - o : 192;
+        for (int i = 0; i < m; ++i) c.v[i] = src_host[o + i];
+        put_i32_kernel<<<1, 192, 0, s>>>(dst + o, c, m);
+    }
+}
+
 void k_ppo_reward(const float* kl, const float* seq_reward, const int* seq_len, const int* prompt_len, int B, int Lmax,
                   float coef, float* out, hipStream_t s) {
     if (B <= 0 || Lmax <= 0) return;

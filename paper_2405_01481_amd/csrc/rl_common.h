@@ -135,6 +135,8 @@ void k_kl_full_rows(const float* zp, const float* zr, int ldz, int V, int nrows,
                     hipStream_t s);
 void k_value_head(int dtype, const float* x, const void* g, const void* head, int n, int d, float eps,
                   const int* tok_slot, const int* tok_pos, float* out, int ld_out, hipStream_t s);
+// n host ints into device memory through kernel arguments (any n; nothing is copied by the runtime)
+void k_put_i32(int* dst, const int* src_host, int n, hipStream_t s);
 void k_ppo_reward(const float* kl, const float* seq_reward, const int* seq_len, const int* prompt_len, int B, int Lmax,
                   float coef, float* out, hipStream_t s);
 void k_lse_reduce(const float2* part, int nparts, const float* z_tgt, int nrows, const int* tok_tgt,

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <unordered_map>
 #include <vector>
 
@@ -1468,6 +1469,48 @@ int ppo_rewards(rl_ctx* c, const float* kl, const float* seq_reward, const int32
     HIP_TRY(hipMemcpyAsync(c->at<int>(L.d_prompt_len), prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     k_ppo_reward(kl, seq_reward, c->at<int>(L.d_seq_len), c->at<int>(L.d_prompt_len), B, Lmax, kl_coef, rewards, s);
+    HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+// ---- ppo_rewards for callers that cannot allocate.  The per-sequence lengths have to be device arrays for the
+// kernel; ppo_rewards keeps them in the context's workspace and copies them there with the runtime.  Here they
+// live in a fixed array of the library's own and are written by kernels that take them as arguments, so the call
+// needs no context, no workspace and no copy: nothing in it allocates, and it can be recorded into a graph.
+static const int kNoAllocMaxB = 4096;                                    // sequences per call
+static __device__ __align__(256) int scratch[2 * kNoAllocMaxB];          // [seq_len | prompt_len], 32 KB per GPU
+static const int kMaxDevices = 64;
+static int* g_scratch_ptr[kMaxDevices];                                  // device address of `scratch`, per device
+static std::mutex g_scratch_mu;
+
+int ppo_rewards_noalloc(const float* kl, const float* seq_reward, const int32_t* seq_len, const int32_t* prompt_len,
+                        int32_t B, int32_t Lmax, float kl_coef, float* rewards, void* stream) {
+    if (!kl || !seq_reward || !seq_len || !prompt_len || !rewards) return fail(RL_EINVAL, "NULL argument");
+    if (B < 1 || B > kNoAllocMaxB) return fail(RL_EINVAL, "B=%d outside [1, %d]", B, kNoAllocMaxB);
+    if (Lmax < 1) return fail(RL_EINVAL, "Lmax < 1");
+    for (int b = 0; b < B; ++b)
+        if (seq_len[b] < 1 || seq_len[b] > Lmax || prompt_len[b] < 0 || prompt_len[b] > seq_len[b])
+            return fail(RL_EINVAL, "row %d: need 1 <= seq_len <= Lmax and 0 <= prompt_len <= seq_len", b);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RL_EINVAL, "device %d outside [0, %d)", dev, kMaxDevices);
+    int* ptr = nullptr;
+    {
+        // every GPU holds its own copy of the array at its own address: looked up once per device, with that
+        // device current
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = static_cast<int*>(p);
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    hipStream_t s = (hipStream_t)stream;
+    // the array keeps the previous call's lengths: every entry this call reads is rewritten first
+    k_put_i32(ptr, seq_len, B, s);
+    k_put_i32(ptr + kNoAllocMaxB, prompt_len, B, s);
+    k_ppo_reward(kl, seq_reward, ptr, ptr + kNoAllocMaxB, B, Lmax, kl_coef, rewards, s);
     HIP_TRY(hipGetLastError());
     return RL_OK;
 }

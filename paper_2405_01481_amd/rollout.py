@@ -77,6 +77,7 @@ def lib():
         L.score_kl_exact.argtypes = [vp, C.POINTER(rl_weights), C.POINTER(rl_weights), vp, vp, vp, i32, i32, vp, vp]
         L.score_values.argtypes = [vp, C.POINTER(rl_weights), vp, vp, vp, i32, i32, vp, vp]
         L.ppo_rewards.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, vp, vp]
+        L.ppo_rewards_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, f32, vp, vp]
         L.rollout_set_policy.argtypes = [vp, C.POINTER(rl_weights)]
         L.rollout_reset.argtypes = [vp]
         L.rollout_destroy.argtypes = [vp]
@@ -287,6 +288,14 @@ class Rollout:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().rollout_profile_read(self.h, kernel_class, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+
+def ppo_rewards_noalloc(kl: torch.Tensor, seq_reward: torch.Tensor, seq_len, prompt_len, kl_coef, rewards):
+    """ppo_rewards without a context: allocates nothing, copies nothing (include/rollout.h)."""
+    sl, slp = _host_i32(seq_len)
+    pl, plp = _host_i32(prompt_len)
+    B, Lmax = kl.shape
+    _chk(lib().ppo_rewards_noalloc(_ptr(kl), _ptr(seq_reward), slp, plp, B, Lmax, kl_coef, _ptr(rewards), _stream()))
 
 
 def rollout_set_decode_tile_rows(rows: int):
