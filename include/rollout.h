@@ -81,11 +81,13 @@ typedef struct rl_weights {
     int32_t location;               /* 0 = device resident.
                                        1 = every tensor pointer above (globals and the entries of the per-layer
                                        arrays) is HOST memory -- pinned (hipHostMalloc) if the transfers are to
-                                       overlap with compute -- and the set is streamed through `staging`.
-                                       Accepted by score_logprobs_kl and score_values; rollout_init, rollout_set_policy
-                                       and score_kl_exact want location 0. */
-    void* staging;                  /* location 1 only: dev buffer of rollout_weight_staging_bytes(cfg) bytes,
-                                       256-byte aligned, scratch for the duration of the call.  Ignored for location 0. */
+                                       overlap with compute.  score_logprobs_kl and score_values stream such a set
+                                       layer by layer through `staging`; rollout_set_policy uploads it whole into
+                                       `staging`; rollout_init and score_kl_exact want location 0. */
+    void* staging;                  /* location 1 only, dev, 256-byte aligned.  For the scoring calls:
+                                       rollout_weight_staging_bytes(cfg) bytes, scratch for the duration of the call.
+                                       For rollout_set_policy: rollout_weight_resident_bytes(cfg) bytes, owned by the
+                                       context while this policy is in use.  Ignored for location 0. */
     size_t staging_bytes;
     void* fp16_copy;                /* read only for the POLICY given to rollout_init / rollout_set_policy, optional
                                        (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg) bytes, 256-byte
@@ -110,6 +112,9 @@ size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg);
 /* Bytes of the optional fp16 copy of a device-resident bf16 policy (rl_weights.fp16_copy of the policy): the
  * per-layer matrices and the LM head, i.e. about the size of the policy; 0 for fp32 configurations. */
 size_t rollout_weight_shadow_bytes(const rl_model_cfg* cfg);
+/* Bytes of a device-resident copy of a whole weight set: rl_weights.staging of a host-resident POLICY given to
+ * rollout_set_policy, which uploads the set into it. */
+size_t rollout_weight_resident_bytes(const rl_model_cfg* cfg);
 /* Bytes of rl_weights.staging for a host-resident weight set (location 1): two layers of weights, one
  * [vocab, d_model] table and the fp32 residual stream of max_batch sequences of max_seq tokens. */
 size_t rollout_weight_staging_bytes(const rl_model_cfg* cfg);
@@ -184,6 +189,8 @@ int rollout_generate_queue(rl_ctx* ctx, const rl_sample_cfg* sample,
  * min(Lmax, max_seq), 0 <= prompt_len[b] <= L_b.  Outputs: dev fp32 [B, Lmax],
  * any may be NULL.  reference may be NULL (policy pass only; logp_ref, kl and
  * kl_penalty must then be NULL).  Does not touch the KV cache of live sequences.
+ * policy may be NULL: the set the context currently generates with (the one given to rollout_init or the last
+ * rollout_set_policy, also when that was uploaded from host memory).
  * Either weight set may be host-resident (location 1: "reference weights streamed layer by layer"): its
  * layers are copied into the set's staging buffer on a stream of the library's own, two layers deep,
  * while the previous layer runs on `stream` for all tokens; results are identical to the resident case.
@@ -245,12 +252,19 @@ int ppo_rewards_noalloc(const float* kl, const float* seq_reward,
 int rollout_check(rl_ctx* ctx, void* stream);
 
 /* Generate with another weight set from now on (Section 3.1 / 3.2: the actor's weights change every PPO
- * step and the generation engine has to pick them up).  The library uses weights in place, so there is
- * nothing to copy: values updated IN PLACE at the same addresses need no call at all (unless the policy has an
- * fp16 copy: then rollout_refresh_policy); this call swaps the
- * pointers (same shapes and dtype, location 0), drops all live sequences -- their caches belong to the old
- * weights -- and the captured decode step.  The caller must have waited for work that uses the old set.
- * Errors: RL_EINVAL. */
+ * step and the generation engine has to pick them up; weight sets that are not in use are kept in host memory
+ * and swapped in).  Same shapes and dtype as the context's.  Drops all live sequences -- their caches belong to the
+ * old weights -- and the captured decode step.
+ *  - location 0 (device-resident set): the library uses weights in place, so this only swaps pointers (values
+ *    updated IN PLACE at the same addresses need no call at all, unless the policy has an fp16 copy: then
+ *    rollout_refresh_policy).  The caller must have waited for work that uses the old set.  Blocks until the fp16
+ *    copy, if any, is rebuilt.
+ *  - location 1 (host-resident set, pinned for the copies to be asynchronous): every tensor is copied into
+ *    policy->staging (rollout_weight_resident_bytes) on a stream of the library's own and the call returns at once;
+ *    work already queued with the old policy keeps running while the upload proceeds (the old set's memory is not
+ *    touched, so with two device buffers the next set loads while the current one generates), and every later call
+ *    that reads the policy makes its stream wait for the upload.  The host tensors must stay valid until then.
+ * Errors: RL_EINVAL, RL_ENOSPACE, RL_EHIP. */
 int rollout_set_policy(rl_ctx* ctx, const rl_weights* policy);
 
 /* The policy's values were updated IN PLACE: rebuild the fp16 copy (if the policy came with a buffer for one; the

@@ -198,6 +198,10 @@ struct rl_ctx {
     hipStream_t copy_stream = nullptr;
     hipEvent_t ev_begin = nullptr, ev_glob_copied = nullptr, ev_glob_free = nullptr;
     hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+    // a policy uploaded from host memory by rollout_set_policy: its copies (and the rebuild of the fp16 copy) run on
+    // copy_stream; every call that reads the policy first makes its stream wait for ev_policy
+    hipEvent_t ev_policy = nullptr;
+    bool policy_pending = false;
     // sequences
     int B = 0;                       // live sequences (0 = no prefill yet)
     std::vector<int> cached;         // tokens in the KV cache per slot (host mirror of seq_len; an upper bound in queue mode)
@@ -222,6 +226,10 @@ struct rl_ctx {
     } gkey{};
     hipGraphExec_t gexec = nullptr;
     bool use_graph = true;
+    // captured steps that may still be running when the policy is swapped without waiting: destroyed once the
+    // event recorded behind their last launch has completed
+    struct Retired { hipGraphExec_t g; hipEvent_t ev; };
+    std::vector<Retired> retired;
     // profiling
     int prof_on[RL_K_COUNT] = {};       // 0 off, n >= 1: time every n-th launch
     uint64_t prof_seen[RL_K_COUNT] = {};
@@ -617,6 +625,55 @@ static int build_shadow(rl_ctx* c, hipStream_t s) {
     return RL_OK;
 }
 
+static int ensure_copy_stream(rl_ctx* c);
+
+// Put the captured decode step aside (its launches may still be in flight on the stream it was captured on).
+static void retire_graph(rl_ctx* c) {
+    if (!c->gexec) return;
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess && hipEventRecord(ev, c->gkey.s) == hipSuccess) {
+        c->retired.push_back({c->gexec, ev});
+    } else {
+        if (ev) (void)hipEventDestroy(ev);
+        (void)hipStreamSynchronize(c->gkey.s);
+        (void)hipGraphExecDestroy(c->gexec);
+    }
+    c->gexec = nullptr;
+}
+// Destroy the retired steps whose work has completed (all of them, after waiting, with force).
+static void reap_graphs(rl_ctx* c, bool force) {
+    for (size_t i = 0; i < c->retired.size();) {
+        if (force) (void)hipEventSynchronize(c->retired[i].ev);
+        if (force || hipEventQuery(c->retired[i].ev) == hipSuccess) {
+            (void)hipGraphExecDestroy(c->retired[i].g);
+            (void)hipEventDestroy(c->retired[i].ev);
+            c->retired.erase(c->retired.begin() + i);
+        } else {
+            (void)hipGetLastError();
+            ++i;
+        }
+    }
+}
+
+// Bytes of a device-resident copy of a whole weight set (every tensor 256-byte aligned).
+static size_t resident_bytes_of(const rl_model_cfg& c) {
+    auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+    const size_t e = esz_of(c.dtype), d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim;
+    const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const size_t layer = 2 * al(d * e) + al(nqkv * d * e) + al(d * qd * e) + al(2 * (size_t)c.d_ffn * d * e) +
+                         al(d * (size_t)c.d_ffn * e);
+    return 2 * al((size_t)c.vocab * d * e) + al(d * e) + layer * c.n_layers;
+}
+
+// Make stream s wait for a policy upload that may still be running on the copy stream.
+static int wait_policy(rl_ctx* c, hipStream_t s) {
+    if (!c->policy_pending) return RL_OK;
+    if (hipEventQuery(c->ev_policy) == hipSuccess) { c->policy_pending = false; return RL_OK; }
+    (void)hipGetLastError();   // hipErrorNotReady is not an error
+    HIP_TRY(hipStreamWaitEvent(s, c->ev_policy, 0));
+    return RL_OK;
+}
+
 // ---------------------------------------------------------------- C ABI
 extern "C" {
 
@@ -630,6 +687,11 @@ size_t rollout_workspace_bytes(const rl_model_cfg* cfg) {
 size_t rollout_weight_shadow_bytes(const rl_model_cfg* cfg) {
     if (validate_cfg(cfg) != RL_OK) return 0;
     return shadow_bytes_of(*cfg);
+}
+
+size_t rollout_weight_resident_bytes(const rl_model_cfg* cfg) {
+    if (validate_cfg(cfg) != RL_OK) return 0;
+    return resident_bytes_of(*cfg);
 }
 
 size_t rollout_kv_pool_bytes(const rl_model_cfg* cfg) {
@@ -692,12 +754,13 @@ int rollout_init(const rl_model_cfg* cfg, const rl_weights* policy, void* worksp
 
 void rollout_destroy(rl_ctx* c) {
     if (!c) return;
+    reap_graphs(c, true);
     if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
     if (c->copy_stream) {
         (void)hipStreamSynchronize(c->copy_stream);
         (void)hipStreamDestroy(c->copy_stream);
         for (hipEvent_t e : {c->ev_begin, c->ev_glob_copied, c->ev_glob_free, c->ev_copied[0], c->ev_copied[1],
-                             c->ev_free[0], c->ev_free[1]})
+                             c->ev_free[0], c->ev_free[1], c->ev_policy})
             if (e) (void)hipEventDestroy(e);
     }
     for (int k = 0; k < RL_K_COUNT; ++k)
@@ -715,8 +778,56 @@ int rollout_reset(rl_ctx* c) {
 int rollout_set_policy(rl_ctx* c, const rl_weights* policy) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     WeightsHost w;
-    int rc = copy_weights(c->cfg, policy, w, "policy");
+    int rc = copy_weights(c->cfg, policy, w, "policy", true);
     if (rc) return rc;
+    if (w.location == 1) {
+        // Host-resident set: every tensor is copied into the caller's device buffer on the library's copy stream
+        // (so the upload overlaps with whatever the caller's streams are still running on the old policy, whose
+        // memory is not touched), and the context switches to the device copies.  Calls that read the policy make
+        // their stream wait for the upload.
+        const rl_model_cfg& m = c->cfg;
+        if (!w.staging) return fail(RL_EINVAL, "host-resident policy needs a device buffer (rl_weights.staging)");
+        if (((uintptr_t)w.staging & 255) != 0) return fail(RL_EINVAL, "policy buffer must be 256-byte aligned");
+        if (w.staging_bytes < resident_bytes_of(m))
+            return fail(RL_ENOSPACE, "policy buffer: %zu bytes given, %zu needed", w.staging_bytes, resident_bytes_of(m));
+        if ((rc = ensure_copy_stream(c))) return rc;
+        if (c->policy_pending) HIP_TRY(hipEventSynchronize(c->ev_policy));   // one upload at a time
+        auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+        const size_t e = esz_of(m.dtype), d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
+        const size_t nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+        char* p = w.staging;
+        hipStream_t cs = c->copy_stream;
+        hipError_t err = hipSuccess;
+        auto up = [&](const void*& ptr, size_t bytes) {
+            if (err == hipSuccess) err = hipMemcpyAsync(p, ptr, bytes, hipMemcpyHostToDevice, cs);
+            ptr = p;
+            p += al(bytes);
+        };
+        up(w.tok_embed, (size_t)m.vocab * d * e);
+        up(w.lm_head, (size_t)m.vocab * d * e);
+        up(w.final_norm, d * e);
+        for (int l = 0; l < m.n_layers; ++l) {
+            up(w.attn_norm[l], d * e);
+            up(w.wqkv[l], nqkv * d * e);
+            up(w.wo[l], d * qd * e);
+            up(w.ffn_norm[l], d * e);
+            up(w.w_gate_up[l], 2 * (size_t)m.d_ffn * d * e);
+            up(w.w_down[l], d * (size_t)m.d_ffn * e);
+        }
+        if (err != hipSuccess) return fail(RL_EHIP, "policy upload: %s", hipGetErrorString(err));
+        w.location = 0;
+        w.staging = nullptr;
+        w.staging_bytes = 0;
+        c->policy = w;
+        reap_graphs(c, false);
+        retire_graph(c);   // the old policy's captured step may still be replaying on the caller's stream
+        rc = build_shadow(c, cs);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(c->ev_policy, cs));
+        c->policy_pending = true;
+        return rollout_reset(c);
+    }
+    if (c->policy_pending) { HIP_TRY(hipEventSynchronize(c->ev_policy)); c->policy_pending = false; }
     c->policy = w;
     // the captured decode step holds the old pointers; caches built with the old weights are void
     if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
@@ -728,6 +839,8 @@ int rollout_set_policy(rl_ctx* c, const rl_weights* policy) {
 
 int rollout_refresh_policy(rl_ctx* c, void* stream) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    int rcw = wait_policy(c, (hipStream_t)stream);
+    if (rcw) return rcw;
     // same addresses, new values: only the fp16 copy (if there is one) has to follow; the captured step stays valid
     int rc = build_shadow(c, (hipStream_t)stream);
     if (rc) return rc;
@@ -788,6 +901,8 @@ int rollout_prefill(rl_ctx* c, const int32_t* prompt_ids, const int32_t* prompt_
     const Layout& L = c->L;
     c->B = 0;
     release_all_pages(c);
+    int rcw = wait_policy(c, s);
+    if (rcw) return rcw;
     std::vector<int> need(B);
     for (int b = 0; b < B; ++b) need[b] = prompt_len[b] - 1;
     int rc = ensure_pages(c, need, s);
@@ -870,6 +985,7 @@ int rollout_decode_step(rl_ctx* c, const rl_sample_cfg* sample, const int32_t* t
     int rc = check_sample(sample);
     if (rc) return rc;
     if (c->B < 1) return fail(RL_ESTATE, "rollout_decode_step before rollout_prefill");
+    if ((rc = wait_policy(c, (hipStream_t)stream))) return rc;
     rc = decode_step_impl(c, sample, tok_in, tok_out, logp_out, nullptr, nullptr, 0, (hipStream_t)stream);
     if (rc) return rc;
     HIP_TRY(hipGetLastError());
@@ -1017,6 +1133,7 @@ int rollout_generate_queue(rl_ctx* c, const rl_sample_cfg* sample, const int32_t
     }
     hipStream_t s = (hipStream_t)stream;
     const Layout& L = c->L;
+    if ((rc = wait_policy(c, s))) return rc;
     // entries past a row's length read eos_id (-1 when there is none) / log-prob 0
     k_fill_i32(out_ids, sample->eos_id, (int64_t)Q * Gmax, s);
     k_fill_i32(out_len, 0, Q, s);
@@ -1205,7 +1322,7 @@ static int ensure_copy_stream(rl_ctx* c) {
     if (c->copy_stream) return RL_OK;
     HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
     for (hipEvent_t* e : {&c->ev_begin, &c->ev_glob_copied, &c->ev_glob_free, &c->ev_copied[0], &c->ev_copied[1],
-                          &c->ev_free[0], &c->ev_free[1]})
+                          &c->ev_free[0], &c->ev_free[1], &c->ev_policy})
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     return RL_OK;
 }
@@ -1329,7 +1446,9 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
         return fail(RL_EINVAL, "kl outputs need logp_policy and logp_ref buffers");
     hipStream_t s = (hipStream_t)stream;
     WeightsHost wp, wr;
-    int rc = copy_weights(m, policy, wp, "policy", true);
+    int rc = RL_OK;
+    if (policy) rc = copy_weights(m, policy, wp, "policy", true);
+    else { wp = c->policy; rc = wait_policy(c, s); }   // the set the context generates with
     if (rc) return rc;
     if (reference) {
         rc = copy_weights(m, reference, wr, "reference", true);

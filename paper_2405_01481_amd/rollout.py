@@ -63,6 +63,8 @@ def lib():
         L.rollout_weight_shadow_bytes.restype = C.c_size_t
         L.rollout_weight_shadow_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_refresh_policy.argtypes = [vp, vp]
+        L.rollout_weight_resident_bytes.restype = C.c_size_t
+        L.rollout_weight_resident_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_weight_staging_bytes.restype = C.c_size_t
         L.rollout_weight_staging_bytes.argtypes = [C.POINTER(rl_model_cfg)]
         L.rollout_init.argtypes = [C.POINTER(rl_model_cfg), C.POINTER(rl_weights), vp, C.c_size_t, vp, C.c_size_t,
@@ -123,6 +125,10 @@ def rollout_weight_shadow_bytes(cfg: rl_model_cfg) -> int:
     return int(lib().rollout_weight_shadow_bytes(C.byref(cfg)))
 
 
+def rollout_weight_resident_bytes(cfg: rl_model_cfg) -> int:
+    return int(lib().rollout_weight_resident_bytes(C.byref(cfg)))
+
+
 def rollout_weight_staging_bytes(cfg: rl_model_cfg) -> int:
     return int(lib().rollout_weight_staging_bytes(C.byref(cfg)))
 
@@ -158,8 +164,8 @@ class Weights:
             s.location = 1
             s.staging = staging.data_ptr()
             s.staging_bytes = staging.numel() * staging.element_size()
-        elif shadow is not None:
-            # device-resident policy with a buffer for the library's fp16 copy (rollout_weight_shadow_bytes)
+        if shadow is not None:
+            # a policy with a buffer for the library's fp16 copy (rollout_weight_shadow_bytes)
             assert shadow.is_cuda
             s.fp16_copy = shadow.data_ptr()
             s.fp16_copy_bytes = shadow.numel() * shadow.element_size()
@@ -239,7 +245,8 @@ class Rollout:
         pl, plp = _host_i32(prompt_len)
         B, Lmax = ids.shape
         ref = C.byref(reference.struct) if reference is not None else None
-        _chk(lib().score_logprobs_kl(self.h, C.byref(policy.struct), ref, _ptr(ids), slp, plp, B, Lmax, kl_coef,
+        pol = C.byref(policy.struct) if policy is not None else None
+        _chk(lib().score_logprobs_kl(self.h, pol, ref, _ptr(ids), slp, plp, B, Lmax, kl_coef,
                                      _ptr(logp_policy), _ptr(logp_ref), _ptr(kl), _ptr(kl_penalty), _stream()))
 
     def score_kl_exact(self, policy: Weights, reference: Weights, ids: torch.Tensor, seq_len, prompt_len, kl_full):

@@ -429,6 +429,58 @@ def test_policy_weight_swap_and_in_place_update():
     ro.close()
 
 
+@pytest.mark.parametrize("shape,shadow", [(MINI128, False), (MINI128, True), (MINI32F, False)],
+                         ids=["mini128", "mini128-fp16copy", "mini32f"])
+def test_policy_swapped_in_from_host_memory(shape, shadow):
+    """Weight sets that are not in use live in (pinned) host memory and are swapped in: rollout_set_policy with a
+    host-resident set uploads it into a second device buffer on the library's copy stream and returns at once, while
+    a rollout with the old policy is still queued on the caller's stream.  That rollout must be unchanged; the next
+    one must be the NEW policy's -- checked against the oracle built on the new weights, token by token -- and
+    scoring with policy = NULL must score under the new policy."""
+    B, G = 5, 9
+    wa, wb = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
+    cfg = R.make_cfg(shape, B, 64)
+    Wa = R.Weights(wa)
+    ids, lens = synth.make_prompts(shape.vocab, B, 40, 20, 63)
+    d_ids = torch.tensor(ids, device=DEV)
+    side = torch.cuda.Stream()
+    ro = R.Rollout(cfg, Wa, DEV)
+    with torch.cuda.stream(side):
+        ref_a = _generate(ro, ids, lens, G, 1.0, seed=8)                 # policy A, for reference
+        side.synchronize()
+    buf = torch.empty(R.rollout_weight_resident_bytes(cfg), dtype=torch.uint8, device=DEV)
+    sh = torch.empty(R.rollout_weight_shadow_bytes(cfg), dtype=torch.uint8, device=DEV) if shadow else None
+    Wb_host = R.Weights(_pinned_copy(wb), staging=buf, shadow=sh)
+    out_a = torch.full((B, G), -7, dtype=torch.int32, device=DEV)
+    lp_a = torch.zeros(B, G, dtype=torch.float32, device=DEV)
+    out_b = torch.full((B, G), -7, dtype=torch.int32, device=DEV)
+    lp_b = torch.zeros(B, G, dtype=torch.float32, device=DEV)
+    with torch.cuda.stream(side):
+        ro.rollout_generate(R.sample_cfg(8, 1.0), d_ids, lens, G, out_a, None, lp_a)      # queued with policy A ...
+        ro.rollout_set_policy(Wb_host)                                                    # ... upload of B starts
+        ro.rollout_generate(R.sample_cfg(8, 1.0), d_ids, lens, G, out_b, None, lp_b)      # waits for the upload
+        side.synchronize()
+    ro.rollout_check()
+    assert np.array_equal(out_a.cpu().numpy(), ref_a[0]) and np.array_equal(lp_a.cpu().numpy(), ref_a[2])
+    mb = O.Model(shape, synth.weights_for_oracle(wb))
+    ma = O.Model(shape, synth.weights_for_oracle(wa))
+    lt, cd = _tol(shape)
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    st = verify_rollout(mb, prompts, out_b.cpu().numpy(), lp_b.cpu().numpy(), 1.0, 8, 0, cd, lt)
+    assert st["n_checked"] == B * G
+    assert not np.array_equal(out_b.cpu().numpy(), ref_a[0])
+    # scoring under "the context's policy" (now B) with A as the reference
+    seqs, slens, plens = synth.make_sequences(shape.vocab, B, 64, 20, 0.5, 64)
+    outs = [torch.full((B, 64), 9.0, dtype=torch.float32, device=DEV) for _ in range(4)]
+    ro.score_logprobs_kl(None, Wa, torch.tensor(seqs, device=DEV), slens, plens, 0.003, *outs)
+    ro.rollout_check()
+    check_scores(*[o.cpu().numpy() for o in outs], O.score_batch(mb, ma, seqs, slens, plens, 0.003), lt, 0.003)
+    with pytest.raises(R.RolloutError) as e:
+        ro.rollout_set_policy(R.Weights(_pinned_copy(wb), staging=buf[:buf.numel() // 2]))
+    assert e.value.code == R.RL_ENOSPACE
+    ro.close()
+
+
 @pytest.mark.parametrize("shape", [MINI32F, MINI128], ids=lambda s: s.name)
 def test_value_head_and_ppo_rewards(shape):
     """Critic / reward-model pass (decoder body + scalar head) and the per-token PPO reward, against the
@@ -496,11 +548,10 @@ def test_exact_kl_against_oracle(shape):
 
 
 @pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
-def test_random_ragged_batches_tuned_against_plain(seed):
+def test_random_ragged_batches_against_oracle(seed):
     """Seeded sweep over batch sizes, length mixes and chunk sizes (rows that are not multiples of the tile
-    sizes, chunks that split the batch unevenly, single-token rows): the tuned kernels in both tile modes
-    against the plain kernels (which other tests hold to the oracle) on scoring, exact KL and values, and a
-    short rollout per case."""
+    sizes, chunks that split the batch unevenly, single-token rows): the plain kernels and the tuned kernels
+    in both tile modes, each against the oracle, on scoring, exact KL, values and a short greedy rollout."""
     rng = np.random.default_rng(seed)
     shape = [MINI64, MINI128][seed % 2]
     B = int(rng.integers(1, 10))
@@ -523,14 +574,26 @@ def test_random_ragged_batches_tuned_against_plain(seed):
         g = _generate(ro, ids, pl, 6, 0.0)
         ro.rollout_check()
         res[impl] = (sc, klx.cpu().numpy(), val.cpu().numpy(), g)
+    # every kernel set against the oracle (the shapes are small: the oracle is cheap) ...
+    want_sc = O.score_batch(mp, mr, ids, lens, plens, 0.01)
+    want_kl = np.zeros((B, Lmax))
+    for b in range(B):
+        L, P = int(lens[b]), max(int(plens[b]), 1)
+        want_kl[b, P:L] = O.kl_full(mp, mr, ids[b, :L])[P:L]
+    want_val = O.values_batch(mr, head.float().cpu().numpy().astype(np.float64), ids, lens)
+    prompts = [ids[b, :pl[b]] for b in range(B)]
+    for impl in (0, 1, 2):
+        check_scores(*res[impl][0], want_sc, 2e-2, 0.01)
+        assert np.abs(res[impl][1] - want_kl).max() < 2e-2, (impl, seed)
+        assert np.all(res[impl][1][want_kl == 0.0] == 0.0)
+        assert np.abs(res[impl][2] - want_val).max() < 2e-2, (impl, seed)
+        verify_rollout(mp, prompts, res[impl][3][0], res[impl][3][2], 0.0, 4, 0, 1e-3, 2e-2)
+    # ... and the tuned sets against the plain one, which bounds how far two roundings of the same values part
     for impl in (1, 2):
         for a, b in zip(res[impl][0], res[0][0]):
             assert np.abs(a - b).max() < 6e-3, (impl, seed)
         assert np.abs(res[impl][1] - res[0][1]).max() < 6e-3
         assert np.abs(res[impl][2] - res[0][2]).max() < 6e-3
-        # greedy tokens agree wherever the plain path's own log-prob says the choice was not a near tie
-        same = res[impl][3][0] == res[0][3][0]
-        assert same.mean() > 0.9, (impl, seed, same.mean())
     ro.close()
 
 
