@@ -67,10 +67,12 @@ def score_flops(shape, lens):
     return f
 
 
-def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperature):
-    """The CPU oracle, as it stands, on a bounded sample: row 0, its first sample_P prompt
-    tokens, sample_G generated tokens (with KV cache).  Weights are handed over as float64
-    arrays (same values) so the timed region holds the oracle's arithmetic only."""
+def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperature, reps=5):
+    """The CPU oracle, as it stands, on a bounded sample of the workload, both stages of the path: generation
+    (row 0's first sample_P prompt tokens, sample_G generated tokens, with KV cache) and teacher-forced scoring of
+    the resulting sample_P + sample_G tokens.  One warm-up and `reps` timed repetitions of each, mean and standard
+    deviation.  Weights are handed over as float64 arrays (same values) so the timed regions hold the oracle's
+    arithmetic only."""
     from oracle import rollout_oracle as O
     try:
         import threadpoolctl
@@ -81,12 +83,25 @@ def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperatu
     w["layers"] = [{k: synth.to_numpy_f32(v).astype(np.float64) for k, v in lw.items()} for lw in wp["layers"]]
     m = O.Model(shape, w)
     prompt = ids[0, :min(sample_P, int(prompt_len[0]))]
-    t0 = time.perf_counter()
-    O.generate(m, [prompt], sample_G, temperature, seed=seed)
-    dt = time.perf_counter() - t0
-    return {"value": sample_G / dt, "unit": "generated tokens/s", "cores": threads, "kind": "oracle",
-            "sample": f"row 0, first {len(prompt)} prompt tokens, {sample_G} generated tokens, "
-                      f"float64 numpy oracle with KV cache, {dt:.1f} s"}
+    tg, ts, toks = [], [], None
+    for r in range(reps + 1):
+        t0 = time.perf_counter()
+        out, _ = O.generate(m, [prompt], sample_G, temperature, seed=seed)
+        t1 = time.perf_counter()
+        seq = np.concatenate([prompt, out[0]])
+        O.score(m, seq)
+        t2 = time.perf_counter()
+        if r > 0:                      # the first repetition is the warm-up
+            tg.append(t1 - t0)
+            ts.append(t2 - t1)
+    n_sc = len(prompt) + sample_G
+    gen_rate, sc_rate = sample_G / np.array(tg), n_sc / np.array(ts)
+    return {"value": float(gen_rate.mean()), "unit": "generated tokens/s", "cores": threads, "kind": "oracle",
+            "std": float(gen_rate.std()), "repetitions": reps,
+            "scored_tok_s": float(sc_rate.mean()), "scored_tok_s_std": float(sc_rate.std()),
+            "sample": f"row 0: first {len(prompt)} prompt tokens + {sample_G} generated tokens (float64 numpy oracle with "
+                      f"KV cache, {np.mean(tg):.1f} s per repetition), then those {n_sc} tokens scored "
+                      f"({np.mean(ts):.1f} s per repetition); 1 warm-up + {reps} repetitions each"}
 
 
 def response_limits(Q, cap, seed):
@@ -181,6 +196,8 @@ def main():
                     help="measurement switch: decode GEMMs above this many rows use the 128 x 128 tile kernel (library default -1 = never)")
     ap.add_argument("--precise-layers", type=int, default=None,
                     help="measurement switch: layers carried as fp16 pairs (library default 1)")
+    ap.add_argument("--no-alt-decode", action="store_true",
+                    help="skip the extra generation without the policy's fp16 copy (key decode_without_fp16_copy)")
     ap.add_argument("--progress", action="store_true", help="phase markers with elapsed time on stderr")
     ap.add_argument("--pin-gb", type=float, default=24.0, help="with --ref-host: most host memory to pin, in GB")
     ap.add_argument("--ref-host", action="store_true",
@@ -342,9 +359,13 @@ def main():
                     "gemm_prefill": R.RL_K_GEMM_PREFILL, "attn_prefill": R.RL_K_ATTN_PREFILL,
                     "lmhead_score": R.RL_K_LMHEAD_SCORE}
     launches_per_step = {"gemm_decode": G * (4 * shape.n_layers + 1), "attn_decode": G * shape.n_layers}
+    import math
     for name, k in prof_classes.items():
         n = launches_per_step.get(name, 0)
-        ro.rollout_profile_enable(k, max(1, -(-n // 6000)))      # sample evenly, stay under the event cap
+        stride = max(1, -(-n // 6000))                           # sample evenly, stay under the event cap ...
+        while math.gcd(stride, 4 * shape.n_layers + 1) != 1:     # ... and visit every GEMM shape of a decode step
+            stride += 1
+        ro.rollout_profile_enable(k, stride)
     one_step(False)
     torch.cuda.synchronize()
     prof = {}
@@ -379,30 +400,76 @@ def main():
         torch.cuda.synchronize()
         kl_exact_s = time.perf_counter() - t1
 
-    # roofline of the dominant decode kernel class
-    def avg_ms(name):
-        p = prof[name]
-        return p["ms_timed"] / p["launches_timed"] if p["launches_timed"] else None
-    g_avg, a_avg = avg_ms("gemm_decode"), avg_ms("attn_decode")
-    g_tot = (g_avg or 0) * launches_per_step["gemm_decode"]
-    a_tot = (a_avg or 0) * launches_per_step["attn_decode"]
-    if g_tot >= a_tot:
-        name = "gemm_decode (weight-streaming MFMA GEMM)"
-        per_launch = gemm_decode_bytes_per_step(shape, B) / (4 * shape.n_layers + 1)
-        achieved = per_launch / (g_avg * 1e-3) / 1e9 if g_avg else None
-    else:
-        name = "attn_decode (paged GQA decode attention)"
-        per_launch = attn_decode_bytes(shape, plen, G) / launches_per_step["attn_decode"]
-        achieved = per_launch / (a_avg * 1e-3) / 1e9 if a_avg else None
-    # HBM-side bytes per launch from hardware counters cannot be taken inside this process; the figure is the
-    # one measured for this workload's decode GEMMs with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by
-    # what the counter reads for a 1 GiB device copy; the counter summary is kept under profiles/)
-    traffic = None
-    if g_tot >= a_tot and args.workload == "8b" and not args.layers and B == wl.batch and args.impl in (-1, 1, 2):
-        traffic = 143.9e6
-    roofline = {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": (achieved / HBM_PEAK_GBPS) if achieved else None, "traffic": traffic,
-                "avg_launch_ms": g_avg if g_tot >= a_tot else a_avg, "bytes_per_launch": per_launch}
+    # The same generation without the policy's fp16 copy (the mode a policy that fills the device has to use): one
+    # untimed-for-`value` run on a second context, reported beside the headline decode figures.
+    no_copy = None
+    if Wp.shadow is not None and not args.no_alt_decode:
+        ro2 = R.Rollout(cfg, R.Weights(wp), dev)
+        if args.precise_layers is not None:
+            ro2.rollout_set_precise_layers(args.precise_layers)
+        ro2.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)      # warm: captures the graph
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ro2.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)
+        torch.cuda.synchronize()
+        g2 = time.perf_counter() - t1
+        d2 = max(g2 - prefill_s, 1e-9)
+        no_copy = {"generate_s": g2, "decode_s": d2, "decode_tok_s": B * G / d2,
+                   "decode_hbm_frac": dbytes / d2 / 1e9 / HBM_PEAK_GBPS}
+        ro2.close()
+        del ro2
+
+    # ---- rooflines per kernel class: algorithmic work of the class in one step / time of its launches in one step
+    def cls_ms(name):            # time of the class in one step: mean timed launch x launches per step
+        p_ = prof[name]
+        if not p_["launches_timed"]:
+            return None, None
+        avg = p_["ms_timed"] / p_["launches_timed"]
+        n = launches_per_step.get(name, p_["launches_timed"])
+        return avg, avg * n
+
+    n_tok_scored = 2 * float(seq_len.sum()) if not args.no_score else 0.0
+    n_tok_prefill = float(np.sum(plen - 1))
+    attn_pairs = sum(int(L_) * (int(L_) + 1) / 2.0 for L_ in seq_len) * (2 if not args.no_score else 0) + \
+        sum(int(p_ - 1) * int(p_) / 2.0 for p_ in plen)
+    work = {
+        "gemm_prefill": ("mfma", 2.0 * shape.body_params() * (n_tok_scored + n_tok_prefill) / 1e12, "TFLOP",
+                         "large-M MFMA GEMMs of prefill and scoring (gemm_dma_kernel 256x256 / gemm_mfma_kernel 128x128)"),
+        "lmhead_score": ("mfma", 2.0 * shape.head_params() * max(n_tok_scored - 2 * B, 0) / 1e12, "TFLOP",
+                         "LM head + log-sum-exp + target gather (MG_LSE epilogue)"),
+        "attn_prefill": ("mfma", shape.n_layers * 4.0 * shape.n_q_heads * shape.head_dim * attn_pairs / 1e12, "TFLOP",
+                         "causal prefill attention (attn_prefill_kernel)"),
+        "gemm_decode": ("hbm", G * gemm_decode_bytes_per_step(shape, B) / 1e9, "GB",
+                        "weight-streaming decode GEMMs (gemm_ring_kernel)"),
+        "attn_decode": ("hbm", attn_decode_bytes(shape, plen, G) / 1e9, "GB",
+                        "paged GQA decode attention (attn_decode_kernel)"),
+    }
+    traffic_db = {}
+    try:
+        traffic_db = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+    except Exception:
+        pass
+    rl = []
+    for name, (bound, amount, unit, desc) in work.items():
+        avg, tot = cls_ms(name)
+        if not tot or amount <= 0:
+            continue
+        peak = HBM_PEAK_GBPS if bound == "hbm" else MFMA_PEAK_TFLOPS
+        achieved = amount / (tot * 1e-3)
+        n = launches_per_step.get(name, prof[name]["launches_timed"])
+        ent = {"kernel": desc, "class": name, "bound": bound, "achieved": achieved, "peak": peak,
+               "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": achieved / peak,
+               "avg_launch_ms": avg, "launches_per_step": n, "ms_per_step": tot,
+               "algorithmic_per_launch": amount / n, "algorithmic_unit": unit, "traffic": None}
+        t = traffic_db.get(args.workload, {}).get(name)
+        if t and not reduced and args.impl in (-1, 1):
+            # HBM-side bytes per launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known
+            # size), taken by the profile step that wrote profiles/hbm_traffic.json at the commit it names
+            ent["traffic"] = t["bytes_per_launch"]
+            ent["traffic_measured_at"] = traffic_db.get("commit")
+        rl.append(ent)
+    rl.sort(key=lambda e: -e["ms_per_step"])
+    roofline = rl[0] if rl else None
 
     line = {
         "metric": "rollout gen tokens/s + decode HBM GB/s % peak, 8B shape batch 128 (1 GPU)",
@@ -410,7 +477,7 @@ def main():
         "unit": "generated tokens/s (whole step: generate + policy/reference scoring + KL)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights, fp16 activations/KV, fp32 accumulate" if shape.dtype == "bf16" else "f32",
+        "dtype": "bf16 weights, fp16 activations/KV (fp16 pairs in layer 0), fp32 accumulate" if shape.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape.name, "layers": shape.n_layers, "batch": B,
                    "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
@@ -421,17 +488,19 @@ def main():
         "kl_exact_s": kl_exact_s,
         "decode_tok_s": B * G / decode_s, "generate_tok_s": B * G / gen_s,
         "decode_hbm_gbps": decode_gbps, "decode_hbm_frac": decode_gbps / HBM_PEAK_GBPS,
+        "decode_without_fp16_copy": no_copy,
         "scored_tok_s": (2 * float(seq_len.sum()) / score_s) if not args.no_score else None,
         "score_tflops": score_tflops,
         "score_mfma_frac": (score_tflops / MFMA_PEAK_TFLOPS) if score_tflops else None,
         "kernel_classes": prof,
         "roofline": roofline,
+        "roofline_others": rl[1:],
         "host_cores": os.cpu_count(),
     }
     if not args.no_cpu:
         small = shape.body_params() < 5e9
         line["cpu_baseline"] = cpu_baseline(shape, wp, ids_np, plen, wl.sample_seed,
-                                            128 if not small else 256, 24 if not small else 64, wl.temperature)
+                                            64 if not small else 128, 8 if not small else 32, wl.temperature)
     else:
         line["cpu_baseline"] = None
     print(json.dumps(line))
