@@ -25,3 +25,21 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _progress(request):
+    """Names each test on the real stderr as it starts and gives the helpers a `tick` that writes through pytest's
+    capture: a long oracle comparison reports each layer it finishes instead of staying silent for minutes."""
+    from tests import helpers
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def tick(msg="."):
+        with capman.global_and_fixture_disabled():
+            sys.stderr.write(msg)
+            sys.stderr.flush()
+
+    helpers.tick = tick
+    tick("\n[%s] " % request.node.name)
+    yield
+    helpers.tick = lambda msg=".": None

@@ -66,6 +66,10 @@ def check_scores(lp_gpu, lr_gpu, kl_gpu, pen_gpu, oracle_out, tol, kl_coef):
     return errs
 
 
+def tick(msg="."):
+    """Progress mark of a long comparison (tests/conftest.py points this at the real stderr)."""
+
+
 class LazyModel(O.Model):
     """The oracle's model with its layers handed over one at a time (float64 arrays of the same values, made
     from the torch tensors the GPU path holds), so that an 80-layer model never has to sit in host memory as
@@ -77,6 +81,7 @@ class LazyModel(O.Model):
 
     def layer(self, l):
         if l != self._at:
+            tick()
             self._cur = None
             self._cur = {k: self._conv(v, np.float64) for k, v in self._wt[l].items()}
             self._at = l
