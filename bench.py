@@ -276,6 +276,9 @@ def main():
     if args.progress:
         print("[bench] weights ready", file=sys.stderr, flush=True)
     ro = R.Rollout(cfg, Wp, dev)
+    if args.progress:
+        torch.cuda.synchronize()
+        print("[bench] context ready", file=sys.stderr, flush=True)
     if args.impl >= 0:
         ro.rollout_set_impl(args.impl)
     if args.decode_tile_rows is not None:
@@ -316,6 +319,9 @@ def main():
         ev[0].record()
         if Wp.shadow is not None:
             ro.rollout_refresh_policy()      # a PPO step starts from updated weights: the fp16 copy is rebuilt, timed
+            if args.progress:
+                torch.cuda.synchronize()
+                note("fp16 copy rebuilt")
         ro.rollout_generate(sc, ids, plen, G, out_ids, None, out_lp)
         ev[1].record()
         if args.progress:
@@ -363,15 +369,19 @@ def main():
     for name, k in prof_classes.items():
         n = launches_per_step.get(name, 0)
         stride = max(1, -(-n // 6000))                           # sample evenly, stay under the event cap ...
-        while math.gcd(stride, 4 * shape.n_layers + 1) != 1:     # ... and visit every GEMM shape of a decode step
-            stride += 1
+        period = shape.n_layers if name == "attn_decode" else 4 * shape.n_layers + 1
+        while math.gcd(stride, period) != 1:     # ... and visit every launch of a decode step equally often (the
+            stride += 1                          # GEMM shapes differ, and so do the layers: the first carries fp16 pairs)
         ro.rollout_profile_enable(k, stride)
     one_step(False)
     torch.cuda.synchronize()
     prof = {}
+    # an event pair with nothing between it does not read zero: that much is in every timed launch on top of the
+    # kernel's own duration (which is what a tracer reports), so it is measured here and taken off
+    event_overhead_ms = ro.rollout_profile_event_overhead(256)
     for name, k in prof_classes.items():
         ms, n = ro.rollout_profile_read(k)
-        prof[name] = {"ms_timed": ms, "launches_timed": n}
+        prof[name] = {"ms_timed_raw": ms, "ms_timed": max(ms - n * event_overhead_ms, 0.0), "launches_timed": n}
         ro.rollout_profile_enable(k, 0)
 
     # prompt prefill alone, to split generation time into prefill + decode loop
@@ -462,7 +472,7 @@ def main():
                "avg_launch_ms": avg, "launches_per_step": n, "ms_per_step": tot,
                "algorithmic_per_launch": amount / n, "algorithmic_unit": unit, "traffic": None}
         t = traffic_db.get(args.workload, {}).get(name)
-        if t and not reduced and args.impl in (-1, 1):
+        if t and not reduced and args.impl in (-1, 1) and not t.get("context_dependent"):
             # HBM-side bytes per launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known
             # size), taken by the profile step that wrote profiles/hbm_traffic.json at the commit it names
             ent["traffic"] = t["bytes_per_launch"]
@@ -493,6 +503,7 @@ def main():
         "score_tflops": score_tflops,
         "score_mfma_frac": (score_tflops / MFMA_PEAK_TFLOPS) if score_tflops else None,
         "kernel_classes": prof,
+        "event_overhead_us": event_overhead_ms * 1e3,
         "roofline": roofline,
         "roofline_others": rl[1:],
         "host_cores": os.cpu_count(),

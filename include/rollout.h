@@ -316,6 +316,11 @@ int rollout_profile_enable(rl_ctx* ctx, int32_t kernel_class, int32_t on);
 /* Waits for the recorded events; returns summed milliseconds and launch count,
  * then clears the records.  total_ms / launches: host. */
 int rollout_profile_read(rl_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches);
+/* What such a bracket reads with nothing inside it: the mean elapsed time of `pairs` (1 .. 4096) back-to-back event
+ * pairs recorded on `stream` behind one small kernel, in milliseconds.  A timed launch reads its kernel's duration
+ * plus about this much; callers that compare with a tracer's kernel durations subtract it.  Synchronises `stream`.
+ * overhead_ms: host. */
+int rollout_profile_event_overhead(rl_ctx* ctx, int32_t pairs, double* overhead_ms, void* stream);
 
 #ifdef __cplusplus
 }

@@ -110,30 +110,111 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
         }
         return;
     }
-    if (EPI == MG_QKV) {
-        // V columns with dim-major destinations (vT[kv head][dim][token], and the V pages of the cache):
-        // the four registers r = 4k .. 4k+3 of a lane are four consecutive tokens of one dimension, so they
-        // leave as one 8-byte store instead of four 2-byte stores a cache line apart from their neighbours'.
-        const int hd = a.hd, half = hd >> 1;
+    if constexpr (EPI == MG_QKV) {
+        // Columns of a wave belong to one head (hd 128) or two (hd 64); the rotation pairs (jj, jj + hd/2) sit in
+        // adjacent 32-column MFMA tiles of a lane (acc[j], acc[j + 1]).  Everything the stores depend on is fetched
+        // first, in batches -- positions and cache slots of the lane's 16 rows, their pages, the rotation factors
+        // -- so that the band pays a few memory latencies instead of one per row: the stores that follow may
+        // alias anything as far as the compiler knows, and a load behind a store waits for it.
+        __builtin_amdgcn_sched_barrier(0);                    // one band at a time: the loads of the next one stay behind
+        const int hd = a.hd, half = hd >> 1, Hq = a.Hq, Hkv = a.Hkv;
+        const int c_first = wn * TN * 32;                     // tile-local column of acc[0], lane 0
+        auto col_of = [&](int j) {                            // global qkv column of acc[j][.] of this lane
+            const int c0 = c_first + j * 32 + lrow;
+            return hd == 128 ? nb * BN + (c0 & ~127) + (((c0 & 127) >> 5) >> 1) * 32 + (c0 & 31) : nb * BN + c0;
+        };
+        const int head_hi = col_of(TN - 2) / hd;              // wave-uniform
+        int pos[16];                                           // < 0: padding row of the packed token list
+        int page[16];
 #pragma unroll
-        for (int j = 0; j < TN; j += 2) {
-            const int c0 = wn * TN * 32 + j * 32 + lrow;
-            const int col0 = hd == 128 ? nb * BN + (c0 & ~127) + (((c0 & 127) >> 5) >> 1) * 32 + (c0 & 31) : nb * BN + c0;
-            const int head = col0 / hd, jj = col0 % hd;
-            if (head < a.Hq + a.Hkv || (a.vt_cap <= 0 && !a.pool)) continue;
-            const int g = head - a.Hq - a.Hkv;
+        for (int r = 0; r < 16; ++r) {
+            const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+            const int p_ = a.tok_pos[min(m, a.M - 1)];
+            pos[r] = m < a.M ? p_ : -1;
+        }
+        const bool to_pool = a.pool != nullptr && head_hi >= Hq;
+        if (to_pool) {
+            int slot[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) slot[r] = a.tok_slot[min(m_base + 8 * (r >> 2) + 4 * lg + (r & 3), a.M - 1)];
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                page[r] = a.block_table[(int64_t)(pos[r] >= 0 ? slot[r] : 0) * a.mpps + max(pos[r], 0) / a.geo.PT];
+        }
+        const int S = a.split_out ? 2 : 1;                     // fp16 pairs: rows of q and k are [hi heads | lo heads]
+#pragma unroll
+        for (int jp = 0; jp < TN / 2; ++jp) {
+            const int j = 2 * jp, col0 = col_of(j);
+            const int head = col0 / hd, jj = col0 % hd;        // jj < half; the partner column is jj + half
+            if (head < Hq + Hkv) {
+                float2 cs[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cs[r] = a.rope[(int64_t)max(pos[r], 0) * half + jj];
+                __builtin_amdgcn_sched_barrier(0);
+                // q and k: rotate, round (and keep what the rounding left over), store token-major; k also to its page
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+                    if (m >= a.M) continue;
+                    const bool pad = pos[r] < 0;               // padding rows get zeros: nothing non-finite is ever read back
+                    const float x0 = pad ? 0.f : acc[j][r], x1 = pad ? 0.f : acc[j + 1][r];
+                    const float v0 = x0 * cs[r].x - x1 * cs[r].y, v1 = x1 * cs[r].x + x0 * cs[r].y;
+                    f16_t h0, l0, h1, l1;
+                    split_f16(v0, h0, l0);
+                    split_f16(v1, h1, l1);
+                    if (head < Hq) {
+                        f16_t* o = a.q_out + (int64_t)m * Hq * hd * S + head * hd + jj;
+                        o[0] = h0; o[half] = h1;
+                        if (a.split_out) { o[Hq * hd] = l0; o[Hq * hd + half] = l1; }
+                    } else {
+                        const int g = head - Hq;
+                        if (a.k_out) {
+                            f16_t* o = a.k_out + ((int64_t)m * Hkv * S + g) * hd + jj;
+                            o[0] = h0; o[half] = h1;
+                            if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
+                        }
+                        if (a.pool && !pad) {
+                            const int st = pos[r] % a.geo.PT;
+                            a.pool[a.geo.k_off(a.layer, page[r], g, st, jj)] = h0;
+                            a.pool[a.geo.k_off(a.layer, page[r], g, st, jj + half)] = h1;
+                            if (a.split_out) {
+                                a.pool[a.geo.k_off(a.layer_lo, page[r], g, st, jj)] = l0;
+                                a.pool[a.geo.k_off(a.layer_lo, page[r], g, st, jj + half)] = l1;
+                            }
+                        }
+                    }
+                }
+                continue;
+            }
+            const int g = head - Hq - Hkv;
+            if (a.v_out && a.vt_cap <= 0) {
+                // token-major V
+                {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+                        if (m >= a.M) continue;
+                        const bool pad = pos[r] < 0;
+                        f16_t h0, l0, h1, l1;
+                        split_f16(pad ? 0.f : acc[j][r], h0, l0);
+                        split_f16(pad ? 0.f : acc[j + 1][r], h1, l1);
+                        f16_t* o = a.v_out + ((int64_t)m * Hkv * S + g) * hd + jj;
+                        o[0] = h0; o[half] = h1;
+                        if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
+                    }
+                }
+            }
+            if (a.vt_cap <= 0 && !a.pool) continue;
+            // V with dim-major destinations (vT[kv head][dim][token], and the V pages of the cache): the four
+            // registers r = 4k .. 4k+3 of a lane are four consecutive tokens of one dimension, so they leave as one
+            // 8-byte store instead of four 2-byte stores a cache line apart from their neighbours'.
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int m4 = m_base + 8 * rq + 4 * lg;
                 if (m4 >= a.M) continue;
-                int p[4];
                 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-                bool all = true;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    p[t] = m4 + t < a.M ? a.tok_pos[m4 + t] : -1;     // < 0: padding row, stored as zero
-                    all = all && p[t] >= 0;
-                }
+                const int* p = &pos[4 * rq];
+                const bool all = p[0] >= 0 && p[1] >= 0 && p[2] >= 0 && p[3] >= 0;
                 // plane 0: the values rounded to fp16; plane 1 (split_out): what the rounding left over
                 auto emit = [&](const int pl) {
                     half4 h0, h1;
@@ -145,7 +226,7 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                         h1[t] = pl == 0 ? r1 : (f16_t)(f1 - (float)r1);
                     }
                     if (a.v_out && a.vt_cap > 0) {
-                        f16_t* o0 = a.v_out + ((int64_t)(pl * a.Hkv + g) * hd + jj) * a.vt_cap + m4;
+                        f16_t* o0 = a.v_out + ((int64_t)(pl * Hkv + g) * hd + jj) * a.vt_cap + m4;
                         f16_t* o1 = o0 + (int64_t)half * a.vt_cap;
                         if (m4 + 3 < a.M) {
                             *reinterpret_cast<half4*>(o0) = h0;
@@ -159,18 +240,16 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                     if (a.pool) {
                         const int lay = pl == 0 ? a.layer : a.layer_lo;
                         if (all && p[0] % 4 == 0 && p[3] == p[0] + 3) {   // four tokens of one sequence: same page, adjacent slots
-                            const int64_t page = a.block_table[(int64_t)a.tok_slot[m4] * a.mpps + p[0] / a.geo.PT];
                             const int st = p[0] % a.geo.PT;
-                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page, g, st, jj)) = h0;
-                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page, g, st, jj + half)) = h1;
+                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page[4 * rq], g, st, jj)) = h0;
+                            *reinterpret_cast<half4*>(a.pool + a.geo.v_off(lay, page[4 * rq], g, st, jj + half)) = h1;
                         } else {
 #pragma unroll
                             for (int t = 0; t < 4; ++t)
                                 if (p[t] >= 0) {
-                                    const int64_t page = a.block_table[(int64_t)a.tok_slot[m4 + t] * a.mpps + p[t] / a.geo.PT];
                                     const int st = p[t] % a.geo.PT;
-                                    a.pool[a.geo.v_off(lay, page, g, st, jj)] = h0[t];
-                                    a.pool[a.geo.v_off(lay, page, g, st, jj + half)] = h1[t];
+                                    a.pool[a.geo.v_off(lay, page[4 * rq + t], g, st, jj)] = h0[t];
+                                    a.pool[a.geo.v_off(lay, page[4 * rq + t], g, st, jj + half)] = h1[t];
                                 }
                         }
                     }
@@ -179,8 +258,16 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 if (a.split_out) emit(1);
             }
         }
+        return;
     }
     {
+        // the targets of the lane's 16 rows, fetched before the first store (a load behind a store that may alias it
+        // waits for the store)
+        int tgt[EPI == MG_LSE ? 16 : 1];
+        if constexpr (EPI == MG_LSE) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tgt[r] = a.tgt[min(m_base + 8 * (r >> 2) + 4 * lg + (r & 3), a.M - 1)];
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
@@ -229,71 +316,10 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 for (int o = 1; o < 32; o <<= 1) se += __shfl_xor(se, o, RL_WAVE);
                 const int nparts = (a.N / BN) * WGN;
                 if (lrow == 0) a.lse_part[(int64_t)m * nparts + nb * WGN + wn] = make_float2(mx, se);
-                const int t = a.tgt[m];
+                const int t = tgt[EPI == MG_LSE ? r : 0];
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     if (t == nb * BN + wn * TN * 32 + j * 32 + lrow) a.z_tgt[m] = acc[j][r];
-            } else if (EPI == MG_QKV) {
-                // columns of this tile belong to one head (hd 128) or two (hd 64); pairs (j, j + hd/2)
-                // sit in adjacent 32-column MFMA tiles of this lane.
-                // pos < 0 marks a padding row of the packed token list: it gets zeros (so that
-                // nothing non-finite is ever read back as a key or value) and no cache slot
-                const int pos_raw = a.tok_pos[m];
-                const bool pad = pos_raw < 0;
-                const int pos = pad ? 0 : pos_raw;
-                const int hd = a.hd, half = hd >> 1;
-#pragma unroll
-                for (int j = 0; j < TN; j += 2) {
-                    // tile-local LDS column of acc[j]: c0; its partner acc[j+1] is c0 + 32 in LDS order
-                    int c0 = wn * TN * 32 + j * 32 + lrow;
-                    int col0;                             // global qkv column of v0; v1 is col0 + hd/2
-                    if (hd == 128) {
-                        int blk = (c0 & 127) >> 5;        // even LDS block of this head
-                        col0 = nb * BN + (c0 & ~127) + (blk >> 1) * 32 + (c0 & 31);
-                    } else {
-                        col0 = nb * BN + c0;
-                    }
-                    float v0 = pad ? 0.f : acc[j][r], v1 = pad ? 0.f : acc[j + 1][r];
-                    const int head = col0 / hd, jj = col0 % hd;      // jj < half
-                    const int Hq = a.Hq, Hkv = a.Hkv;
-                    if (head < Hq + Hkv) {
-                        float2 cs = a.rope[(int64_t)pos * half + jj];
-                        float r0 = v0 * cs.x - v1 * cs.y, r1 = v1 * cs.x + v0 * cs.y;
-                        v0 = r0; v1 = r1;
-                    }
-                    // fp16 pairs (split_out): rows of q and k are twice as wide, [hi heads | lo heads]
-                    const int S = a.split_out ? 2 : 1;
-                    f16_t h0, l0, h1, l1;
-                    split_f16(v0, h0, l0);
-                    split_f16(v1, h1, l1);
-                    if (head < Hq) {
-                        f16_t* o = a.q_out + (int64_t)m * Hq * hd * S + head * hd + jj;
-                        o[0] = h0; o[half] = h1;
-                        if (a.split_out) { o[Hq * hd] = l0; o[Hq * hd + half] = l1; }
-                    } else if (head < Hq + Hkv) {
-                        int g = head - Hq;
-                        if (a.k_out) {
-                            f16_t* o = a.k_out + ((int64_t)m * Hkv * S + g) * hd + jj;
-                            o[0] = h0; o[half] = h1;
-                            if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
-                        }
-                        if (a.pool && !pad) {
-                            int64_t page = a.block_table[(int64_t)a.tok_slot[m] * a.mpps + pos / a.geo.PT];
-                            int st = pos % a.geo.PT;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj)] = h0;
-                            a.pool[a.geo.k_off(a.layer, page, g, st, jj + half)] = h1;
-                            if (a.split_out) {
-                                a.pool[a.geo.k_off(a.layer_lo, page, g, st, jj)] = l0;
-                                a.pool[a.geo.k_off(a.layer_lo, page, g, st, jj + half)] = l1;
-                            }
-                        }
-                    } else if (a.v_out && a.vt_cap <= 0) {   // token-major V (dim-major V and the pages: packed path above)
-                        int g = head - Hq - Hkv;
-                        f16_t* o = a.v_out + ((int64_t)m * Hkv * S + g) * hd + jj;
-                        o[0] = h0; o[half] = h1;
-                        if (a.split_out) { o[Hkv * hd] = l0; o[Hkv * hd + half] = l1; }
-                    }
-                }
             }
         }
     }

@@ -1658,4 +1658,30 @@ int rollout_profile_read(rl_ctx* c, int32_t k, double* total_ms, int64_t* launch
     return RL_OK;
 }
 
+int rollout_profile_event_overhead(rl_ctx* c, int32_t pairs, double* overhead_ms, void* stream) {
+    if (!c || !overhead_ms) return fail(RL_EINVAL, "NULL argument");
+    if (pairs < 1 || pairs > 4096) return fail(RL_EINVAL, "pairs must be in 1 .. 4096");
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t a = nullptr, b = nullptr;
+    HIP_TRY(hipEventCreate(&a));
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(RL_EHIP, "hipEventCreate failed"); }
+    double tot = 0.0;
+    int rc = RL_OK;
+    for (int i = 0; i < pairs && rc == RL_OK; ++i) {
+        // a kernel in front, as in a timed pass: the first event then waits for real work instead of an idle queue
+        k_fill_f32(c->at<float>(c->L.x), 0.f, 64, s);
+        if (hipEventRecord(a, s) != hipSuccess || hipEventRecord(b, s) != hipSuccess || hipEventSynchronize(b) != hipSuccess) {
+            rc = fail(RL_EHIP, "event record failed");
+            break;
+        }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, a, b) != hipSuccess) { rc = fail(RL_EHIP, "hipEventElapsedTime failed"); break; }
+        tot += ms;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (rc == RL_OK) *overhead_ms = tot / pairs;
+    return rc;
+}
+
 }  // extern "C"

@@ -4,7 +4,7 @@
         the --kernel-trace --stats table as markdown rows (calls, total ms, average / min / max us, share)
 
     python -m paper_2405_01481_amd.profile_summary traffic <fetch counter csv> <write counter csv> <workload> <out.json>
-        HBM-side bytes per launch of the decode kernel classes from two --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per
+        HBM-side bytes per launch of the kernel classes from two --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per
         dispatch), each scaled by what the same counter reads for the 1 GiB device copies that
         `bench.py --calib-copy` runs first; merged into <out.json> under the workload's name together with the
         current commit, which is where bench.py takes `roofline.traffic` from.
@@ -21,8 +21,10 @@ import re
 import subprocess
 import sys
 
-# kernel name prefix -> class of bench.py's roofline entries
-CLASSES = {"gemm_ring_kernel": "gemm_decode", "attn_decode_kernel": "attn_decode"}
+# kernel name pattern -> class of bench.py's roofline entries (the LM-head GEMM is the tile kernel with epilogue 5)
+CLASSES = {r"gemm_ring_kernel": "gemm_decode", r"attn_decode_kernel": "attn_decode",
+           r"gemm_dma_kernel<[0-4],": "gemm_prefill", r"gemm_dma_kernel<5,": "lmhead_score",
+           r"attn_prefill_kernel": "attn_prefill"}
 
 
 def trace_table(path, top=24):
@@ -41,7 +43,7 @@ def _per_kernel(path, counter):
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] != counter:
             continue
-        name = re.sub(r"\(.*", "", r["Kernel_Name"])
+        name = re.sub(r"^void ", "", re.sub(r"\(.*", "", r["Kernel_Name"]))
         per[name][r["Dispatch_Id"]] = per[name].get(r["Dispatch_Id"], 0.0) + float(r["Counter_Value"])
     return {k: list(v.values()) for k, v in per.items()}
 
@@ -55,16 +57,18 @@ def traffic(fetch_csv, write_csv, workload, out_json):
         copies = [v for k, v in per.items() if "copyBuffer" in k]
         if not copies:
             raise SystemExit(f"no calibration copies in the {what} run (bench.py --calib-copy)")
-        big = [x for x in copies[0] if x > 0.2 * gib_kib]
-        return gib_kib / (sum(big) / len(big))
+        first = copies[0][:3]          # --calib-copy runs its three 1 GiB copies before anything else
+        return gib_kib / (sum(first) / len(first))
     sf, sw = scale(fetch, "FETCH_SIZE"), scale(write, "WRITE_SIZE")
     res = {}
-    for prefix, cls in CLASSES.items():
-        f = [x for k, v in fetch.items() if k.startswith(prefix) for x in v]
-        w = [x for k, v in write.items() if k.startswith(prefix) for x in v]
+    for pattern, cls in CLASSES.items():
+        f = [x for k, v in fetch.items() if re.match(pattern, k) for x in v]
+        w = [x for k, v in write.items() if re.match(pattern, k) for x in v]
         if not f or not w:
             continue
-        res[cls] = {"bytes_per_launch": (sum(f) / len(f) * sf + sum(w) / len(w) * sw) * 1024.0,
+        res[cls] = {"context_dependent": cls.startswith("attn_"),   # per-launch bytes grow with the sequences: only
+                    # comparable with a run of the same prompt and generation lengths
+                    "bytes_per_launch": (sum(f) / len(f) * sf + sum(w) / len(w) * sw) * 1024.0,
                     "fetch_bytes_per_launch": sum(f) / len(f) * sf * 1024.0,
                     "write_bytes_per_launch": sum(w) / len(w) * sw * 1024.0, "dispatches": len(f)}
     try:

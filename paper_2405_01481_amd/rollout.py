@@ -89,6 +89,7 @@ def lib():
         L.rollout_set_precise_layers.argtypes = [vp, i32]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
+        L.rollout_profile_event_overhead.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -295,6 +296,11 @@ class Rollout:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().rollout_profile_read(self.h, kernel_class, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+    def rollout_profile_event_overhead(self, pairs: int = 256) -> float:
+        ms = C.c_double()
+        _chk(lib().rollout_profile_event_overhead(self.h, int(pairs), C.byref(ms), _stream()))
+        return ms.value
 
 
 def ppo_rewards_noalloc(kl: torch.Tensor, seq_reward: torch.Tensor, seq_len, prompt_len, kl_coef, rewards):
