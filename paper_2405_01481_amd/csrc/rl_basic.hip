@@ -782,6 +782,177 @@ void k_sample(const float* logits, int ldz, int V, int B, SampleArgs a, int* las
                                      logp_out, out_ids, out_logp, out_stride);
 }
 
+// The same draw from per-block statistics instead of logits (the LM-head GEMM's MG_SAMPLE epilogue: per row and
+// 32-column block the maximum, its column, and the sums of exp((z - max) / T) and exp(z - max)): the logits of a decode
+// step never reach memory.  One block of 1024 threads per sequence; thread t owns the contiguous run of blocks
+// [t * per, (t + 1) * per), sums are formed in block order and scanned in thread order, so results are
+// reproducible run to run.  Greedy: the first block holding the global maximum, and its column.  Otherwise the
+// block in which the cumulative sum passes u * total is found from the statistics, and only that block's 32
+// logits are recomputed (h . W rows, fp32 accumulation) to place the token inside it; if rounding differences between
+// those 32 values and the block's own sum keep the cumulative sum from passing the target inside the block, the
+// block's last column is taken (the crossing then lies on the block's end within rounding).
+__global__ __launch_bounds__(1024) void sample_blocks_kernel(const float4* stats, int nblk, const f16_t* h, int ldh,
+                                                             const bf16_t* W, int d, SampleArgs a, int* last_tok,
+                                                             int* seq_len, int* gen_count, int* finished,
+                                                             int* step_count, int* tok_out, float* logp_out,
+                                                             int* out_ids, float* out_logp, int out_stride) {
+    __shared__ ArgMax ared[16];
+    __shared__ float red1[16], redT[16], zs[32];
+    __shared__ int s_first, s_blk, s_tok;
+    __shared__ float s_before, s_ztok;
+    const int b = blockIdx.x;
+    const int64_t orow = a.out_row ? a.out_row[b] : b;
+    if (finished[b] != 0) {
+        // a finished sequence keeps emitting eos_id with log-prob 0 and no longer advances
+        if (threadIdx.x == 0) {
+            last_tok[b] = a.eos_id >= 0 ? a.eos_id : 0;   // a parked row still feeds a valid id through the GEMMs
+            if (tok_out) tok_out[b] = a.eos_id;
+            if (logp_out) logp_out[b] = 0.f;
+            const int st = step_count[b];
+            step_count[b] = st + 1;
+            if (st < out_stride) {
+                if (out_ids) out_ids[orow * out_stride + st] = a.eos_id;
+                if (out_logp) out_logp[orow * out_stride + st] = 0.f;
+            }
+        }
+        return;
+    }
+    const float4* st4 = stats + (int64_t)b * nblk;
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int per = (nblk + 1023) / 1024;
+    const int b0 = min(nblk, t * per), b1 = min(nblk, b0 + per);
+    const bool greedy = !(a.temperature > 0.f);
+    const float invT = greedy ? 1.0f : 1.0f / a.temperature;
+    // global maximum and the first block that holds it
+    ArgMax am{-INFINITY, 0x7fffffff};
+    for (int i = b0; i < b1; ++i) {
+        const float v = st4[i].x;
+        if (v > am.v) { am.v = v; am.i = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ArgMax o2{__shfl_xor(am.v, o, RL_WAVE), __shfl_xor(am.i, o, RL_WAVE)};
+        am = argmax_combine(am, o2);
+    }
+    if (lane == 0) ared[w] = am;
+    if (t == 0) { s_first = 0x7fffffff; s_blk = nblk - 1; s_before = 0.f; }
+    __syncthreads();
+    am = ared[0];
+    for (int i = 1; i < 16; ++i) am = argmax_combine(am, ared[i]);
+    const float mx = am.v;
+    // this thread's share of both sums, then an inclusive scan of the temperature sum over the threads
+    float l1 = 0.f, lT = 0.f;
+    for (int i = b0; i < b1; ++i) {
+        const float4 q = st4[i];
+        l1 += q.z * __expf(q.x - mx);
+        lT += q.y * __expf((q.x - mx) * invT);
+    }
+    float pT = lT;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float u_ = __shfl_up(pT, o, RL_WAVE);
+        if (lane >= o) pT += u_;
+    }
+    const float w1 = wave_sum(l1);
+    if (lane == 63) redT[w] = pT;
+    if (lane == 0) red1[w] = w1;
+    __syncthreads();
+    float tot1 = 0.f, totT = 0.f, baseT = 0.f;
+    for (int i = 0; i < 16; ++i) {
+        if (i == w) baseT = totT;
+        tot1 += red1[i];
+        totT += redT[i];
+    }
+    const float incl = baseT + pT, excl = incl - lT;
+    const int n_gen = gen_count[b];
+    float target = 0.f;
+    if (!greedy) {
+        const float u = hash_uniform(a.seed, (uint64_t)(a.seq_base + (a.seq_id ? a.seq_id[b] : b)), (uint64_t)n_gen);
+        target = u * totT;
+        if (b0 < b1 && incl > target) atomicMin(&s_first, t);
+        __syncthreads();
+        if (t == s_first) {
+            float cum = excl;
+            int sel = b1 - 1;
+            float before = cum;
+            for (int i = b0; i < b1; ++i) {
+                const float4 q = st4[i];
+                const float nc = cum + q.y * __expf((q.x - mx) * invT);
+                if (nc > target) { sel = i; before = cum; break; }
+                before = cum = nc;
+            }
+            if (sel == b1 - 1 && !(before <= target)) before = cum;   // unreachable in exact arithmetic
+            s_blk = sel;
+            s_before = before;
+        }
+        __syncthreads();
+        // the 32 logits of the chosen block: column t / 32, 32 threads per column over 16-byte pieces of k
+        const int blk = s_blk;
+        const int col = t >> 5, part = t & 31;
+        const bf16_t* wrow = W + ((int64_t)blk * 32 + col) * d;
+        const f16_t* hrow = h + (int64_t)b * ldh;
+        float acc = 0.f;
+        for (int k = part * 8; k < d; k += 256) {
+            typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+            typedef unsigned short us8_t __attribute__((ext_vector_type(8)));
+            const half8_t hv = *reinterpret_cast<const half8_t*>(hrow + k);
+            const us8_t wv = *reinterpret_cast<const us8_t*>(wrow + k);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += (float)hv[e] * __uint_as_float((unsigned)wv[e] << 16);
+        }
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) acc += __shfl_xor(acc, o, RL_WAVE);
+        if (part == 0) zs[col] = acc;
+        __syncthreads();
+        if (t < 64) {
+            const float e = t < 32 ? __expf((zs[t & 31] - mx) * invT) : 0.f;
+            float pe = e;
+#pragma unroll
+            for (int o = 1; o < 32; o <<= 1) {
+                const float u_ = __shfl_up(pe, o, RL_WAVE);
+                if (lane >= o) pe += u_;
+            }
+            const unsigned long long hit = __ballot(t < 32 && s_before + pe > target);
+            if (t == 0) {
+                const int c = hit ? __ffsll((long long)hit) - 1 : 31;
+                s_tok = blk * 32 + c;
+                s_ztok = zs[c];
+            }
+        }
+    } else if (t == 0) {
+        s_tok = am.i * 32 + __float_as_int(st4[am.i].w);
+        s_ztok = mx;
+    }
+    __syncthreads();
+    if (t == 0) {
+        const int tok = s_tok;
+        const float lp = s_ztok - mx - logf(tot1);
+        gen_count[b] = n_gen + 1;
+        if ((a.eos_id >= 0 && tok == a.eos_id) || (a.gen_limit && n_gen + 1 >= a.gen_limit[b])) {
+            finished[b] = 1;
+            if (a.out_len) a.out_len[orow] = n_gen + 1;
+        }
+        last_tok[b] = tok;
+        seq_len[b] = seq_len[b] + 1;
+        if (tok_out) tok_out[b] = tok;
+        if (logp_out) logp_out[b] = lp;
+        const int st = step_count[b];
+        step_count[b] = st + 1;
+        if (st < out_stride) {
+            if (out_ids) out_ids[orow * out_stride + st] = tok;
+            if (out_logp) out_logp[orow * out_stride + st] = lp;
+        }
+    }
+}
+void k_sample_blocks(const float4* stats, int V, const void* h, int ldh, const void* W, int d, int B, SampleArgs a,
+                     int* last_tok, int* seq_len, int* gen_count, int* finished, int* step_count, int* tok_out,
+                     float* logp_out, int* out_ids, float* out_logp, int out_stride, hipStream_t s) {
+    if (B <= 0) return;
+    sample_blocks_kernel<<<B, 1024, 0, s>>>(stats, V / 32, (const f16_t*)h, ldh, (const bf16_t*)W, d, a, last_tok, seq_len,
+                                            gen_count, finished, step_count, tok_out, logp_out, out_ids, out_logp,
+                                            out_stride);
+}
+
 // ---------------------------------------------------------------- log-sum-exp + gather over materialised logits
 // logp_out[slot, pos + 1] = z[target] - log sum_v exp(z_v) for rows with a target.
 __global__ __launch_bounds__(1024) void lse_gather_kernel(const float* logits, int ldz, int V, const int* tok_tgt,

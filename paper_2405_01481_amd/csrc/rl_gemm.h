@@ -2,7 +2,7 @@
 #pragma once
 #include "rl_common.h"
 
-enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4, MG_LSE = 5, MG_KLFULL = 6 };
+enum { MG_STORE_F32 = 0, MG_STORE_F16 = 1, MG_RESID = 2, MG_SWIGLU = 3, MG_QKV = 4, MG_LSE = 5, MG_KLFULL = 6, MG_SAMPLE = 7 };
 
 struct GemmArgs {
     const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
@@ -46,6 +46,11 @@ struct GemmArgs {
     // MG_KLFULL (both LM heads for the exact KL): the reference's logits A2 * W2^T are formed for the same
     // tile as the policy's A * W^T; per row and 64-column group five floats go to kl_part[row][N/64][5]
     // (see kl_epilogue).  No logits are stored.
+    // MG_SAMPLE (LM head of a decode step): per row and 32-column block, samp_part[row][N/32] =
+    // (max, sum exp((z - max) * inv_temp), sum exp(z - max), block-local column of the max [lowest on ties], as int bits).
+    // The logits themselves are never stored; the sampler picks a block from these and recomputes its 32 logits.
+    float4* samp_part = nullptr;
+    float inv_temp = 1.0f;
     const f16_t* A2 = nullptr;
     int lda2 = 0;
     const bf16_t* W2 = nullptr;

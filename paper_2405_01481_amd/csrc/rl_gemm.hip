@@ -86,6 +86,36 @@ template <int EPI, int BN, int TN, int WGN>
 __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs& a, int m_base, int nb, int wn,
                                             int ks, int lane) {
     const int lg = lane >> 5, lrow = lane & 31;
+    if constexpr (EPI == MG_SAMPLE) {
+        // Reductions over the 32 lanes that hold one row of a 32-column MFMA tile (xor butterflies: every lane ends
+        // with the same bits).  Ties of the maximum go to the lowest column, as the sampler's arg-max rule wants.
+        const int nblk = a.N / 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float v = acc[j][r];
+                float mx = v;
+                int mi = lrow;
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) {
+                    const float ov = __shfl_xor(mx, o, RL_WAVE);
+                    const int oi = __shfl_xor(mi, o, RL_WAVE);
+                    if (ov > mx || (ov == mx && oi < mi)) { mx = ov; mi = oi; }
+                }
+                float e1 = __expf(v - mx), eT = __expf((v - mx) * a.inv_temp);
+#pragma unroll
+                for (int o = 1; o < 32; o <<= 1) {
+                    e1 += __shfl_xor(e1, o, RL_WAVE);
+                    eT += __shfl_xor(eT, o, RL_WAVE);
+                }
+                if (lrow == 0 && m < a.M)
+                    a.samp_part[(int64_t)m * nblk + nb * (BN / 32) + wn * TN + j] = make_float4(mx, eT, e1, __int_as_float(mi));
+            }
+        }
+        return;
+    }
     if (EPI == MG_RESID) {
         // read-modify-write of the fp32 residual stream: all of the band's loads are issued before the
         // first add (rows past M read row M-1 instead of branching, so nothing separates the loads)
@@ -1061,7 +1091,7 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
 
 // ---- decode (M <= 128): ring kernel on 128-column tiles, split over K in units of 128
 bool k_gemm_decode_supported(int epi, int N, int K) {
-    if (epi != MG_STORE_F32 && epi != MG_SWIGLU) return false;
+    if (epi != MG_STORE_F32 && epi != MG_SWIGLU && epi != MG_SAMPLE) return false;
     const int cols = epi == MG_SWIGLU ? 2 * N : N;
     return K % 128 == 0 && cols % 128 == 0 && (uint64_t)cols * K * 2 < (1ull << 32);
 }
@@ -1112,7 +1142,7 @@ void k_gemm_decode_tile_above(int rows) { g_decode_tile_above = rows; }
 void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0 || a.M > 128) return;
     if (a.Kw <= 0) a.Kw = a.K;
-    if (epi == MG_SWIGLU) splits = 1;
+    if (epi == MG_SWIGLU || epi == MG_SAMPLE) splits = 1;
     const int units = a.K / 128;
     if (splits < 1) splits = 1;
     const int per = (units + splits - 1) / splits;
@@ -1123,7 +1153,7 @@ void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {
     // kernel.  Back to back on 128 rows it streams W 4-9 % faster; inside the decode step the ring kernel on the
     // policy's fp16 copy wins by 3 %, so it stays the default.  Both split K the same way (units of 128), so the
     // partial buffers are the same.
-    if (g_decode_tile_above >= 0 && a.M > g_decode_tile_above) {
+    if (g_decode_tile_above >= 0 && a.M > g_decode_tile_above && epi != MG_SAMPLE) {
         a.k_per_split = per * 128;
         if (epi == MG_SWIGLU) {
             if (a.w_f16) launch<128, 128, 2, 2, MG_SWIGLU, 64, true>(a, a.N / 64, 1, s);
@@ -1135,6 +1165,7 @@ void k_gemm_decode(int epi, GemmArgs a, int splits, hipStream_t s) {
         return;
     }
     if (epi == MG_SWIGLU) launch_ring<MG_SWIGLU, 4, 2>(a, a.N / 64, 1, s);   // gate / up pairs: two column tiles per wave
+    else if (epi == MG_SAMPLE) launch_ring<MG_SAMPLE, 2, 4>(a, a.N / 128, 1, s);
     else launch_ring<MG_STORE_F32, 2, 4>(a, a.N / 128, splits, s);
 }
 
