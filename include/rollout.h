@@ -296,6 +296,16 @@ int rollout_set_impl(rl_ctx* ctx, int32_t impl);
  * Errors: RL_EINVAL (n out of range, or n > 0 on a context that runs the plain kernels). */
 int rollout_set_precise_layers(rl_ctx* ctx, int32_t n);
 
+/* Tuned bf16 path only.  on != 0 (default): the LM head of a decode step writes, per row and 32 vocabulary
+ * columns, the maximum, its column and two sums of exponentials (Section 3.2's generation step never needs the
+ * logits themselves), and the sampler draws from those, recomputing the 32 logits of the one block the draw lands
+ * in.  on = 0: the LM head writes fp32 logits [batch, vocab] and the sampler reads them all.  Same rule for the
+ * token either way (arg-max with the lowest id on ties; inverse CDF in vocabulary order for the shared uniform);
+ * the sums are formed in a different order, so log-probs agree to rounding and a sampled token can differ where the
+ * uniform falls within rounding of a CDF step.  The caller must have waited for work on the context.  Takes effect
+ * with the next decode step; live sequences are kept.  Errors: RL_EINVAL. */
+int rollout_set_fused_sampling(rl_ctx* ctx, int32_t on);
+
 /* Measurement switch (process-wide): decode-step GEMMs of more than `rows` rows run on the 128 x 128 tile kernel
  * instead of the LDS-ring weight streamer (default: a negative value = ring kernel for every batch). */
 int rollout_set_decode_tile_rows(int32_t rows);

@@ -863,7 +863,8 @@ __global__ __launch_bounds__(1024) void sample_blocks_kernel(const float4* stats
         tot1 += red1[i];
         totT += redT[i];
     }
-    const float incl = baseT + pT, excl = incl - lT;
+    const float up1 = __shfl_up(pT, 1, RL_WAVE);
+    const float incl = baseT + pT, excl = baseT + (lane > 0 ? up1 : 0.f);   // excl of thread t == incl of thread t - 1, bit for bit
     const int n_gen = gen_count[b];
     float target = 0.f;
     if (!greedy) {
@@ -872,18 +873,18 @@ __global__ __launch_bounds__(1024) void sample_blocks_kernel(const float4* stats
         if (b0 < b1 && incl > target) atomicMin(&s_first, t);
         __syncthreads();
         if (t == s_first) {
+            // the scan says this thread's run of blocks holds the crossing; summed block by block it may fall just
+            // short of it within rounding: then the run's last block takes it
             float cum = excl;
             int sel = b1 - 1;
-            float before = cum;
             for (int i = b0; i < b1; ++i) {
                 const float4 q = st4[i];
                 const float nc = cum + q.y * __expf((q.x - mx) * invT);
-                if (nc > target) { sel = i; before = cum; break; }
-                before = cum = nc;
+                if (nc > target || i == b1 - 1) { sel = i; break; }
+                cum = nc;
             }
-            if (sel == b1 - 1 && !(before <= target)) before = cum;   // unreachable in exact arithmetic
             s_blk = sel;
-            s_before = before;
+            s_before = cum;
         }
         __syncthreads();
         // the 32 logits of the chosen block: column t / 32, 32 threads per column over 16-byte pieces of k

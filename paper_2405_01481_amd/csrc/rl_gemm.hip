@@ -79,6 +79,29 @@ __device__ __forceinline__ bool tile_of(int id, int MB, int NB, int& mb, int& nb
     return true;
 }
 
+// Maximum / sum over the 32 lanes of a half-wave (the lanes that hold one row of a 32-column MFMA tile); every lane
+// ends with the same bits.  Four steps inside each row of 16 lanes are data-parallel-primitive moves (swap lanes 1
+// apart, 2 apart, mirror 8, mirror 16: each lane always meets a partner that holds the complementary set, and both
+// form the same commutative combination), the step across the two rows is one cross-lane shuffle.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row32_max(float v) {
+    v = fmaxf(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_move<0x141>(v));   // row_half_mirror
+    v = fmaxf(v, dpp_move<0x140>(v));   // row_mirror
+    return fmaxf(v, __shfl_xor(v, 16, RL_WAVE));
+}
+__device__ __forceinline__ float row32_sum(float v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return v + __shfl_xor(v, 16, RL_WAVE);
+}
+
 // Epilogue shared by the tile kernels, for one 32-row band of a wave's accumulators: acc[j][r] of the
 // wave in tile-column position wn is C(row, col) with
 //   row = m_base + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
@@ -87,8 +110,8 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                                             int ks, int lane) {
     const int lg = lane >> 5, lrow = lane & 31;
     if constexpr (EPI == MG_SAMPLE) {
-        // Reductions over the 32 lanes that hold one row of a 32-column MFMA tile (xor butterflies: every lane ends
-        // with the same bits).  Ties of the maximum go to the lowest column, as the sampler's arg-max rule wants.
+        // Reductions over the 32 lanes that hold one row of a 32-column MFMA tile.  Ties of the maximum go to the
+        // lowest column (the lowest lane that holds it), as the sampler's arg-max rule wants.
         const int nblk = a.N / 32;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -96,20 +119,10 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const float v = acc[j][r];
-                float mx = v;
-                int mi = lrow;
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) {
-                    const float ov = __shfl_xor(mx, o, RL_WAVE);
-                    const int oi = __shfl_xor(mi, o, RL_WAVE);
-                    if (ov > mx || (ov == mx && oi < mi)) { mx = ov; mi = oi; }
-                }
-                float e1 = __expf(v - mx), eT = __expf((v - mx) * a.inv_temp);
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) {
-                    e1 += __shfl_xor(e1, o, RL_WAVE);
-                    eT += __shfl_xor(eT, o, RL_WAVE);
-                }
+                const float mx = row32_max(v);
+                const unsigned holders = (unsigned)(__ballot(v == mx) >> (32 * lg));
+                const int mi = __ffs(holders) - 1;
+                const float e1 = row32_sum(__expf(v - mx)), eT = row32_sum(__expf((v - mx) * a.inv_temp));
                 if (lrow == 0 && m < a.M)
                     a.samp_part[(int64_t)m * nblk + nb * (BN / 32) + wn * TN + j] = make_float4(mx, eT, e1, __int_as_float(mi));
             }
@@ -337,13 +350,11 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
                 float mx = acc[0][r];
 #pragma unroll
                 for (int j = 1; j < TN; ++j) mx = fmaxf(mx, acc[j][r]);
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, RL_WAVE));
+                mx = row32_max(mx);
                 float se = 0.f;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) se += __expf(acc[j][r] - mx);
-#pragma unroll
-                for (int o = 1; o < 32; o <<= 1) se += __shfl_xor(se, o, RL_WAVE);
+                se = row32_sum(se);
                 const int nparts = (a.N / BN) * WGN;
                 if (lrow == 0) a.lse_part[(int64_t)m * nparts + nb * WGN + wn] = make_float2(mx, se);
                 const int t = tgt[EPI == MG_LSE ? r : 0];

@@ -226,6 +226,7 @@ struct rl_ctx {
     } gkey{};
     hipGraphExec_t gexec = nullptr;
     bool use_graph = true;
+    bool fused_sample = true;        // decode LM head emits block statistics instead of logits (tuned path)
     // captured steps that may still be running when the policy is swapped without waiting: destroyed once the
     // event recorded behind their last launch has completed
     struct Retired { hipGraphExec_t g; hipEvent_t ev; };
@@ -384,7 +385,7 @@ static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a0, int splits, hi
     ProfScope ps(c, cls, s);
     GemmArgs a = a0;
     a.big_mode = c->big_mode;
-    if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU) &&
+    if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU || epi == MG_SAMPLE) &&
         k_gemm_decode_supported(epi, a.N, a.K)) {
         auto it = c->shadow_of.find((const void*)a.W);
         if (it != c->shadow_of.end()) { a.W = (const bf16_t*)it->second; a.w_f16 = 1; }
@@ -874,6 +875,13 @@ int rollout_set_precise_layers(rl_ctx* c, int32_t n) {
     return rollout_reset(c);
 }
 
+int rollout_set_fused_sampling(rl_ctx* c, int32_t on) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    c->fused_sample = on != 0;
+    if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return RL_OK;
+}
+
 int rollout_check(rl_ctx* c, void* stream) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     hipStream_t s = (hipStream_t)stream;
@@ -958,7 +966,6 @@ static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_
             c->at<int>(L.errflag), s);
     if (!run_layers(c, c->policy, B, true, true, max_ctx, 0, s))
         k_rmsnorm(m.dtype, c->at<float>(L.x), c->policy.final_norm, c->at<char>(L.h), B, m.d_model, m.rms_eps, s);
-    lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
     SampleArgs a{sample->seed, sample->seq_id_base, sample->temperature, sample->eos_id};
     if (queue_out_len) {
         a.out_row = c->at<int>(L.out_row);
@@ -966,9 +973,27 @@ static int decode_step_impl(rl_ctx* c, const rl_sample_cfg* sample, const int32_
         a.gen_limit = c->at<int>(L.gen_limit);
         a.out_len = queue_out_len;
     }
-    k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
-             c->at<int>(L.gen_count), c->at<int>(L.finished), c->at<int>(L.step_count), tok_out, logp_out, out_ids,
-             out_logp, out_stride, s);
+    // The LM head either writes fp32 logits [B, V] for the sampler to read, or -- tuned path, decode GEMM shapes --
+    // only per-block statistics (16 bytes per row and 32 columns, in the same buffer), from which the sampler draws
+    // and re-derives the 32 logits of the one block it lands in: the step's logits never reach memory.
+    const bool fused = c->impl == 1 && c->fused_sample && B <= 128 && m.vocab % 128 == 0 && m.d_model % 8 == 0 &&
+                       k_gemm_decode_supported(MG_SAMPLE, m.vocab, m.d_model) &&
+                       (size_t)B * (m.vocab / 32) * sizeof(float4) <= (size_t)L.logit_rows * m.vocab * 4;
+    if (fused) {
+        GemmArgs g;
+        g.M = B; g.A = c->at<f16_t>(L.h); g.lda = m.d_model; g.W = (const bf16_t*)c->policy.lm_head; g.N = m.vocab;
+        g.K = m.d_model; g.samp_part = c->at<float4>(L.logits);
+        g.inv_temp = sample->temperature > 0.f ? 1.0f / sample->temperature : 1.0f;
+        mfma(c, RL_K_GEMM_DECODE, MG_SAMPLE, g, 1, s);
+        k_sample_blocks(c->at<float4>(L.logits), m.vocab, c->at<char>(L.h), m.d_model, c->policy.lm_head, m.d_model, B, a,
+                        c->at<int>(L.last_tok), c->at<int>(L.seq_len), c->at<int>(L.gen_count), c->at<int>(L.finished),
+                        c->at<int>(L.step_count), tok_out, logp_out, out_ids, out_logp, out_stride, s);
+    } else {
+        lm_head_logits(c, RL_K_GEMM_DECODE, c->policy, c->at<char>(L.h), B, s);
+        k_sample(c->at<float>(L.logits), m.vocab, m.vocab, B, a, c->at<int>(L.last_tok), c->at<int>(L.seq_len),
+                 c->at<int>(L.gen_count), c->at<int>(L.finished), c->at<int>(L.step_count), tok_out, logp_out, out_ids,
+                 out_logp, out_stride, s);
+    }
     for (int b = 0; b < B; ++b) c->cached[b] = need[b];
     return RL_OK;
 }

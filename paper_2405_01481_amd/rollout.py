@@ -87,6 +87,7 @@ def lib():
         L.rollout_set_impl.argtypes = [vp, i32]
         L.rollout_set_decode_tile_rows.argtypes = [i32]
         L.rollout_set_precise_layers.argtypes = [vp, i32]
+        L.rollout_set_fused_sampling.argtypes = [vp, i32]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
         L.rollout_profile_event_overhead.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
@@ -288,6 +289,9 @@ class Rollout:
 
     def rollout_set_precise_layers(self, n: int):
         _chk(lib().rollout_set_precise_layers(self.h, n))
+
+    def rollout_set_fused_sampling(self, on: bool):
+        _chk(lib().rollout_set_fused_sampling(self.h, 1 if on else 0))
 
     def rollout_profile_enable(self, kernel_class: int, every: int):
         _chk(lib().rollout_profile_enable(self.h, kernel_class, int(every)))

@@ -756,3 +756,34 @@ def test_split_kv_rows_do_not_depend_on_batch_size():
         assert np.array_equal(o[0], a_ids[b]) and np.allclose(l[0], a_lp[b], atol=1e-6), b
     verify_rollout(mp, [ids[b, :lens[b]] for b in range(B)], a_ids, a_lp, 1.0, 23, 0, 1e-3, 2e-2, rows=[0, 3])
     ro.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [MINI64, MINI128], ids=lambda s: s.name)
+def test_sampling_from_block_statistics(shape):
+    """Decode with the LM head emitting per-block statistics (no logits in memory; the default on the tuned path)
+    against the oracle along its own trajectory, at two temperatures and greedy, and against the same context with
+    the switch off (fp32 logits written and read back): same tokens, log-probs equal to rounding."""
+    B, G = 7, 24
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 48 + G)
+    ids, lens = synth.make_prompts(shape.vocab, B, 48, 9, 77)
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    lt, cd = _tol(shape)
+    for temp, seed in ((1.0, 5), (0.7, 6), (0.0, 7)):
+        ro.rollout_set_fused_sampling(True)
+        g_ids, g_len, g_lp = _generate(ro, ids, lens, G, temp, seed=seed, base=3)
+        st = verify_rollout(mp, prompts, g_ids, g_lp, temp, seed, 3, cd, lt)
+        print(shape.name, temp, st)
+        torch.cuda.synchronize()
+        ro.rollout_set_fused_sampling(False)
+        p_ids, _, p_lp = _generate(ro, ids, lens, G, temp, seed=seed, base=3)
+        torch.cuda.synchronize()
+        # a token may differ only where the uniform falls within rounding of a CDF step; from there on the two rows
+        # are different sequences, so compare up to the first difference and require that to be rare
+        same = g_ids == p_ids
+        first = np.where(same.all(axis=1), G, np.argmin(same, axis=1))
+        assert (first == G).sum() >= B - 1, first
+        for b in range(B):
+            assert np.abs(g_lp[b, :first[b]] - p_lp[b, :first[b]]).max(initial=0.0) < 1e-4
+    ro.rollout_set_fused_sampling(True)
+    ro.close()
