@@ -838,6 +838,126 @@ __device__ __forceinline__ void dma_mainloop5(const GemmArgs& a, const f16_t* Ao
 #undef D5_SLICE
 }
 
+// The same tile and the same five-stage paired-load loop on EIGHT waves (2 x 4, 128 x 64 of C per wave, two waves per
+// SIMD): a wave that waits -- at a barrier, for its fragment reads, behind a queued staging load -- leaves the SIMD's
+// matrix core to the other one.  Per wave and k-tile: 2 + 2 staging loads; per k-slice 8 MFMAs, 6 fragment reads (W 0-1
+// after MFMAs 0-1, A 0-3 after MFMAs 2-5), 4 half-fragment conversions (after MFMAs 4-7), and of the pair's 4 loads per
+// tile 2, 1, 1 in the three slices that may issue them (after MFMAs 6, 7).  Waits: inside an even k-tile everything
+// but the youngest 8 loads; inside an odd one everything but the youngest 7 (tile p+3's last and the 6 issued so far).
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
+    constexpr int BM = 256, BN = 256, WGN = 4, TM = 4, TN = 2, SLOTS = 8;
+    constexpr int STAGE = (BM + BN) * 64;
+    constexpr int LPT = 4;                            // staging loads per wave per k-tile: A rows, A rows, W rows, W rows
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [5 stages][A 256 x 64 B | W 256 x 64 B]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int NB = a.n_blocks_n, MB = (a.M + BM - 1) / BM;
+    int nb, mb;
+    if (!tile_of(blockIdx.x, MB, NB, mb, nb)) return;
+    const int m0 = mb * BM;
+    const int nk = a.K / 32, nkw = a.Kw / 32;
+    unsigned g_off[LPT];
+    {
+        const int lc = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+        for (int l = 0; l < LPT; ++l) {
+            const int r = ((l & 1) * 8 + wave) * 16 + (lane >> 2);
+            g_off[l] = l < 2 ? ((unsigned)min(m0 + r, a.M - 1) * (unsigned)a.lda + lc * 8) * 2u   // rows >= M: clamped, never stored
+                             : ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.Kw + lc * 8) * 2u;
+        }
+    }
+    const char* Ag = reinterpret_cast<const char*>(a.A);
+    const char* Wg = reinterpret_cast<const char*>(a.W);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    // load l of k-tile kt (clamped to the last one: the count of loads per trip never changes) into stage st
+#define D8_LOAD(st, kt, l)                                                                                      \
+    {                                                                                                           \
+        const int kt_ = min((kt), nk - 1);                                                                      \
+        const unsigned sa_ = lds_base + (st) * STAGE + ((l) >= 2 ? BM * 64 : 0) + (((l) & 1) * 8 + wave) * 1024; \
+        const char* g_ = (l) < 2 ? Ag + (size_t)kt_ * 64 : Wg + (size_t)wrap_k(kt_, nkw) * 64;                  \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
+                     :: "s"(sa_), "v"(g_off[l]), "s"(g_) : "memory");                                           \
+    }
+    int fa[2], fw[2];
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl) {
+        const int ko = ((sl * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
+        fa[sl] = (wm * TM * 32 + (lane & 31)) * 64 + ko;
+        fw[sl] = BM * 64 + (wn * TN * 32 + (lane & 31)) * 64 + ko;
+    }
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    half8 af[2][TM];
+    u32x4_t bf[2][TN], bw[TN];
+#define D8_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
+#define D8_LDA(so, sl, i) *reinterpret_cast<const half8*>(smem + (so) + fa[sl] + (i) * 2048)
+#define D8_LDW(so, sl, j) *reinterpret_cast<const u32x4_t*>(smem + (so) + fw[sl] + (j) * 2048)
+#define D8_SLICE(CUR, NSO, NSL, LOADS, LB, PT, PS0, PS1)                                                        \
+    _Pragma("unroll") for (int q = 0; q < SLOTS; ++q) {                                                         \
+        const int j_ = q / TM, i_ = q % TM;                                                                     \
+        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
+        if (q < 2) bw[q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);                                                     \
+        else if (q < 6) af[1 - (CUR)][q >= 2 && q < 6 ? q - 2 : 0] = D8_LDA(NSO, NSL, q - 2);                   \
+        if (q >= 6 && q - 6 < (LOADS)) {                                                                        \
+            D8_LOAD(PS0, PT, (LB) + q - 6)                                                                      \
+            D8_LOAD(PS1, (PT) + 1, (LB) + q - 6)                                                                \
+        }                                                                                                       \
+        if (q >= 4) {                                                                                           \
+            const int c_ = q >= 4 ? q - 4 : 0, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                                \
+            bf[1 - (CUR)][jj_][h_] = D8_CVT2(bw[jj_][h_]);                                                      \
+            bf[1 - (CUR)][jj_][h_ + 1] = D8_CVT2(bw[jj_][h_ + 1]);                                              \
+        }                                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                      \
+    }
+    int s0 = 0, s1 = 1, s2 = 2, s3 = 3, s4 = 4;
+#pragma unroll
+    for (int l = 0; l < LPT; ++l) { D8_LOAD(0, 0, l) D8_LOAD(1, 1, l) }
+#pragma unroll
+    for (int l = 0; l < LPT; ++l) { D8_LOAD(2, 2, l) D8_LOAD(3, 3, l) }
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT + 1, 15));   // tile 0 landed (its last load is the one before the pair's last)
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = D8_LDA(0, 0, i);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        bw[j] = D8_LDW(0, 0, j);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bf[0][j][c] = D8_CVT2(bw[j][c]);
+    }
+    for (int kt = 0; kt < nk; kt += 2) {
+        const int o0 = s0 * STAGE, o1 = s1 * STAGE, o2 = s2 * STAGE;
+        D8_SLICE(0, o0, 1, 0, 0, 0, 0, 0)
+        __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT, 0));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        D8_SLICE(1, o1, 0, 2, 0, kt + 4, s4, s0)
+        D8_SLICE(0, o1, 1, 1, 2, kt + 4, s4, s0)
+        __builtin_amdgcn_s_waitcnt(dma_waitcnt(6 + 1, 0));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        D8_SLICE(1, o2, 0, 1, 3, kt + 4, s4, s0)
+        const int t0 = s0, t1 = s1;
+        s0 = s2; s1 = s3; s2 = s4; s3 = t0; s4 = t1;
+    }
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after the workgroup ends
+#undef D8_LOAD
+#undef D8_CVT2
+#undef D8_LDA
+#undef D8_LDW
+#undef D8_SLICE
+    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[1], a, m0 + wm * TM * 32 + 32, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[2], a, m0 + wm * TM * 32 + 64, nb, wn, 0, lane);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[3], a, m0 + wm * TM * 32 + 96, nb, wn, 0, lane);
+}
+
 // P5: the five-stage loop with paired staging loads (dma_mainloop5) instead of the four-stage one.
 template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG, bool P5 = false>
 __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
@@ -1023,13 +1143,27 @@ static void launch_dma(const GemmArgs& a, int n_blocks_n, int splits, hipStream_
     dim3 grid(8 * ((n_blocks_n * ((a.M + BM - 1) / BM) + 7) / 8), 1, splits);
     gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG, P5><<<grid, 256, lds, s>>>(b);
 }
-static int g_big_pairs = 1;   // 256 x 256 kernel: 1 = five stages with paired staging loads, 0 = four stages
+template <int EPI>
+static void launch_dma8(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
+    constexpr int lds = 5 * 512 * 64;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)gemm_dma8_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    GemmArgs b = a;
+    b.n_blocks_n = n_blocks_n;
+    dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8), 1, 1);
+    gemm_dma8_kernel<EPI><<<grid, 512, lds, s>>>(b);
+}
+static int g_big_pairs = 2;   // 256 x 256 kernel: 1 = five stages with paired staging loads, 0 = four stages
 void k_gemm_big_pairs(int on) { g_big_pairs = on; }
 template <int EPI>
 static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     GemmArgs b = a;
     b.k_per_split = a.K;
-    if (g_big_pairs) launch_dma<EPI, 256, 256, 2, 2, 1, true>(b, n_blocks_n, 1, s);
+    if (g_big_pairs == 2) launch_dma8<EPI>(b, n_blocks_n, s);
+    else if (g_big_pairs) launch_dma<EPI, 256, 256, 2, 2, 1, true>(b, n_blocks_n, 1, s);
     else launch_dma<EPI, 256, 256, 2, 2, 1, false>(b, n_blocks_n, 1, s);
 }
 
@@ -1054,7 +1188,9 @@ static bool use_big(int epi, const GemmArgs& a, int splits) {
 int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
     GemmArgs a;
     a.M = M; a.N = N; a.K = K; a.Kw = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
-    return use_big(MG_LSE, a, 1) ? N / 128 : N / 64;
+    // column groups are as wide as a wave's share of the tile: 128 columns on the four-wave 256 x 256 kernels, 64 on the
+    // eight-wave one and on the 128 x 128 kernel
+    return use_big(MG_LSE, a, 1) && g_big_pairs != 2 ? N / 128 : N / 64;
 }
 
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
