@@ -444,7 +444,7 @@ def main():
         sum(int(p_ - 1) * int(p_) / 2.0 for p_ in plen)
     work = {
         "gemm_prefill": ("mfma", 2.0 * shape.body_params() * (n_tok_scored + n_tok_prefill) / 1e12, "TFLOP",
-                         "large-M MFMA GEMMs of prefill and scoring (gemm_dma_kernel 256x256 / gemm_mfma_kernel 128x128)"),
+                         "large-M MFMA GEMMs of prefill and scoring (gemm_dma8_kernel 256x256 / gemm_mfma_kernel 128x128)"),
         "lmhead_score": ("mfma", 2.0 * shape.head_params() * max(n_tok_scored - 2 * B, 0) / 1e12, "TFLOP",
                          "LM head + log-sum-exp + target gather (MG_LSE epilogue)"),
         "attn_prefill": ("mfma", shape.n_layers * 4.0 * shape.n_q_heads * shape.head_dim * attn_pairs / 1e12, "TFLOP",

@@ -702,148 +702,24 @@ __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop
 #undef DG_STEP
 }
 
-// The same k loop with the staging loads issued in PAIRS of k-tiles and five stages.  A stage row is 64 B, half a
-// 128-byte cache line, and a request for half a line makes the L2 deliver the whole line: with one k-tile per
-// request group the L2 -> L1 path carries twice the operand bytes (counted: 4 sectors per request, the vector L1
-// stalled on pending requests for most of the kernel).  Here the loads of k-tiles 2p and 2p+1 -- the two halves of
-// the same lines -- are issued back to back, so the second finds the line already on its way and only one request
-// per line reaches the L2.  A pair needs two free stages; with five stages the pair (p+4, p+5) is issued from the
-// second slice of tile p (whose stage the barrier before it has released) to the end of tile p+1, three, three and
-// two loads of each tile per slice: bunched into fewer slices, the loads queue up in the vector memory path and hold
-// back the MFMAs behind them.  The pair has two tiles of MFMA work to arrive in.  Waits: before the barrier
-// inside an even tile p everything but the youngest 16 loads (pair p+2, p+3) has landed, i.e. tile p+1; inside an odd
-// tile p+1 everything but the youngest 13 (the last load of tile p+3 and the 12 loads of pair p+4, p+5 issued so
-// far), i.e. tile p+2.
-// Requires nk % 2 == 0, four by four fragments per wave and 5 * (BM + BN) * 64 bytes of LDS.
-template <int EPI, int BM, int BN, int WGM, int WGN>
-__device__ __forceinline__ void dma_mainloop5(const GemmArgs& a, const f16_t* Aop, int lda, const bf16_t* Wop, int m0,
-                                              int nb, int kbeg, int nk, int wave, int lane, char* smem,
-                                              floatx16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
-    constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-    constexpr int SLOTS = TM * TN;
-    constexpr int STAGE = (BM + BN) * 64;
-    constexpr int LPT = (BM + BN) / 64;              // staging loads per wave per k-tile
-    static_assert(WGM * WGN == 4, "four waves");
-    static_assert(TM == 4 && TN == 4 && LPT == 8, "the slice schedule below is written for 4 x 4 fragments per wave");
-    const int wm = wave / WGN, wn = wave % WGN;
-    unsigned g_off[LPT];
-    {
-        const int lc = (lane & 3) ^ ((lane >> 4) & 3);
-#pragma unroll
-        for (int l = 0; l < LPT; ++l) {
-            if (l < BM / 64) {
-                const int r = (l * 4 + wave) * 16 + (lane >> 2);
-                g_off[l] = ((unsigned)min(m0 + r, a.M - 1) * (unsigned)lda + lc * 8) * 2u;   // rows >= M: clamped, never stored
-            } else {
-                const int r = ((l - BM / 64) * 4 + wave) * 16 + (lane >> 2);
-                g_off[l] = ((unsigned)min(w_row_of<EPI, BN>(r, nb, a), a.Wrows - 1) * (unsigned)a.Kw + lc * 8) * 2u;
-            }
-        }
-    }
-    const char* Ag = reinterpret_cast<const char*>(Aop + kbeg);
-    const char* Wg = reinterpret_cast<const char*>(Wop);
-    const int kw0 = kbeg / 32, nkw = a.Kw / 32;
-    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-    // load l of k-tile kt (clamped to the last one: the count of loads per trip never changes) into stage st
-#define D5_LOAD(st, kt, l)                                                                                      \
-    {                                                                                                           \
-        const int kt_ = min((kt), nk - 1);                                                                      \
-        const unsigned sa_ = lds_base + (st) * STAGE + ((l) * 4 + wave) * 1024;                                 \
-        const char* g_ = (l) < BM / 64 ? Ag + (size_t)kt_ * 64 : Wg + (size_t)wrap_k(kw0 + kt_, nkw) * 64;      \
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
-                     :: "s"(sa_), "v"(g_off[l]), "s"(g_) : "memory");                                           \
-    }
-    // fragment offsets inside a stage: row lane%32 of a 32-row block, logical chunk sl*2 + lane/32, swizzled
-    int fa[2], fw[2];
-#pragma unroll
-    for (int sl = 0; sl < 2; ++sl) {
-        const int ko = ((sl * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
-        fa[sl] = (wm * TM * 32 + (lane & 31)) * 64 + ko;
-        fw[sl] = BM * 64 + (wn * TN * 32 + (lane & 31)) * 64 + ko;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    half8 af[2][TM];
-    u32x4_t bf[2][TN], bw[TN];
-#define D5_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
-#define D5_LDA(so, sl, i) *reinterpret_cast<const half8*>(smem + (so) + fa[sl] + (i) * 2048)
-#define D5_LDW(so, sl, j) *reinterpret_cast<const u32x4_t*>(smem + (so) + fw[sl] + (j) * 2048)
-    // One k-slice: 16 MFMAs on fragment set CUR, with the rest spread between them.  Fragment reads of slice NSL of
-    // the stage at byte offset NSO into the other set: the four W fragments after MFMAs 0-3, the four A fragments
-    // after MFMAs 5, 7, 9, 11; LOADS pairs of staging loads (loads LB, LB+1, .. of k-tiles PT and PT + 1, into stages
-    // PS0 and PS1) after MFMAs 4, 8, 12; the eight half-fragment conversions of the W fragments after MFMAs 8-15.
-#define D5_SLICE(CUR, NSO, NSL, LOADS, LB, PT, PS0, PS1)                                                        \
-    _Pragma("unroll") for (int q = 0; q < SLOTS; ++q) {                                                         \
-        const int j_ = q / TM, i_ = q % TM;                                                                     \
-        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
-        {                                                                                                       \
-            if (q < 4) bw[q < 4 ? q : 0] = D5_LDW(NSO, NSL, q);                                                 \
-            else if (q < 12 && (q & 1)) af[1 - (CUR)][q >= 5 && q < 12 ? (q - 5) / 2 : 0] = D5_LDA(NSO, NSL, (q - 5) / 2); \
-        }                                                                                                       \
-        if (q >= 4 && (q & 3) == 0 && (q - 4) / 4 < (LOADS)) {                                                  \
-            D5_LOAD(PS0, PT, (LB) + (q - 4) / 4)                                                                \
-            D5_LOAD(PS1, (PT) + 1, (LB) + (q - 4) / 4)                                                          \
-        }                                                                                                       \
-        if (q >= 8) {                                                                                           \
-            const int c_ = q >= 8 ? q - 8 : 0, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                                \
-            bf[1 - (CUR)][jj_][h_] = D5_CVT2(bw[jj_][h_]);                                                      \
-            bf[1 - (CUR)][jj_][h_ + 1] = D5_CVT2(bw[jj_][h_ + 1]);                                              \
-        }                                                                                                       \
-        __builtin_amdgcn_sched_barrier(0);                                                                      \
-    }
-    // stage of k-tile t is t % 5; s0 .. s4 are the stages of tiles kt .. kt + 4 (kt even), rotated by two per trip
-    int s0 = 0, s1 = 1, s2 = 2, s3 = 3, s4 = 4;
-    // prologue: pairs (0, 1) and (2, 3)
-#pragma unroll
-    for (int l = 0; l < LPT; ++l) { D5_LOAD(0, 0, l) D5_LOAD(1, 1, l) }
-#pragma unroll
-    for (int l = 0; l < LPT; ++l) { D5_LOAD(2, 2, l) D5_LOAD(3, 3, l) }
-    __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT + 1, 15));   // tile 0 landed (its last load is the one before the pair's last)
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = D5_LDA(0, 0, i);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        bw[j] = D5_LDW(0, 0, j);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) bf[0][j][c] = D5_CVT2(bw[j][c]);
-    }
-    for (int kt = 0; kt < nk; kt += 2) {
-        const int o0 = s0 * STAGE, o1 = s1 * STAGE, o2 = s2 * STAGE;
-        // even tile kt: first slice (no loads), barrier (tile kt+1 complete, stage of tile kt released), second
-        // slice with the first half of pair (kt+4, kt+5) into the stages s4 and s0
-        D5_SLICE(0, o0, 1, 0, 0, 0, 0, 0)
-        __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT, 0));
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        D5_SLICE(1, o1, 0, 3, 0, kt + 4, s4, s0)
-        // odd tile kt+1: first slice with the second half of the pair, barrier (tile kt+2 complete), second slice
-        D5_SLICE(0, o1, 1, 3, 3, kt + 4, s4, s0)
-        __builtin_amdgcn_s_waitcnt(dma_waitcnt(12 + 1, 0));   // all but the 12 loads of this trip and tile kt+3's last
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        D5_SLICE(1, o2, 0, 2, 6, kt + 4, s4, s0)
-        const int t0 = s0, t1 = s1;
-        s0 = s2; s1 = s3; s2 = s4; s3 = t0; s4 = t1;
-    }
-    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after the workgroup ends
-#undef D5_LOAD
-#undef D5_CVT2
-#undef D5_LDA
-#undef D5_LDW
-#undef D5_SLICE
-}
-
-// The same tile and the same five-stage paired-load loop on EIGHT waves (2 x 4, 128 x 64 of C per wave, two waves per
-// SIMD): a wave that waits -- at a barrier, for its fragment reads, behind a queued staging load -- leaves the SIMD's
-// matrix core to the other one.  Per wave and k-tile: 2 + 2 staging loads; per k-slice 8 MFMAs, 6 fragment reads (W 0-1
-// after MFMAs 0-1, A 0-3 after MFMAs 2-5), 4 half-fragment conversions (after MFMAs 4-7), and of the pair's 4 loads per
-// tile 2, 1, 1 in the three slices that may issue them (after MFMAs 6, 7).  Waits: inside an even k-tile everything
-// but the youngest 8 loads; inside an odd one everything but the youngest 7 (tile p+3's last and the 6 issued so far).
+// Large-M GEMM, 256 x 256 tiles, eight waves (2 x 4; 128 x 64 of C per wave; two waves per SIMD, so a wave that waits
+// -- at a barrier, for its fragment reads, behind a queued staging load -- leaves the SIMD's matrix core to the other
+// one), operands staged global -> LDS through FIVE stages of 32 k with the loads of two consecutive k-tiles issued
+// together.  A stage row is 64 B, half a 128-byte cache line, and a request for half a line makes the L2 deliver the
+// whole line: with one k-tile per request group the L2 -> L1 path carries twice the operand bytes (counted: 4 sectors
+// per request, the vector L1 stalled on pending requests for most of the kernel).  The loads of k-tiles 2p and 2p+1 --
+// the two halves of the same lines -- go out back to back, so the second finds the line already on its way and one
+// request per line reaches the L2.  A pair needs two free stages; with five stages the pair (p+4, p+5) is issued from
+// the second slice of tile p (whose stage the barrier before it has released) to the end of tile p+1, spread over
+// those three slices: bunched, the loads queue up in the vector memory path and hold back the MFMAs behind them.
+// Per wave and k-tile: 2 + 2 staging loads; per k-slice 8 MFMAs, 6 fragment reads (W 0-1 after MFMAs 0-1, A 0-3 after
+// MFMAs 2-5), 4 half-fragment conversions (after MFMAs 4-7), and of the pair's 4 loads per tile 2, 1, 1 in the three
+// slices that may issue them (after MFMAs 6, 7).  Loads complete in issue order, so the waits are counts: inside an
+// even k-tile p everything but the youngest 8 loads (pair p+2, p+3) has landed, i.e. tile p+1; inside an odd tile p+1
+// everything but the youngest 7 (tile p+3's last load and the 6 of pair p+4, p+5 issued so far), i.e. tile p+2.  The
+// loop issues the same number of loads on every trip (the last trips re-request the final tile), so the counts hold to
+// the end; vmcnt(0) before the epilogue keeps loads from landing in LDS after the workgroup has ended.
+// Requires K % 64 == 0, no split over K, 5 * 512 * 64 bytes of LDS.
 template <int EPI>
 __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     constexpr int BM = 256, BN = 256, WGN = 4, TM = 4, TN = 2, SLOTS = 8;
@@ -958,11 +834,10 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     mg_epilogue<EPI, BN, TN, WGN>(acc[3], a, m0 + wm * TM * 32 + 96, nb, wn, 0, lane);
 }
 
-// P5: the five-stage loop with paired staging loads (dma_mainloop5) instead of the four-stage one.
-template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG, bool P5 = false>
+template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
 __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 or 5 stages][A BM x 64 B | W BN x 64 B]
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [4 stages][A BM x 64 B | W BN x 64 B]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
@@ -984,10 +859,7 @@ __global__ __launch_bounds__(256, MINWG) void gemm_dma_kernel(GemmArgs a) {
         if (TM > 1) kl_epilogue<BN, TN, WGN>(acc[TM > 1 ? 1 : 0], acc_r[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, lane);
         return;
     }
-    if constexpr (P5) {
-        dma_mainloop5<EPI, BM, BN, WGM, WGN>(a, a.A, a.lda, a.W, m0, nb, kbeg, nk, wave, lane, smem, acc);
-    }
-    else dma_mainloop<EPI, BM, BN, WGM, WGN>(a, a.A, a.lda, a.W, m0, nb, kbeg, nk, wave, lane, smem, acc);
+    dma_mainloop<EPI, BM, BN, WGM, WGN>(a, a.A, a.lda, a.W, m0, nb, kbeg, nk, wave, lane, smem, acc);
     // written out: with the largest epilogue the unroller gives up on a loop over the bands
     mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, ks, lane);
     if (TM > 1) mg_epilogue<EPI, BN, TN, WGN>(acc[TM > 1 ? 1 : 0], a, m0 + wm * TM * 32 + 32, nb, wn, ks, lane);
@@ -1129,19 +1001,19 @@ static void launch(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s)
     gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, BKT, WF16><<<grid, 256, lds, s>>>(b);
 }
 
-template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG, bool P5 = false>
+template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
 static void launch_dma(const GemmArgs& a, int n_blocks_n, int splits, hipStream_t s) {
-    constexpr int lds = (P5 ? 5 : 4) * (BM + BN) * 64;
+    constexpr int lds = 4 * (BM + BN) * 64;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG, P5>,
+        (void)hipFuncSetAttribute((const void*)gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
     dim3 grid(8 * ((n_blocks_n * ((a.M + BM - 1) / BM) + 7) / 8), 1, splits);
-    gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG, P5><<<grid, 256, lds, s>>>(b);
+    gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG><<<grid, 256, lds, s>>>(b);
 }
 template <int EPI>
 static void launch_dma8(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
@@ -1156,15 +1028,15 @@ static void launch_dma8(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8), 1, 1);
     gemm_dma8_kernel<EPI><<<grid, 512, lds, s>>>(b);
 }
-static int g_big_pairs = 2;   // 256 x 256 kernel: 1 = five stages with paired staging loads, 0 = four stages
+// 256 x 256 kernel: 1 = eight waves, five stages, paired staging loads; 0 = four waves, four stages (measurement switch)
+static int g_big_pairs = 1;
 void k_gemm_big_pairs(int on) { g_big_pairs = on; }
 template <int EPI>
 static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     GemmArgs b = a;
     b.k_per_split = a.K;
-    if (g_big_pairs == 2) launch_dma8<EPI>(b, n_blocks_n, s);
-    else if (g_big_pairs) launch_dma<EPI, 256, 256, 2, 2, 1, true>(b, n_blocks_n, 1, s);
-    else launch_dma<EPI, 256, 256, 2, 2, 1, false>(b, n_blocks_n, 1, s);
+    if (g_big_pairs) launch_dma8<EPI>(b, n_blocks_n, s);
+    else launch_dma<EPI, 256, 256, 2, 2, 1>(b, n_blocks_n, 1, s);
 }
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
@@ -1190,7 +1062,7 @@ int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
     a.M = M; a.N = N; a.K = K; a.Kw = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
     // column groups are as wide as a wave's share of the tile: 128 columns on the four-wave 256 x 256 kernels, 64 on the
     // eight-wave one and on the 128 x 128 kernel
-    return use_big(MG_LSE, a, 1) && g_big_pairs != 2 ? N / 128 : N / 64;
+    return use_big(MG_LSE, a, 1) && !g_big_pairs ? N / 128 : N / 64;
 }
 
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {

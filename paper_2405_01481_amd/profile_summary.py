@@ -23,7 +23,7 @@ import sys
 
 # kernel name pattern -> class of bench.py's roofline entries (the LM-head GEMM is the tile kernel with epilogue 5)
 CLASSES = {r"gemm_ring_kernel": "gemm_decode", r"attn_decode_kernel": "attn_decode",
-           r"gemm_dma_kernel<[0-4],": "gemm_prefill", r"gemm_dma_kernel<5,": "lmhead_score",
+           r"gemm_dma8?_kernel<[0-4][,>]": "gemm_prefill", r"gemm_dma8?_kernel<5[,>]": "lmhead_score",
            r"attn_prefill_kernel": "attn_prefill"}
 
 
