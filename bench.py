@@ -196,6 +196,8 @@ def main():
                     help="measurement switch: decode GEMMs above this many rows use the 128 x 128 tile kernel (library default -1 = never)")
     ap.add_argument("--precise-layers", type=int, default=None,
                     help="measurement switch: layers carried as fp16 pairs (library default 1)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time torch.matmul (the vendor library) on the layer's GEMM shapes, as context")
     ap.add_argument("--no-alt-decode", action="store_true",
                     help="skip the extra generation without the policy's fp16 copy (key decode_without_fp16_copy)")
     ap.add_argument("--progress", action="store_true", help="phase markers with elapsed time on stderr")
@@ -384,6 +386,30 @@ def main():
         prof[name] = {"ms_timed_raw": ms, "ms_timed": max(ms - n * event_overhead_ms, 0.0), "launches_timed": n}
         ro.rollout_profile_enable(k, 0)
 
+    # context for the MFMA-bound rooflines: what the matrix cores sustain on their own under this chip's power
+    # management (random operands as in a real GEMM, and zeros), and optionally the vendor library's GEMM on the layer's
+    # shapes with the same value distributions
+    mfma_sustained = {"random_operands": ro.rollout_probe_mfma_rate(True), "zeros": ro.rollout_probe_mfma_rate(False)}
+    vendor = None
+    if args.vendor_gemm:
+        vendor = {}
+        Mv = min(args.chunk, 16384)
+        nqkv = (shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim
+        for name, (N_, K_) in {"qkv": (nqkv, shape.d_model), "o": (shape.d_model, shape.n_q_heads * shape.head_dim),
+                               "gate_up": (2 * shape.d_ffn, shape.d_model), "down": (shape.d_model, shape.d_ffn)}.items():
+            A_ = (torch.rand(Mv, K_, device=dev) * 2 - 1).to(torch.float16)
+            W_ = ((torch.rand(N_, K_, device=dev) - 0.5) * 0.08).to(torch.float16)
+            for _ in range(3):
+                torch.matmul(A_, W_.t())
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0_.record()
+            for _ in range(10):
+                torch.matmul(A_, W_.t())
+            e1_.record()
+            e1_.synchronize()
+            vendor[name] = {"M": Mv, "N": N_, "K": K_, "tflops": 2.0 * Mv * N_ * K_ * 10 / (e0_.elapsed_time(e1_) * 1e-3) / 1e12}
+            del A_, W_
+
     # prompt prefill alone, to split generation time into prefill + decode loop
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -471,6 +497,8 @@ def main():
                "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": achieved / peak,
                "avg_launch_ms": avg, "launches_per_step": n, "ms_per_step": tot,
                "algorithmic_per_launch": amount / n, "algorithmic_unit": unit, "traffic": None}
+        if bound == "mfma":
+            ent["frac_of_sustained_mfma"] = achieved / mfma_sustained["random_operands"]
         t = traffic_db.get(args.workload, {}).get(name)
         if t and not reduced and args.impl in (-1, 1) and not t.get("context_dependent"):
             # HBM-side bytes per launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known
@@ -504,6 +532,8 @@ def main():
         "score_mfma_frac": (score_tflops / MFMA_PEAK_TFLOPS) if score_tflops else None,
         "kernel_classes": prof,
         "event_overhead_us": event_overhead_ms * 1e3,
+        "mfma_sustained_tflops": mfma_sustained,
+        "vendor_gemm": vendor,
         "roofline": roofline,
         "roofline_others": rl[1:],
         "host_cores": os.cpu_count(),

@@ -128,6 +128,7 @@ void k_sample(const float* logits, int ldz, int V, int B, SampleArgs a, int* las
 void k_sample_blocks(const float4* stats, int V, const void* h, int ldh, const void* W, int d, int B, SampleArgs a,
                      int* last_tok, int* seq_len, int* gen_count, int* finished, int* step_count, int* tok_out,
                      float* logp_out, int* out_ids, float* out_logp, int out_stride, hipStream_t s);
+void k_mfma_rate(void* scratch, int n_wg, int iters, int random, hipStream_t s);
 void k_lse_gather(const float* logits, int ldz, int V, int nrows, const int* tok_tgt, const int* tok_slot,
                   const int* tok_pos, float* logp_out, int ld_out, hipStream_t s);
 void k_kl(const float* lp, const float* lr, const int* seq_len, const int* prompt_len, int B, int Lmax, float coef,

@@ -1709,4 +1709,33 @@ int rollout_profile_event_overhead(rl_ctx* c, int32_t pairs, double* overhead_ms
     return rc;
 }
 
+int rollout_probe_mfma_rate(rl_ctx* c, int32_t random_operands, double* tflops, void* stream) {
+    if (!c || !tflops) return fail(RL_EINVAL, "NULL argument");
+    hipStream_t s = (hipStream_t)stream;
+    int dev = 0, n_cu = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu < 1 || n_cu > 1024) return fail(RL_EHIP, "unexpected compute-unit count %d", n_cu);
+    // the fp32 logits area of the workspace is free between calls (at least 512 rows of vocab floats)
+    if ((size_t)c->L.logit_rows * c->cfg.vocab * 4 < 65536 + (size_t)n_cu * 1024)
+        return fail(RL_ENOSPACE, "workspace too small for the probe");
+    void* scratch = c->at<char>(c->L.logits);
+    hipEvent_t a = nullptr, b = nullptr;
+    HIP_TRY(hipEventCreate(&a));
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(RL_EHIP, "hipEventCreate failed"); }
+    const int iters = 200000;                      // about 0.1 s: long enough for the clock to settle
+    k_mfma_rate(scratch, n_cu, iters, random_operands != 0, s);   // warm
+    int rc = RL_OK;
+    float ms = 0.f;
+    if (hipEventRecord(a, s) != hipSuccess) rc = fail(RL_EHIP, "event record failed");
+    k_mfma_rate(scratch, n_cu, iters, random_operands != 0, s);
+    if (rc == RL_OK && (hipEventRecord(b, s) != hipSuccess || hipEventSynchronize(b) != hipSuccess ||
+                        hipEventElapsedTime(&ms, a, b) != hipSuccess))
+        rc = fail(RL_EHIP, "event timing failed");
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (rc == RL_OK) *tflops = (double)n_cu * 4 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12;
+    return rc;
+}
+
 }  // extern "C"

@@ -91,6 +91,7 @@ def lib():
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
         L.rollout_profile_event_overhead.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
+        L.rollout_probe_mfma_rate.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -300,6 +301,11 @@ class Rollout:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().rollout_profile_read(self.h, kernel_class, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+    def rollout_probe_mfma_rate(self, random_operands: bool = True) -> float:
+        tf = C.c_double()
+        _chk(lib().rollout_probe_mfma_rate(self.h, 1 if random_operands else 0, C.byref(tf), _stream()))
+        return tf.value
 
     def rollout_profile_event_overhead(self, pairs: int = 256) -> float:
         ms = C.c_double()

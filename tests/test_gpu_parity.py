@@ -787,3 +787,40 @@ def test_sampling_from_block_statistics(shape):
             assert np.abs(g_lp[b, :first[b]] - p_lp[b, :first[b]]).max(initial=0.0) < 1e-4
     ro.rollout_set_fused_sampling(True)
     ro.close()
+
+
+@pytest.mark.gpu
+def test_measurement_instruments():
+    """The two instruments bench.py leans on: the cost of an empty event pair (microseconds, not zero, not
+    milliseconds) and the matrix cores' sustained rate (zeros at least as fast as random operands, both below the
+    published 2.5 PFLOP/s); neither disturbs live sequences."""
+    shape = MINI64
+    B, G = 3, 4
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 32 + 2 * G)
+    ids, lens = synth.make_prompts(shape.vocab, B, 32, 20, 5)
+    dev = "cuda:0"
+    out = torch.zeros(B, G, dtype=torch.int32, device=dev)
+    lp = torch.zeros(B, G, dtype=torch.float32, device=dev)
+    ro.rollout_prefill(torch.tensor(ids, device=dev), lens)
+    toks = []
+    for step in range(2 * G):
+        t = torch.zeros(B, dtype=torch.int32, device=dev)
+        l = torch.zeros(B, dtype=torch.float32, device=dev)
+        ro.rollout_decode_step(R.sample_cfg(4, 0.0), None, t, l)
+        toks.append(t.cpu().numpy())
+        if step == G - 1:
+            ov = ro.rollout_profile_event_overhead(64)
+            rnd, zer = ro.rollout_probe_mfma_rate(True), ro.rollout_probe_mfma_rate(False)
+            print("event pair %.2f us, MFMA %.0f / %.0f TFLOP/s" % (ov * 1e3, rnd, zer))
+            assert 1e-4 < ov < 0.1
+            assert 200.0 < rnd <= zer * 1.02 and zer < 2600.0
+    got = np.stack(toks, axis=1)
+    # the same rollout without the probes in the middle
+    ro.rollout_generate(R.sample_cfg(4, 0.0), torch.tensor(ids, device=dev), lens, 2 * G,
+                        torch.zeros(B, 2 * G, dtype=torch.int32, device=dev), None,
+                        torch.zeros(B, 2 * G, dtype=torch.float32, device=dev))
+    ref = torch.zeros(B, 2 * G, dtype=torch.int32, device=dev)
+    ro.rollout_generate(R.sample_cfg(4, 0.0), torch.tensor(ids, device=dev), lens, 2 * G, ref, None,
+                        torch.zeros(B, 2 * G, dtype=torch.float32, device=dev))
+    assert np.array_equal(got, ref.cpu().numpy())
+    ro.close()
