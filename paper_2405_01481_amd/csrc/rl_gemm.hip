@@ -105,9 +105,35 @@ __device__ __forceinline__ float row32_sum(float v) {
 // Epilogue shared by the tile kernels, for one 32-row band of a wave's accumulators: acc[j][r] of the
 // wave in tile-column position wn is C(row, col) with
 //   row = m_base + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
+// Row metadata of the MG_QKV epilogue held across a wave: lane l keeps position and cache page of rows row0 + l and
+// row0 + 64 + l (fetched before the main loop, so that the epilogue starts without a chain of dependent loads).
+struct QkvRowMeta {
+    int pos[2] = {-1, -1};    // < 0: padding row / past M
+    int page[2] = {0, 0};
+    int row0 = 0;
+};
+__device__ __forceinline__ QkvRowMeta qkv_row_meta(const GemmArgs& a, int row0, int lane) {
+    QkvRowMeta q;
+    q.row0 = row0;
+    int slot[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int m = row0 + h * 64 + lane;
+        const int p_ = a.tok_pos[min(m, a.M - 1)];
+        slot[h] = a.pool ? a.tok_slot[min(m, a.M - 1)] : 0;
+        q.pos[h] = m < a.M ? p_ : -1;
+    }
+    if (a.pool) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            q.page[h] = a.block_table[(int64_t)(q.pos[h] >= 0 ? slot[h] : 0) * a.mpps + max(q.pos[h], 0) / a.geo.PT];
+    }
+    return q;
+}
+
 template <int EPI, int BN, int TN, int WGN>
 __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs& a, int m_base, int nb, int wn,
-                                            int ks, int lane) {
+                                            int ks, int lane, const QkvRowMeta* pre = nullptr) {
     const int lg = lane >> 5, lrow = lane & 31;
     if constexpr (EPI == MG_SAMPLE) {
         // Reductions over the 32 lanes that hold one row of a 32-column MFMA tile.  Ties of the maximum go to the
@@ -169,14 +195,27 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
         const int head_hi = col_of(TN - 2) / hd;              // wave-uniform
         int pos[16];                                           // < 0: padding row of the packed token list
         int page[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
-            const int p_ = a.tok_pos[min(m, a.M - 1)];
-            pos[r] = m < a.M ? p_ : -1;
-        }
         const bool to_pool = a.pool != nullptr && head_hi >= Hq;
-        if (to_pool) {
+        if (pre) {
+            // the wave already holds these, one row per lane: pick them up with cross-lane reads
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rel = m_base - pre->row0 + 8 * (r >> 2) + 4 * lg + (r & 3);   // 0 .. 127
+                const int src = rel & 63;
+                const int p0 = __shfl(pre->pos[0], src, RL_WAVE), p1 = __shfl(pre->pos[1], src, RL_WAVE);
+                const int g0 = __shfl(pre->page[0], src, RL_WAVE), g1 = __shfl(pre->page[1], src, RL_WAVE);
+                pos[r] = rel < 64 ? p0 : p1;
+                page[r] = rel < 64 ? g0 : g1;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m_base + 8 * (r >> 2) + 4 * lg + (r & 3);
+                const int p_ = a.tok_pos[min(m, a.M - 1)];
+                pos[r] = m < a.M ? p_ : -1;
+            }
+        }
+        if (to_pool && !pre) {
             int slot[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) slot[r] = a.tok_slot[min(m_base + 8 * (r >> 2) + 4 * lg + (r & 3), a.M - 1)];
@@ -797,7 +836,12 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     for (int l = 0; l < LPT; ++l) { D8_LOAD(0, 0, l) D8_LOAD(1, 1, l) }
 #pragma unroll
     for (int l = 0; l < LPT; ++l) { D8_LOAD(2, 2, l) D8_LOAD(3, 3, l) }
-    __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT + 1, 15));   // tile 0 landed (its last load is the one before the pair's last)
+    // MG_QKV: positions and cache pages of this wave's 128 rows, one row per lane and half, fetched while the first
+    // k-tiles arrive (ordinary loads issued after the staging loads above: they complete after those, so the wait
+    // below, which counts the youngest outstanding loads, still covers tile 0 -- and usually tiles 1-3 too)
+    QkvRowMeta meta;
+    if constexpr (EPI == MG_QKV) meta = qkv_row_meta(a, m0 + wm * TM * 32, lane);
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(EPI == MG_QKV ? 0 : 2 * LPT + 1, 15));   // tile 0 landed (its last load is the one before the pair's last)
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < TM; ++i) af[0][i] = D8_LDA(0, 0, i);
@@ -828,10 +872,11 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
 #undef D8_LDA
 #undef D8_LDW
 #undef D8_SLICE
-    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[1], a, m0 + wm * TM * 32 + 32, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[2], a, m0 + wm * TM * 32 + 64, nb, wn, 0, lane);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[3], a, m0 + wm * TM * 32 + 96, nb, wn, 0, lane);
+    const QkvRowMeta* pre = EPI == MG_QKV ? &meta : nullptr;
+    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, 0, lane, pre);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[1], a, m0 + wm * TM * 32 + 32, nb, wn, 0, lane, pre);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[2], a, m0 + wm * TM * 32 + 64, nb, wn, 0, lane, pre);
+    mg_epilogue<EPI, BN, TN, WGN>(acc[3], a, m0 + wm * TM * 32 + 96, nb, wn, 0, lane, pre);
 }
 
 template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
