@@ -82,6 +82,7 @@ def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperatu
     w = {k: synth.to_numpy_f32(v).astype(np.float64) for k, v in wp.items() if k != "layers"}
     w["layers"] = [{k: synth.to_numpy_f32(v).astype(np.float64) for k, v in lw.items()} for lw in wp["layers"]]
     m = O.Model(shape, w)
+    print("[bench] cpu oracle: weights converted, %d repetitions of generate + score" % (reps + 1), file=sys.stderr, flush=True)
     prompt = ids[0, :min(sample_P, int(prompt_len[0]))]
     tg, ts, toks = [], [], None
     for r in range(reps + 1):
@@ -91,6 +92,7 @@ def cpu_baseline(shape, wp, ids, prompt_len, seed, sample_P, sample_G, temperatu
         seq = np.concatenate([prompt, out[0]])
         O.score(m, seq)
         t2 = time.perf_counter()
+        print("[bench] cpu oracle repetition %d: generate %.1f s, score %.1f s" % (r, t1 - t0, t2 - t1), file=sys.stderr, flush=True)
         if r > 0:                      # the first repetition is the warm-up
             tg.append(t1 - t0)
             ts.append(t2 - t1)
@@ -342,19 +344,26 @@ def main():
     torch.cuda.synchronize()
     torch.cuda.set_stream(stream)
 
-    for _ in range(args.warmup):
+    def beat(msg):
+        # one short line per step on stderr, always: a default run is otherwise silent for minutes (stdout keeps the JSON line alone)
+        print("[bench %.0fs] %s" % (time.perf_counter() - t_start, msg), file=sys.stderr, flush=True)
+
+    for i in range(args.warmup):
         one_step(False)
+        ev[2].synchronize()
+        beat("warm-up step %d of %d done" % (i + 1, args.warmup))
     torch.cuda.synchronize()
     ro.rollout_check()
 
     gen_ms, score_ms = [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
         one_step(True)
         ev[2].synchronize()
         gen_ms.append(ev[0].elapsed_time(ev[1]))
         score_ms.append(ev[1].elapsed_time(ev[2]))
+        beat("step %d of %d: %.0f ms" % (i + 1, args.steps, gen_ms[-1] + score_ms[-1]))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ro.rollout_check()

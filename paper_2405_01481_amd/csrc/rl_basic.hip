@@ -175,6 +175,34 @@ __device__ __forceinline__ void put_pair(T* o, int64_t lo_off, float v, int spli
     o[0] = hi;
     if (split) o[lo_off] = from_f<T>(v - to_f(hi));
 }
+// Four consecutive values (o 4-element aligned) scaled by four consecutive gains: one store per plane, one gain load.
+template <typename T, typename TW>
+__device__ __forceinline__ void put_pair4(T* o, int64_t lo_off, float4 v, float rs, const TW* g, int split) {
+    float gf[4];
+    if constexpr (sizeof(TW) == 2) {
+        const uint2 gv = *reinterpret_cast<const uint2*>(g);          // four bf16
+        gf[0] = __uint_as_float(gv.x << 16); gf[1] = __uint_as_float(gv.x & 0xffff0000u);
+        gf[2] = __uint_as_float(gv.y << 16); gf[3] = __uint_as_float(gv.y & 0xffff0000u);
+    } else {
+        const float4 gv = *reinterpret_cast<const float4*>(g);
+        gf[0] = gv.x; gf[1] = gv.y; gf[2] = gv.z; gf[3] = gv.w;
+    }
+    const float w[4] = {v.x * rs * gf[0], v.y * rs * gf[1], v.z * rs * gf[2], v.w * rs * gf[3]};
+    if constexpr (sizeof(T) == 2) {
+        typedef T T4 __attribute__((ext_vector_type(4)));
+        T4 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            hi[e] = from_f<T>(w[e]);
+            lo[e] = from_f<T>(w[e] - to_f(hi[e]));
+        }
+        *reinterpret_cast<T4*>(o) = hi;
+        if (split) *reinterpret_cast<T4*>(o + lo_off) = lo;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) put_pair(o + e, lo_off, w[e], split);
+    }
+}
 
 // ---------------------------------------------------------------- RMSNorm: out = x * rsqrt(mean(x^2) + eps) * g
 // split: the output row is twice as wide, [d values rounded to T | d remainders] (fp16 pairs).
@@ -201,12 +229,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* x, const TW* 
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int j = (it * 256 + threadIdx.x) * 4;
-            if (j < d) {
-                put_pair(o + j, d, keep[it].x * rs * to_f(g[j]), split);
-                put_pair(o + j + 1, d, keep[it].y * rs * to_f(g[j + 1]), split);
-                put_pair(o + j + 2, d, keep[it].z * rs * to_f(g[j + 2]), split);
-                put_pair(o + j + 3, d, keep[it].w * rs * to_f(g[j + 3]), split);
-            }
+            if (j < d) put_pair4(o + j, d, keep[it], rs, g + j, split);
         }
         return;
     }
@@ -508,12 +531,7 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float* x, const float*
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int j = (it * 1024 + threadIdx.x) * 4;
-        if (j < d) {
-            put_pair(o + j + 0, d, keep[it].x * rs * to_f(g[j + 0]), split);
-            put_pair(o + j + 1, d, keep[it].y * rs * to_f(g[j + 1]), split);
-            put_pair(o + j + 2, d, keep[it].z * rs * to_f(g[j + 2]), split);
-            put_pair(o + j + 3, d, keep[it].w * rs * to_f(g[j + 3]), split);
-        }
+        if (j < d) put_pair4(o + j, d, keep[it], rs, g + j, split);
     }
 }
 // d must be a multiple of 4 and at most 8192; nsplit at most RL_MAX_SPLITS.
