@@ -277,7 +277,10 @@ int rollout_reset(rl_ctx* ctx);
 void rollout_destroy(rl_ctx* ctx);
 const char* rollout_last_error(void);
 
-/* ---- implementation switches and measurement hooks (not part of the method) ---- */
+/* ---- implementation switches and measurement hooks (not part of the method) ----
+ * The switches that change which kernels run (rollout_set_impl, rollout_set_precise_layers,
+ * rollout_set_fused_sampling) discard the captured decode step: call them only when the work queued on the context
+ * has finished (e.g. after rollout_check), never while a rollout_generate is still running on its stream. */
 
 /* impl 0 = plain reference kernels for every step (any dtype);
  * impl 1 = tuned gfx950 kernels where they exist (bf16 MFMA GEMMs, MFMA
