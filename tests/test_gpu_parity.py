@@ -824,3 +824,27 @@ def test_measurement_instruments():
                         torch.zeros(B, 2 * G, dtype=torch.float32, device=dev))
     assert np.array_equal(got, ref.cpu().numpy())
     ro.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("fused", [True, False], ids=["block-statistics", "logits"])
+def test_end_of_sequence_on_the_tuned_path(fused):
+    """EOS bookkeeping of both decode samplers on the tuned kernels (the fp32 EOS test above runs the plain ones): a
+    row stops at its first EOS, keeps emitting it with log-prob 0, and rows that never meet it are untouched."""
+    shape = MINI64
+    B, G = 4, 12
+    ro, Wp, Wr, mp, mr = _setup(shape, B, 40 + G)
+    ro.rollout_set_fused_sampling(fused)
+    ids, lens = synth.make_prompts(shape.vocab, B, 40, 25, 19)
+    for temp in (0.0, 1.0):
+        free_ids, _, free_lp = _generate(ro, ids, lens, G, temp, seed=8)
+        eos = int(free_ids[2, 4])
+        e_ids, e_len, e_lp = _generate(ro, ids, lens, G, temp, seed=8, eos=eos)
+        for b in range(B):
+            hits = np.where(free_ids[b] == eos)[0]
+            n = int(hits[0]) + 1 if len(hits) else G
+            assert e_len[b] == n
+            assert np.array_equal(e_ids[b, :n], free_ids[b, :n]) and np.array_equal(e_lp[b, :n], free_lp[b, :n])
+            assert np.all(e_ids[b, n:] == eos) and np.all(e_lp[b, n:] == 0.0)
+        assert e_len[2] <= 5
+    ro.close()
