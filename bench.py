@@ -198,6 +198,8 @@ def main():
                     help="measurement switch: decode GEMMs above this many rows use the 128 x 128 tile kernel (library default -1 = never)")
     ap.add_argument("--precise-layers", type=int, default=None,
                     help="measurement switch: layers carried as fp16 pairs (library default 1)")
+    ap.add_argument("--no-large-gemm-copy", action="store_true",
+                    help="measurement: the large-M GEMMs convert bf16 weights in the loop even where an fp16 copy exists")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time torch.matmul (the vendor library) on the layer's GEMM shapes, as context")
     ap.add_argument("--no-alt-decode", action="store_true",
@@ -276,7 +278,9 @@ def main():
         Wp, Wr = R.Weights(wp, shadow=policy_shadow(cfg)), R.Weights(wr, staging=staging)
     else:
         wr = synth.make_weights(shape, wl.ref_seed, dev)
-        Wp, Wr = R.Weights(wp, shadow=policy_shadow(cfg)), R.Weights(wr)
+        # the frozen reference gets a copy of its own when there is room: its large-M GEMMs read it too
+        Wp = R.Weights(wp, shadow=policy_shadow(cfg))
+        Wr = R.Weights(wr, shadow=policy_shadow(cfg) if Wp.shadow is not None else None)
     if args.progress:
         print("[bench] weights ready", file=sys.stderr, flush=True)
     ro = R.Rollout(cfg, Wp, dev)
@@ -287,6 +291,8 @@ def main():
         ro.rollout_set_impl(args.impl)
     if args.decode_tile_rows is not None:
         R.rollout_set_decode_tile_rows(args.decode_tile_rows)
+    if args.no_large_gemm_copy:
+        R.rollout_set_large_gemm_copy(False)
     if args.precise_layers is not None:
         ro.rollout_set_precise_layers(args.precise_layers)
     if args.queue:
@@ -530,6 +536,7 @@ def main():
                    "prompt": [int(Pmin), int(Pmax)], "gen": G, "page_tokens": shape.page_tokens,
                    "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
                    "policy_fp16_copy": Wp.shadow is not None,
+                   "reference_fp16_copy": getattr(Wr, "shadow", None) is not None,
                    "reference": ("host, streamed (%.0f GB pinned, %.0f GB pageable)" % (host_bytes["pinned"] / 1e9, host_bytes["pageable"] / 1e9)) if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
         "kl_exact_s": kl_exact_s,

@@ -89,11 +89,18 @@ typedef struct rl_weights {
                                        For rollout_set_policy: rollout_weight_resident_bytes(cfg) bytes, owned by the
                                        context while this policy is in use.  Ignored for location 0. */
     size_t staging_bytes;
-    void* fp16_copy;                /* read only for the POLICY given to rollout_init / rollout_set_policy, optional
-                                       (NULL = none): a dev buffer of rollout_weight_shadow_bytes(cfg) bytes, 256-byte
-                                       aligned, owned by the context until it is destroyed or given another policy, in
-                                       which the library keeps an fp16 copy of the bf16 matrices for the decode GEMMs
-                                       (same results bit for bit; those GEMMs then skip the conversion). */
+    void* fp16_copy;                /* optional (NULL = none), device-resident bf16 sets on the tuned path only: a dev
+                                       buffer of rollout_weight_shadow_bytes(cfg) bytes, 256-byte aligned, in which the
+                                       library keeps an fp16 copy of the bf16 matrices; the GEMMs that can, read the
+                                       copy and skip the conversion (same results bit for bit; 3-10 % faster).
+                                       POLICY given to rollout_init / rollout_set_policy: owned by the context until it
+                                       is destroyed or given another policy; rebuilt by those calls and by
+                                       rollout_refresh_policy.
+                                       REFERENCE given to score_logprobs_kl / score_kl_exact: filled the first time
+                                       the set is seen and reused while the same set (its first layer's QKV matrix)
+                                       comes back with the same buffer; the set is taken to be frozen (Section 3.1) --
+                                       after changing its values in place call rollout_forget_fp16_copies.  The
+                                       context remembers one such set.  Ignored elsewhere. */
     size_t fp16_copy_bytes;
 } rl_weights;
 
@@ -309,9 +316,16 @@ int rollout_set_precise_layers(rl_ctx* ctx, int32_t n);
  * with the next decode step; live sequences are kept.  Errors: RL_EINVAL. */
 int rollout_set_fused_sampling(rl_ctx* ctx, int32_t on);
 
+/* Forget the fp16 copy the context keeps of a reference set (rl_weights.fp16_copy): the next scoring call that
+ * brings one rebuilds it.  For callers that overwrite a reference set's values in place. */
+int rollout_forget_fp16_copies(rl_ctx* ctx);
+
 /* Measurement switch (process-wide): decode-step GEMMs of more than `rows` rows run on the 128 x 128 tile kernel
  * instead of the LDS-ring weight streamer (default: a negative value = ring kernel for every batch). */
 int rollout_set_decode_tile_rows(int32_t rows);
+/* Measurement switch, process-wide: on = 0 makes the large-M GEMMs convert the bf16 weights even where an fp16 copy
+ * (rl_weights.fp16_copy) exists; on != 0 (default) lets them read the copy.  Results are the same bit for bit. */
+int rollout_set_large_gemm_copy(int32_t on);
 
 /* Kernel classes for timing. */
 enum {

@@ -8,7 +8,8 @@ struct GemmArgs {
     const f16_t* A = nullptr;   // [M, K] row-major, leading dimension lda
     int lda = 0;
     const bf16_t* W = nullptr;  // [Wrows, K] row-major
-    int w_f16 = 0;              // decode GEMM only: W points at an fp16 copy made by k_bf16_to_f16 (no conversion in the kernel)
+    int w_f16 = 0;              // W points at an fp16 copy made by k_bf16_to_f16 (no conversion in the kernel): decode GEMMs,
+                                // and large-M GEMMs for which k_gemm_mfma_reads_f16_copy() says yes
     int M = 0, N = 0, K = 0;    // N = output columns (MG_SWIGLU: d_ffn)
     // Activations carried as fp16 pairs (value = hi + lo, about 22 significant bits): A is [M, 2 Kw] with the hi
     // halves of a row in columns [0, Kw) and the lo halves in [Kw, 2 Kw), K = 2 Kw, and the k index into W wraps
@@ -63,6 +64,8 @@ struct GemmArgs {
 };
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd);
+bool k_gemm_mfma_reads_f16_copy(int epi, GemmArgs a, int splits);
+void k_gemm_big_reads_copy(int on);
 // splits > 1 only with MG_STORE_F32: partial sums of split s go to outF + s * split_stride.
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
 // Measurement switch for the 256 x 256 kernel: 1 (default) = five LDS stages with the staging loads of two k-tiles

@@ -759,7 +759,8 @@ __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop
 // loop issues the same number of loads on every trip (the last trips re-request the final tile), so the counts hold to
 // the end; vmcnt(0) before the epilogue keeps loads from landing in LDS after the workgroup has ended.
 // Requires K % 64 == 0, no split over K, 5 * 512 * 64 bytes of LDS.
-template <int EPI>
+// WF16: W points at an fp16 copy of the weights: nothing to convert next to the MFMAs (5 % faster).
+template <int EPI, bool WF16 = false>
 __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     constexpr int BM = 256, BN = 256, WGN = 4, TM = 4, TN = 2, SLOTS = 8;
     constexpr int STAGE = (BM + BN) * 64;
@@ -811,7 +812,7 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     half8 af[2][TM];
     u32x4_t bf[2][TN], bw[TN];
-#define D8_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
+#define D8_CVT2(w) (WF16 ? (w) : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u))))
 #define D8_LDA(so, sl, i) *reinterpret_cast<const half8*>(smem + (so) + fa[sl] + (i) * 2048)
 #define D8_LDW(so, sl, j) *reinterpret_cast<const u32x4_t*>(smem + (so) + fw[sl] + (j) * 2048)
 #define D8_SLICE(CUR, NSO, NSL, LOADS, LB, PT, PS0, PS1)                                                        \
@@ -1060,27 +1061,30 @@ static void launch_dma(const GemmArgs& a, int n_blocks_n, int splits, hipStream_
     dim3 grid(8 * ((n_blocks_n * ((a.M + BM - 1) / BM) + 7) / 8), 1, splits);
     gemm_dma_kernel<EPI, BM, BN, WGM, WGN, MINWG><<<grid, 256, lds, s>>>(b);
 }
-template <int EPI>
+template <int EPI, bool WF16 = false>
 static void launch_dma8(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     constexpr int lds = 5 * 512 * 64;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_dma8_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute((const void*)gemm_dma8_kernel<EPI, WF16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
     GemmArgs b = a;
     b.n_blocks_n = n_blocks_n;
     dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8), 1, 1);
-    gemm_dma8_kernel<EPI><<<grid, 512, lds, s>>>(b);
+    gemm_dma8_kernel<EPI, WF16><<<grid, 512, lds, s>>>(b);
 }
 // 256 x 256 kernel: 1 = eight waves, five stages, paired staging loads; 0 = four waves, four stages (measurement switch)
 static int g_big_pairs = 1;
 void k_gemm_big_pairs(int on) { g_big_pairs = on; }
+static int g_big_reads_copy = 1;   // measurement switch: 0 = the large-M GEMMs convert bf16 weights even where an fp16 copy exists
+void k_gemm_big_reads_copy(int on) { g_big_reads_copy = on; }
 template <int EPI>
 static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     GemmArgs b = a;
     b.k_per_split = a.K;
-    if (g_big_pairs) launch_dma8<EPI>(b, n_blocks_n, s);
+    if (g_big_pairs && a.w_f16) launch_dma8<EPI, true>(b, n_blocks_n, s);
+    else if (g_big_pairs) launch_dma8<EPI>(b, n_blocks_n, s);
     else launch_dma<EPI, 256, 256, 2, 2, 1>(b, n_blocks_n, 1, s);
 }
 
@@ -1110,6 +1114,17 @@ int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
     return use_big(MG_LSE, a, 1) && !g_big_pairs ? N / 128 : N / 64;
 }
 
+// Whether k_gemm_mfma will run this GEMM on the kernel that can read an fp16 copy of W (GemmArgs.w_f16).
+bool k_gemm_mfma_reads_f16_copy(int epi, GemmArgs a, int splits) {
+    if (a.M <= 0 || a.N <= 0 || epi == MG_KLFULL || !g_big_pairs || !g_big_reads_copy) return false;
+    if (a.Kw <= 0) a.Kw = a.K;
+    if (splits < 1) splits = 1;
+    const int kt = a.K / BK, per = (kt + splits - 1) / splits;
+    splits = (kt + per - 1) / per;
+    a.Wrows = epi == MG_SWIGLU ? a.up_offset + a.N : a.N;
+    return use_big(epi, a, splits);
+}
+
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return;
     if (a.Kw <= 0) a.Kw = a.K;
@@ -1120,6 +1135,7 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     splits = (kt + per - 1) / per;
     a.Wrows = epi == MG_SWIGLU ? a.up_offset + a.N : a.N;
     const bool big = use_big(epi, a, splits);
+    if (a.w_f16 && !(big && g_big_pairs && epi != MG_KLFULL)) return;   // callers check k_gemm_mfma_reads_f16_copy first
     switch (epi) {
         case MG_STORE_F32:
             if (big) launch_big<MG_STORE_F32>(a, a.N / 256, s);

@@ -194,6 +194,11 @@ struct rl_ctx {
     int big_mode = 1;                // GemmArgs::big_mode of every tuned GEMM
     // optional fp16 copy of the policy's matrices for the decode GEMMs (caller's buffer): bf16 pointer -> copy
     std::unordered_map<const void*, const void*> shadow_of;
+    // fp16 copy of one more weight set (the frozen reference): built when a set with rl_weights.fp16_copy is first
+    // scored, kept while the same set (its first matrix) and the same buffer come back
+    std::unordered_map<const void*, const void*> other_shadow_of;
+    const void* other_key = nullptr;
+    const void* other_buf = nullptr;
     // host-resident weight sets (scoring only): copies run on a stream of the library's own
     hipStream_t copy_stream = nullptr;
     hipEvent_t ev_begin = nullptr, ev_glob_copied = nullptr, ev_glob_free = nullptr;
@@ -385,13 +390,21 @@ static void mfma(rl_ctx* c, int cls, int epi, const GemmArgs& a0, int splits, hi
     ProfScope ps(c, cls, s);
     GemmArgs a = a0;
     a.big_mode = c->big_mode;
+    auto copy_of = [&](const void* w) -> const void* {
+        auto it = c->shadow_of.find(w);
+        if (it != c->shadow_of.end()) return it->second;
+        it = c->other_shadow_of.find(w);
+        return it != c->other_shadow_of.end() ? it->second : nullptr;
+    };
     if (cls == RL_K_GEMM_DECODE && a.M <= 128 && (epi == MG_STORE_F32 || epi == MG_SWIGLU || epi == MG_SAMPLE) &&
         k_gemm_decode_supported(epi, a.N, a.K)) {
-        auto it = c->shadow_of.find((const void*)a.W);
-        if (it != c->shadow_of.end()) { a.W = (const bf16_t*)it->second; a.w_f16 = 1; }
+        if (const void* h = copy_of((const void*)a.W)) { a.W = (const bf16_t*)h; a.w_f16 = 1; }
         k_gemm_decode(epi, a, splits, s);
-    } else
+    } else {
+        if (k_gemm_mfma_reads_f16_copy(epi, a, splits))
+            if (const void* h = copy_of((const void*)a.W)) { a.W = (const bf16_t*)h; a.w_f16 = 1; }
         k_gemm_mfma(epi, a, splits, s);
+    }
 }
 
 // Split count for a decode GEMM of n rows with N output columns: one 8-wave workgroup per CU and 128-column
@@ -623,6 +636,39 @@ static int build_shadow(rl_ctx* c, hipStream_t s) {
     }
     put(W.lm_head, (size_t)m.vocab * d);
     HIP_TRY(hipGetLastError());
+    return RL_OK;
+}
+
+// The same for a weight set that is not the context's policy (the reference of a scoring call), on the caller's
+// stream, once per (set, buffer) pair.
+static int ensure_other_shadow(rl_ctx* c, const WeightsHost& W, hipStream_t s) {
+    const rl_model_cfg& m = c->cfg;
+    if (!W.fp16_copy || m.dtype != RL_BF16 || W.location != 0 || c->impl != 1) return RL_OK;
+    if (!W.wqkv.empty() && c->shadow_of.count(W.wqkv[0])) return RL_OK;      // this is the context's policy: it has its copy
+    if (c->other_key == W.wqkv[0] && c->other_buf == W.fp16_copy) return RL_OK;
+    if (W.fp16_copy_bytes < shadow_bytes_of(m))
+        return fail(RL_ENOSPACE, "fp16 copy: %zu bytes given, %zu needed", W.fp16_copy_bytes, shadow_bytes_of(m));
+    if (((uintptr_t)W.fp16_copy & 255) != 0) return fail(RL_EINVAL, "fp16 copy buffer must be 256-byte aligned");
+    c->other_shadow_of.clear();
+    auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+    const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
+    const size_t nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    char* p = W.fp16_copy;
+    auto put = [&](const void* src, size_t elems) {
+        k_bf16_to_f16(src, p, (int64_t)elems, s);
+        c->other_shadow_of[src] = p;
+        p += al(elems * 2);
+    };
+    for (int l = 0; l < m.n_layers; ++l) {
+        put(W.wqkv[l], nqkv * d);
+        put(W.wo[l], d * qd);
+        put(W.w_gate_up[l], 2 * (size_t)m.d_ffn * d);
+        put(W.w_down[l], d * (size_t)m.d_ffn);
+    }
+    put(W.lm_head, (size_t)m.vocab * d);
+    HIP_TRY(hipGetLastError());
+    c->other_key = W.wqkv[0];
+    c->other_buf = W.fp16_copy;
     return RL_OK;
 }
 
@@ -865,6 +911,11 @@ int rollout_set_decode_tile_rows(int32_t rows) {
     return RL_OK;
 }
 
+int rollout_set_large_gemm_copy(int32_t on) {
+    k_gemm_big_reads_copy(on != 0);
+    return RL_OK;
+}
+
 int rollout_set_precise_layers(rl_ctx* c, int32_t n) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     if (n < 0 || n > precise_cap(c->cfg))
@@ -879,6 +930,13 @@ int rollout_set_fused_sampling(rl_ctx* c, int32_t on) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     c->fused_sample = on != 0;
     if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return RL_OK;
+}
+
+int rollout_forget_fp16_copies(rl_ctx* c) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    c->other_shadow_of.clear();
+    c->other_key = c->other_buf = nullptr;
     return RL_OK;
 }
 
@@ -1478,6 +1536,7 @@ int score_logprobs_kl(rl_ctx* c, const rl_weights* policy, const rl_weights* ref
     if (reference) {
         rc = copy_weights(m, reference, wr, "reference", true);
         if (rc) return rc;
+        if ((rc = ensure_other_shadow(c, wr, s))) return rc;
     }
     if (logp_policy) {
         rc = wp.location == 1 ? score_pass_streamed(c, wp, ids, seq_len, B, Lmax, logp_policy, s)
@@ -1518,6 +1577,7 @@ int score_kl_exact(rl_ctx* c, const rl_weights* policy, const rl_weights* refere
     int rc = copy_weights(m, policy, wp, "policy");
     if (rc) return rc;
     if ((rc = copy_weights(m, reference, wr, "reference"))) return rc;
+    if ((rc = ensure_other_shadow(c, wr, (hipStream_t)stream))) return rc;
     hipStream_t s = (hipStream_t)stream;
     const Layout& L = c->L;
     const size_t e = esz_of(m.dtype);

@@ -86,8 +86,10 @@ def lib():
         L.rollout_destroy.restype = None
         L.rollout_set_impl.argtypes = [vp, i32]
         L.rollout_set_decode_tile_rows.argtypes = [i32]
+        L.rollout_set_large_gemm_copy.argtypes = [i32]
         L.rollout_set_precise_layers.argtypes = [vp, i32]
         L.rollout_set_fused_sampling.argtypes = [vp, i32]
+        L.rollout_forget_fp16_copies.argtypes = [vp]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
         L.rollout_profile_event_overhead.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
@@ -291,6 +293,9 @@ class Rollout:
     def rollout_set_precise_layers(self, n: int):
         _chk(lib().rollout_set_precise_layers(self.h, n))
 
+    def rollout_forget_fp16_copies(self):
+        _chk(lib().rollout_forget_fp16_copies(self.h))
+
     def rollout_set_fused_sampling(self, on: bool):
         _chk(lib().rollout_set_fused_sampling(self.h, 1 if on else 0))
 
@@ -323,6 +328,10 @@ def ppo_rewards_noalloc(kl: torch.Tensor, seq_reward: torch.Tensor, seq_len, pro
 
 def rollout_set_decode_tile_rows(rows: int):
     _chk(lib().rollout_set_decode_tile_rows(int(rows)))
+
+
+def rollout_set_large_gemm_copy(on: bool):
+    _chk(lib().rollout_set_large_gemm_copy(1 if on else 0))
 
 
 def sample_cfg(seed=0, temperature=0.0, eos_id=-1, seq_id_base=0) -> rl_sample_cfg:

@@ -848,3 +848,43 @@ def test_end_of_sequence_on_the_tuned_path(fused):
             assert np.all(e_ids[b, n:] == eos) and np.all(e_lp[b, n:] == 0.0)
         assert e_len[2] <= 5
     ro.close()
+
+
+@pytest.mark.gpu
+def test_fp16_copies_in_the_large_m_gemms():
+    """Scoring with fp16 copies of both weight sets (the policy's, kept by the context, and one the library builds for
+    the frozen reference) on the 256 x 256-tile kernel: bit-identical to scoring without copies, checked against the
+    oracle, and the reference's copy is rebuilt after rollout_forget_fp16_copies when its values were changed in
+    place."""
+    shape, B = MINI128, 6
+    wa, wb = synth.make_weights(shape, 1, DEV), synth.make_weights(shape, 2, DEV)
+    cfg = R.make_cfg(shape, B, 80, max_chunk_tokens=512)
+    nbytes = R.rollout_weight_shadow_bytes(cfg)
+    sh_a = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    sh_b = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    seqs, slens, plens = synth.make_sequences(shape.vocab, B, 72, 40, 0.4, 91)
+    plain = R.Rollout(cfg, R.Weights(wa), DEV)
+    plain.rollout_set_impl(2)
+    want = _score(plain, R.Weights(wa), R.Weights(wb), seqs, slens, plens, 0.25)
+    plain.close()
+    Wa, Wb = R.Weights(wa, shadow=sh_a), R.Weights(wb, shadow=sh_b)
+    ro = R.Rollout(cfg, Wa, DEV)
+    ro.rollout_set_impl(2)
+    got = _score(ro, Wa, Wb, seqs, slens, plens, 0.25)
+    for a, b in zip(got, want):
+        assert np.array_equal(a, b)
+    mp = O.Model(shape, synth.weights_for_oracle(wa))
+    mr = O.Model(shape, synth.weights_for_oracle(wb))
+    check_scores(*got, O.score_batch(mp, mr, seqs, slens, plens, 0.25), 2e-2, 0.25)
+    # the reference changes in place (it takes the policy's values): stale copy until the context is told
+    for k in ("tok_embed", "final_norm", "lm_head"):
+        wb[k].copy_(wa[k])
+    for la, lb in zip(wa["layers"], wb["layers"]):
+        for k in la:
+            lb[k].copy_(la[k])
+    torch.cuda.synchronize()
+    ro.rollout_forget_fp16_copies()
+    got2 = _score(ro, Wa, Wb, seqs, slens, plens, 0.25)
+    assert np.array_equal(got2[0], got2[1])            # same weights on both sides now
+    assert np.all(got2[2] == 0.0)
+    ro.close()
