@@ -819,13 +819,15 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     _Pragma("unroll") for (int q = 0; q < SLOTS; ++q) {                                                         \
         const int j_ = q / TM, i_ = q % TM;                                                                     \
         acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
-        if (q < 2) bw[q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);                                                     \
-        else if (q < 6) af[1 - (CUR)][q >= 2 && q < 6 ? q - 2 : 0] = D8_LDA(NSO, NSL, q - 2);                   \
+        if (q < 2) {                                                                                            \
+            if (WF16) bf[1 - (CUR)][q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);   /* already fp16: straight into place */ \
+            else bw[q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);                                                       \
+        } else if (q < 6) af[1 - (CUR)][q >= 2 && q < 6 ? q - 2 : 0] = D8_LDA(NSO, NSL, q - 2);                 \
         if (q >= 6 && q - 6 < (LOADS)) {                                                                        \
             D8_LOAD(PS0, PT, (LB) + q - 6)                                                                      \
             D8_LOAD(PS1, (PT) + 1, (LB) + q - 6)                                                                \
         }                                                                                                       \
-        if (q >= 4) {                                                                                           \
+        if (q >= 4 && !WF16) {                                                                                  \
             const int c_ = q >= 4 ? q - 4 : 0, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                                \
             bf[1 - (CUR)][jj_][h_] = D8_CVT2(bw[jj_][h_]);                                                      \
             bf[1 - (CUR)][jj_][h_ + 1] = D8_CVT2(bw[jj_][h_ + 1]);                                              \
