@@ -469,6 +469,18 @@ def main():
                    "decode_hbm_frac": dbytes / d2 / 1e9 / HBM_PEAK_GBPS}
         ro2.close()
         del ro2
+        if not args.no_score and not args.no_large_gemm_copy:
+            # and the scoring pass with the large-M GEMMs converting the bf16 weights themselves
+            R.rollout_set_large_gemm_copy(False)
+            assemble()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            ro.score_logprobs_kl(Wp, Wr, full, seq_len, plen, 0.003, *outs)
+            torch.cuda.synchronize()
+            s2 = time.perf_counter() - t1
+            R.rollout_set_large_gemm_copy(True)
+            no_copy["score_s"] = s2
+            no_copy["score_mfma_frac"] = sflops / s2 / 1e12 / MFMA_PEAK_TFLOPS
 
     # ---- rooflines per kernel class: algorithmic work of the class in one step / time of its launches in one step
     def cls_ms(name):            # time of the class in one step: mean timed launch x launches per step
