@@ -751,20 +751,29 @@ __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop
 // request per line reaches the L2.  A pair needs two free stages; with five stages the pair (p+4, p+5) is issued from
 // the second slice of tile p (whose stage the barrier before it has released) to the end of tile p+1, spread over
 // those three slices: bunched, the loads queue up in the vector memory path and hold back the MFMAs behind them.
-// Per wave and k-tile: 2 + 2 staging loads; per k-slice 8 MFMAs, 6 fragment reads (W 0-1 after MFMAs 0-1, A 0-3 after
-// MFMAs 2-5), 4 half-fragment conversions (after MFMAs 4-7), and of the pair's 4 loads per tile 2, 1, 1 in the three
-// slices that may issue them (after MFMAs 6, 7).  Loads complete in issue order, so the waits are counts: inside an
-// even k-tile p everything but the youngest 8 loads (pair p+2, p+3) has landed, i.e. tile p+1; inside an odd tile p+1
-// everything but the youngest 7 (tile p+3's last load and the 6 of pair p+4, p+5 issued so far), i.e. tile p+2.  The
-// loop issues the same number of loads on every trip (the last trips re-request the final tile), so the counts hold to
-// the end; vmcnt(0) before the epilogue keeps loads from landing in LDS after the workgroup has ended.
+// The matrix cores run 16x16x32 MFMAs, the shape that draws less power per flop (a register-only probe sustains 5 %
+// more on it than on 32x32x16).  Per wave and k-tile: 2 + 2 staging loads, 8 A fragments (16 rows x 32 k each: one
+// 16-byte read per lane) and 4 W fragments, 32 MFMAs in two slices of 16: slice 0 on rows 0-63 of the wave, slice 1 on
+// rows 64-127.  During slice 0 the A fragments of rows 64-127 are read (same stage); during slice 1, behind the
+// barrier that publishes the next k-tile, its W fragments and its A fragments of rows 0-63; of the pair's 4 loads per
+// tile 2, 1, 1 go out in the three slices that may issue them.  Loads complete in issue order, so the waits are
+// counts: inside an even k-tile p everything but the youngest 8 loads (pair p+2, p+3) has landed, i.e. tile p+1;
+// inside an odd tile p+1 everything but the youngest 7 (tile p+3's last load and the 6 of pair p+4, p+5 issued so
+// far), i.e. tile p+2.  The loop issues the same number of loads on every trip (the last trips re-request the final
+// tile), so the counts hold to the end; vmcnt(0) after the loop keeps loads from landing in LDS later.
+// WF16: W points at an fp16 copy of the weights and its fragments go from LDS straight into the MFMAs; otherwise W is
+// bf16 and each fragment is converted (exactly) next to the MFMAs of slice 1, which costs 5-10 % of the loop.  Both
+// forms feed the MFMAs the same values in the same order: their results are identical bit for bit.
+// The accumulators come out in the 16 x 16 layout (lane: column lane % 16, rows 4 * (lane / 16) + 0..3); before the
+// epilogues, which are written for the 32 x 32 layout, each wave passes them through its own 18 KB of the then idle
+// LDS, 64 rows at a time.
 // Requires K % 64 == 0, no split over K, 5 * 512 * 64 bytes of LDS.
-// WF16: W points at an fp16 copy of the weights: nothing to convert next to the MFMAs (5 % faster).
-template <int EPI, bool WF16 = false>
+template <int EPI, bool WF16>
 __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
-    constexpr int BM = 256, BN = 256, WGN = 4, TM = 4, TN = 2, SLOTS = 8;
+    constexpr int BM = 256, BN = 256, WGN = 4, TM = 4, TN = 2;
     constexpr int STAGE = (BM + BN) * 64;
-    constexpr int LPT = 4;                            // staging loads per wave per k-tile: A rows, A rows, W rows, W rows
+    constexpr int LPT = 4;
+    typedef float floatx4_t __attribute__((ext_vector_type(4)));
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // [5 stages][A 256 x 64 B | W 256 x 64 B]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -787,8 +796,7 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
     const char* Ag = reinterpret_cast<const char*>(a.A);
     const char* Wg = reinterpret_cast<const char*>(a.W);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-    // load l of k-tile kt (clamped to the last one: the count of loads per trip never changes) into stage st
-#define D8_LOAD(st, kt, l)                                                                                      \
+#define X8_LOAD(st, kt, l)                                                                                      \
     {                                                                                                           \
         const int kt_ = min((kt), nk - 1);                                                                      \
         const unsigned sa_ = lds_base + (st) * STAGE + ((l) >= 2 ? BM * 64 : 0) + (((l) & 1) * 8 + wave) * 1024; \
@@ -796,90 +804,114 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                            \
                      :: "s"(sa_), "v"(g_off[l]), "s"(g_) : "memory");                                           \
     }
-    int fa[2], fw[2];
+    // fragment offsets inside a stage: row lane % 16 of a 16-row block, logical 16-byte chunk lane / 16, swizzled
+    const int fr = lane & 15;
+    const int fko = ((lane >> 4) ^ ((fr >> 2) & 3)) * 16;
+    const int fa = (wm * 128 + fr) * 64 + fko;                 // + i * 1024 for the i-th 16-row block of the wave
+    const int fw = BM * 64 + (wn * 64 + fr) * 64 + fko;        // + j * 1024
+    floatx4_t acc[8][4];
 #pragma unroll
-    for (int sl = 0; sl < 2; ++sl) {
-        const int ko = ((sl * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16;
-        fa[sl] = (wm * TM * 32 + (lane & 31)) * 64 + ko;
-        fw[sl] = BM * 64 + (wn * TN * 32 + (lane & 31)) * 64 + ko;
-    }
-    floatx16 acc[TM][TN];
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    half8 af[2][TM];
-    u32x4_t bf[2][TN], bw[TN];
-#define D8_CVT2(w) (WF16 ? (w) : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u))))
-#define D8_LDA(so, sl, i) *reinterpret_cast<const half8*>(smem + (so) + fa[sl] + (i) * 2048)
-#define D8_LDW(so, sl, j) *reinterpret_cast<const u32x4_t*>(smem + (so) + fw[sl] + (j) * 2048)
-#define D8_SLICE(CUR, NSO, NSL, LOADS, LB, PT, PS0, PS1)                                                        \
-    _Pragma("unroll") for (int q = 0; q < SLOTS; ++q) {                                                         \
-        const int j_ = q / TM, i_ = q % TM;                                                                     \
-        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[CUR][i_], __builtin_bit_cast(half8, bf[CUR][j_]), acc[i_][j_], 0, 0, 0); \
-        if (q < 2) {                                                                                            \
-            if (WF16) bf[1 - (CUR)][q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);   /* already fp16: straight into place */ \
-            else bw[q < 2 ? q : 0] = D8_LDW(NSO, NSL, q);                                                       \
-        } else if (q < 6) af[1 - (CUR)][q >= 2 && q < 6 ? q - 2 : 0] = D8_LDA(NSO, NSL, q - 2);                 \
-        if (q >= 6 && q - 6 < (LOADS)) {                                                                        \
-            D8_LOAD(PS0, PT, (LB) + q - 6)                                                                      \
-            D8_LOAD(PS1, (PT) + 1, (LB) + q - 6)                                                                \
+        for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    half8 af[2][4];
+    u32x4_t wf[2][4], bw[WF16 ? 1 : 4];   // W fragments as they go into the MFMAs; bf16 fragments waiting for their conversion
+#define X8_CVT2(w) __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(__uint_as_float((w) << 16), __uint_as_float((w) & 0xffff0000u)))
+#define X8_LDA(so, i) *reinterpret_cast<const half8*>(smem + (so) + fa + (i) * 1024)
+#define X8_LDW(so, j) *reinterpret_cast<const u32x4_t*>(smem + (so) + fw + (j) * 1024)
+    // One slice: 16 MFMAs on A set AS (rows AS * 64 ..) and W set WS.  NR fragment reads spread behind the first
+    // MFMAs (slice 0: the wave's rows 64-127 of stage NSO into A set 1; slice 1: W of stage NSO into W set 1 - WS, then
+    // rows 0-63 into A set 0); LOADS pairs of staging loads behind MFMAs 12, 14.
+#define X8_SLICE(AS, WS, NSO, LOADS, LB, PT, PS0, PS1)                                                          \
+    _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                                            \
+        const int j_ = q / 4, i_ = q % 4;                                                                       \
+        acc[(AS) * 4 + i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[AS][i_], __builtin_bit_cast(half8, wf[WS][j_]), acc[(AS) * 4 + i_][j_], 0, 0, 0); \
+        if ((AS) == 0) {                                                                                        \
+            if (q < 8 && (q & 1) == 0) af[1][q / 2 < 4 ? q / 2 : 0] = X8_LDA(NSO, 4 + q / 2);                   \
+        } else {                                                                                                \
+            if (q < 4) {                                                                                        \
+                if (WF16) wf[1 - (WS)][q < 4 ? q : 0] = X8_LDW(NSO, q);                                         \
+                else bw[!WF16 && q < 4 ? q : 0] = X8_LDW(NSO, q);                                               \
+            } else if (q < 12 && (q & 1) == 0) af[0][q >= 4 && q < 12 ? (q - 4) / 2 : 0] = X8_LDA(NSO, (q - 4) / 2); \
+            if (!WF16 && q >= 8) {           /* half a bf16 fragment -> fp16 per slot */                        \
+                const int c_ = q >= 8 ? q - 8 : 0, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                            \
+                wf[1 - (WS)][jj_][h_] = X8_CVT2(bw[WF16 ? 0 : jj_][h_]);                                        \
+                wf[1 - (WS)][jj_][h_ + 1] = X8_CVT2(bw[WF16 ? 0 : jj_][h_ + 1]);                                \
+            }                                                                                                   \
         }                                                                                                       \
-        if (q >= 4 && !WF16) {                                                                                  \
-            const int c_ = q >= 4 ? q - 4 : 0, jj_ = c_ >> 1, h_ = (c_ & 1) * 2;                                \
-            bf[1 - (CUR)][jj_][h_] = D8_CVT2(bw[jj_][h_]);                                                      \
-            bf[1 - (CUR)][jj_][h_ + 1] = D8_CVT2(bw[jj_][h_ + 1]);                                              \
+        if (q >= 12 && (q & 1) == 0 && (q - 12) / 2 < (LOADS)) {                                                \
+            X8_LOAD(PS0, PT, (LB) + (q - 12) / 2)                                                               \
+            X8_LOAD(PS1, (PT) + 1, (LB) + (q - 12) / 2)                                                         \
         }                                                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                                                      \
     }
     int s0 = 0, s1 = 1, s2 = 2, s3 = 3, s4 = 4;
 #pragma unroll
-    for (int l = 0; l < LPT; ++l) { D8_LOAD(0, 0, l) D8_LOAD(1, 1, l) }
+    for (int l = 0; l < LPT; ++l) { X8_LOAD(0, 0, l) X8_LOAD(1, 1, l) }
 #pragma unroll
-    for (int l = 0; l < LPT; ++l) { D8_LOAD(2, 2, l) D8_LOAD(3, 3, l) }
-    // MG_QKV: positions and cache pages of this wave's 128 rows, one row per lane and half, fetched while the first
-    // k-tiles arrive (ordinary loads issued after the staging loads above: they complete after those, so the wait
-    // below, which counts the youngest outstanding loads, still covers tile 0 -- and usually tiles 1-3 too)
+    for (int l = 0; l < LPT; ++l) { X8_LOAD(2, 2, l) X8_LOAD(3, 3, l) }
     QkvRowMeta meta;
-    if constexpr (EPI == MG_QKV) meta = qkv_row_meta(a, m0 + wm * TM * 32, lane);
-    __builtin_amdgcn_s_waitcnt(dma_waitcnt(EPI == MG_QKV ? 0 : 2 * LPT + 1, 15));   // tile 0 landed (its last load is the one before the pair's last)
+    if constexpr (EPI == MG_QKV) meta = qkv_row_meta(a, m0 + wm * 128, lane);
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(EPI == MG_QKV ? 0 : 2 * LPT + 1, 15));
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = D8_LDA(0, 0, i);
+    for (int i = 0; i < 4; ++i) af[0][i] = X8_LDA(0, i);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        bw[j] = D8_LDW(0, 0, j);
+    for (int j = 0; j < 4; ++j) {
+        const u32x4_t w_ = X8_LDW(0, j);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bf[0][j][c] = D8_CVT2(bw[j][c]);
+        for (int c = 0; c < 4; ++c) wf[0][j][c] = WF16 ? w_[c] : X8_CVT2(w_[c]);
     }
     for (int kt = 0; kt < nk; kt += 2) {
         const int o0 = s0 * STAGE, o1 = s1 * STAGE, o2 = s2 * STAGE;
-        D8_SLICE(0, o0, 1, 0, 0, 0, 0, 0)
+        // even k-tile kt (W set 0): rows 0-63, barrier (tile kt+1 complete, stage of tile kt released after this
+        // slice's reads), rows 64-127 with the first loads of pair (kt+4, kt+5)
+        X8_SLICE(0, 0, o0, 0, 0, 0, 0, 0)
         __builtin_amdgcn_s_waitcnt(dma_waitcnt(2 * LPT, 0));
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-        D8_SLICE(1, o1, 0, 2, 0, kt + 4, s4, s0)
-        D8_SLICE(0, o1, 1, 1, 2, kt + 4, s4, s0)
+        X8_SLICE(1, 0, o1, 2, 0, kt + 4, s4, s0)
+        // odd k-tile kt+1 (W set 1)
+        X8_SLICE(0, 1, o1, 1, 2, kt + 4, s4, s0)
         __builtin_amdgcn_s_waitcnt(dma_waitcnt(6 + 1, 0));
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-        D8_SLICE(1, o2, 0, 1, 3, kt + 4, s4, s0)
+        X8_SLICE(1, 1, o2, 1, 3, kt + 4, s4, s0)
         const int t0 = s0, t1 = s1;
         s0 = s2; s1 = s3; s2 = s4; s3 = t0; s4 = t1;
     }
-    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after the workgroup ends
-#undef D8_LOAD
-#undef D8_CVT2
-#undef D8_LDA
-#undef D8_LDW
-#undef D8_SLICE
+    __builtin_amdgcn_s_waitcnt(dma_waitcnt(0, 15));   // nothing may land in LDS after this point
+#undef X8_LOAD
+#undef X8_CVT2
+#undef X8_LDA
+#undef X8_LDW
+#undef X8_SLICE
+    __syncthreads();                                   // every wave is done with the stages: LDS is free
+    // 16 x 16 layout -> 32 x 32 layout through this wave's own [64 rows][64 columns] fp32 patch (row stride 72 floats)
+    float* patch = reinterpret_cast<float*>(smem) + wave * (64 * 72);
     const QkvRowMeta* pre = EPI == MG_QKV ? &meta : nullptr;
-    mg_epilogue<EPI, BN, TN, WGN>(acc[0], a, m0 + wm * TM * 32, nb, wn, 0, lane, pre);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[1], a, m0 + wm * TM * 32 + 32, nb, wn, 0, lane, pre);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[2], a, m0 + wm * TM * 32 + 64, nb, wn, 0, lane, pre);
-    mg_epilogue<EPI, BN, TN, WGN>(acc[3], a, m0 + wm * TM * 32 + 96, nb, wn, 0, lane, pre);
+    const int lg = lane >> 5, lrow = lane & 31;
+    // written out per half: with the largest epilogue the unroller gives up on a loop over the halves, and the
+    // accumulators must stay statically indexed
+#define D8_HALF(hf)                                                                                             \
+    {                                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                       \
+                _Pragma("unroll") for (int t = 0; t < 4; ++t)                                                   \
+                    patch[(i * 16 + 4 * (lane >> 4) + t) * 72 + j * 16 + (lane & 15)] = acc[(hf) * 4 + i][j][t]; \
+        __builtin_amdgcn_wave_barrier();      /* LDS accesses of a wave complete in order */                    \
+        floatx16 band[2][TN];                                                                                   \
+        _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                           \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                      \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                  \
+                    band[b][j][r] = patch[(b * 32 + 8 * (r >> 2) + 4 * lg + (r & 3)) * 72 + j * 32 + lrow];     \
+        __builtin_amdgcn_wave_barrier();                                                                        \
+        mg_epilogue<EPI, BN, TN, WGN>(band[0], a, m0 + wm * 128 + (hf) * 64, nb, wn, 0, lane, pre);             \
+        mg_epilogue<EPI, BN, TN, WGN>(band[1], a, m0 + wm * 128 + (hf) * 64 + 32, nb, wn, 0, lane, pre);        \
+    }
+    D8_HALF(0)
+    D8_HALF(1)
+#undef D8_HALF
 }
 
 template <int EPI, int BM, int BN, int WGM, int WGN, int MINWG>
