@@ -765,7 +765,7 @@ __device__ __forceinline__ void dma_mainloop(const GemmArgs& a, const f16_t* Aop
 // bf16 and each fragment is converted (exactly) next to the MFMAs of slice 1, which costs 5-10 % of the loop.  Both
 // forms feed the MFMAs the same values in the same order: their results are identical bit for bit.
 // The accumulators come out in the 16 x 16 layout (lane: column lane % 16, rows 4 * (lane / 16) + 0..3); before the
-// epilogues, which are written for the 32 x 32 layout, each wave passes them through its own 18 KB of the then idle
+// epilogues, which are written for the 32 x 32 layout, each wave passes them through its own 17 KB of the then idle
 // LDS, 64 rows at a time.
 // Requires K % 64 == 0, no split over K, 5 * 512 * 64 bytes of LDS.
 template <int EPI, bool WF16>
@@ -887,8 +887,10 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
 #undef X8_LDW
 #undef X8_SLICE
     __syncthreads();                                   // every wave is done with the stages: LDS is free
-    // 16 x 16 layout -> 32 x 32 layout through this wave's own [64 rows][64 columns] fp32 patch (row stride 72 floats)
-    float* patch = reinterpret_cast<float*>(smem) + wave * (64 * 72);
+    // 16 x 16 layout -> 32 x 32 layout through this wave's own [64 rows][64 columns] fp32 patch; row stride 68 floats:
+    // four rows further on is 16 banks further on, so neither the writes (lanes 16 apart: 4 rows apart) nor the reads
+    // (lanes 32 apart: 4 rows apart, 32 consecutive columns per half-wave) collide
+    float* patch = reinterpret_cast<float*>(smem) + wave * (64 * 68);
     const QkvRowMeta* pre = EPI == MG_QKV ? &meta : nullptr;
     const int lg = lane >> 5, lrow = lane & 31;
     // written out per half: with the largest epilogue the unroller gives up on a loop over the halves, and the
@@ -898,13 +900,13 @@ __global__ __launch_bounds__(512, 1) void gemm_dma8_kernel(GemmArgs a) {
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
             _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                       \
                 _Pragma("unroll") for (int t = 0; t < 4; ++t)                                                   \
-                    patch[(i * 16 + 4 * (lane >> 4) + t) * 72 + j * 16 + (lane & 15)] = acc[(hf) * 4 + i][j][t]; \
+                    patch[(i * 16 + 4 * (lane >> 4) + t) * 68 + j * 16 + (lane & 15)] = acc[(hf) * 4 + i][j][t]; \
         __builtin_amdgcn_wave_barrier();      /* LDS accesses of a wave complete in order */                    \
         floatx16 band[2][TN];                                                                                   \
         _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                           \
             _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                      \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                  \
-                    band[b][j][r] = patch[(b * 32 + 8 * (r >> 2) + 4 * lg + (r & 3)) * 72 + j * 32 + lrow];     \
+                    band[b][j][r] = patch[(b * 32 + 8 * (r >> 2) + 4 * lg + (r & 3)) * 68 + j * 32 + lrow];     \
         __builtin_amdgcn_wave_barrier();                                                                        \
         mg_epilogue<EPI, BN, TN, WGN>(band[0], a, m0 + wm * 128 + (hf) * 64, nb, wn, 0, lane, pre);             \
         mg_epilogue<EPI, BN, TN, WGN>(band[1], a, m0 + wm * 128 + (hf) * 64 + 32, nb, wn, 0, lane, pre);        \
