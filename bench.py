@@ -200,6 +200,8 @@ def main():
                     help="measurement switch: layers carried as fp16 pairs (library default 1)")
     ap.add_argument("--no-large-gemm-copy", action="store_true",
                     help="measurement: the large-M GEMMs convert bf16 weights in the loop even where an fp16 copy exists")
+    ap.add_argument("--separate-qkv-consumer", action="store_true",
+                    help="measurement: a separate kernel sums, rotates and appends the decode QKV partial sums (default: decode attention does)")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time torch.matmul (the vendor library) on the layer's GEMM shapes, as context")
     ap.add_argument("--no-alt-decode", action="store_true",
@@ -295,6 +297,8 @@ def main():
         R.rollout_set_large_gemm_copy(False)
     if args.precise_layers is not None:
         ro.rollout_set_precise_layers(args.precise_layers)
+    if args.separate_qkv_consumer:
+        ro.rollout_set_fused_qkv_consumer(False)
     if args.queue:
         return queue_bench(args, wl, shape, ro, B, Pmax, Pmin, dev)
     ids_np, plen = synth.make_prompts(shape.vocab, B, Pmax, Pmin, wl.prompt_seed)
@@ -549,6 +553,7 @@ def main():
                    "temperature": wl.temperature, "reduced": reduced, "impl": args.impl,
                    "policy_fp16_copy": Wp.shadow is not None,
                    "reference_fp16_copy": getattr(Wr, "shadow", None) is not None,
+                   "attention_consumes_qkv_partials": not args.separate_qkv_consumer,
                    "reference": ("host, streamed (%.0f GB pinned, %.0f GB pageable)" % (host_bytes["pinned"] / 1e9, host_bytes["pageable"] / 1e9)) if args.ref_host else "device"},
         "generate_s": gen_s, "prefill_s": prefill_s, "decode_s": decode_s, "score_s": score_s,
         "kl_exact_s": kl_exact_s,

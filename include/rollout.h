@@ -286,7 +286,7 @@ const char* rollout_last_error(void);
 
 /* ---- implementation switches and measurement hooks (not part of the method) ----
  * The switches that change which kernels run (rollout_set_impl, rollout_set_precise_layers,
- * rollout_set_fused_sampling) discard the captured decode step: call them only when the work queued on the context
+ * rollout_set_fused_sampling, rollout_set_fused_qkv_consumer) discard the captured decode step: call them only when the work queued on the context
  * has finished (e.g. after rollout_check), never while a rollout_generate is still running on its stream. */
 
 /* impl 0 = plain reference kernels for every step (any dtype);
@@ -315,6 +315,16 @@ int rollout_set_precise_layers(rl_ctx* ctx, int32_t n);
  * uniform falls within rounding of a CDF step.  The caller must have waited for work on the context.  Takes effect
  * with the next decode step; live sequences are kept.  Errors: RL_EINVAL. */
 int rollout_set_fused_sampling(rl_ctx* ctx, int32_t on);
+
+/* Tuned bf16 path only.  on != 0 (default): in a decode step (Section 3.2's generation stage) the attention kernel of
+ * a plain layer is itself the consumer of the QKV projection's split-K partial sums: each workgroup adds up the
+ * partial rows of its own query heads and of its kv head's new key and value (in split order), applies the rotary
+ * embedding, appends key and value to the cache page and attends with them.  on = 0: a separate kernel does that
+ * first and attention reads its results.  The arithmetic is the same either way; fp16-pair layers
+ * (rollout_set_precise_layers) and models with more than 6 query heads per kv head at head_dim 128 always use the
+ * separate kernel.  The caller must have waited for work on the context.
+ * Takes effect with the next decode step; live sequences are kept.  Errors: RL_EINVAL. */
+int rollout_set_fused_qkv_consumer(rl_ctx* ctx, int32_t on);
 
 /* Forget the fp16 copy the context keeps of a reference set (rl_weights.fp16_copy): the next scoring call that
  * brings one rebuilds it.  For callers that overwrite a reference set's values in place. */

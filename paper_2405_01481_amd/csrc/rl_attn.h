@@ -16,7 +16,18 @@ struct DecodeAttnArgs {
     // split = 1: q and out rows are fp16 pairs, [Hq * hd hi | Hq * hd lo]; the cache's lo planes of K and V are
     // in layer `layer_lo` of the pool
     int split = 0, layer_lo = 0;
+    // qkv_part != nullptr (plain layers only, Hq / Hkv <= 8): q is not read; the kernel itself sums the QKV
+    // projection's split-K partial rows [qkv_nsplit][B, (Hq + 2 Hkv) hd] (split stride in floats), rotates q and k
+    // with rope[pos][hd/2] = (cos, sin), and appends k and v of the new token to the cache through pool_w
+    const float* qkv_part = nullptr;
+    int qkv_nsplit = 0;
+    int64_t qkv_split_stride = 0;
+    const float2* rope = nullptr;
+    f16_t* pool_w = nullptr;
 };
+// Whether k_attn_decode can take the QKV partial sums itself (qkv_part) for these head counts; it launches nothing
+// if asked to for others, or for a pair layer.
+bool k_attn_decode_consumes_qkv(int Hq, int Hkv, int hd);
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s);
 
 // Causal attention over a packed token list.  Sequences start at rows that are multiples of 32

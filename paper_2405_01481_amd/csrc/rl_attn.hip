@@ -28,18 +28,57 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // a.layer_lo, the lo halves of a query row after its hi halves).  Scores take the three leading terms
 // k_hi q_hi + k_lo q_hi + k_hi q_lo, the probabilities are split the same way for the second contraction, and
 // the output leaves as a pair: the layer then carries about 22 significant bits instead of 11.
-template <int HD, int PT, bool SP>
+// FU: the kernel is also the consumer of the QKV projection's split-K partial sums.  While its first page is on the
+// way, the workgroup sums the partials of its own G query heads and of its kv head's new key and value (in split
+// order), rotates q and k, keeps them in LDS as fp16, and -- split 0 only, after its loop -- appends k and v to the
+// cache page.
+// Queries are then read from LDS, and the wave that holds the page of the new token takes that token's key row and
+// value column from LDS instead of from the page, so nothing depends on when the appended values become visible.
+template <int HD, int PT, bool SP, bool FU>
 __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttnArgs a) {
+    static_assert(!(SP && FU), "the pair layers keep the separate consumer kernel");
     static_assert(PT == 16, "page tile is one 16-row MFMA block");
     constexpr int KS = HD / 32;    // k-steps of the 16x16x32 S^T MFMAs
     constexpr int DB = HD / 16;    // 16-dim blocks of O^T
     __shared__ float sm_m[4][16], sm_l[4][16];
     __shared__ float sm_o[4][8][HD + 4];
+    __shared__ __attribute__((aligned(16))) f16_t sm_q[FU ? 8 : 1][HD], sm_k[HD], sm_v[HD];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, g4 = lane >> 4;
     const int b = blockIdx.x, g = blockIdx.y, split = blockIdx.z;
     const int G = a.Hq / a.Hkv;
+    // FU: the partial sums of this thread's (at most two) column pairs are requested before anything else -- they
+    // depend on nothing but the row -- so they travel together with the position, the page index and the first page.
+    // Pair i = (head hh = i / (hd/2), j = i % (hd/2)) covers columns j and j + hd/2 of head hh; hh < G a query head,
+    // hh == G the key, hh == G + 1 the value.
+    constexpr int NE = 6;                           // splits requested up front (the rest, if any, later)
+    constexpr int HALF = HD / 2;
+    float pe0[FU ? 2 : 1][NE], pe1[FU ? 2 : 1][NE];
+    const float* prow[2] = {nullptr, nullptr};
+    if (FU) {
+        const int width = (a.Hq + 2 * a.Hkv) * HD;
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            // no branches here (a thread without a second pair re-reads the last pair, a split past the last one
+            // re-reads the last split): conditional loads would be waited for one by one
+            const int i = min((int)threadIdx.x + sl * 256, (G + 2) * HALF - 1);
+            const int hh = i / HALF, j = i % HALF;
+            prow[sl] = a.qkv_part + (int64_t)b * width + (hh < G ? g * G + hh : hh == G ? a.Hq + g : a.Hq + a.Hkv + g) * HD + j;
+#pragma unroll
+            for (int sp = 0; sp < NE; ++sp) {
+                const int64_t o = min(sp, a.qkv_nsplit - 1) * a.qkv_split_stride;
+                pe0[sl][sp] = prow[sl][o];
+                pe1[sl][sp] = prow[sl][o + HALF];
+            }
+        }
+    }
     const int ctx = a.tok_pos[b] + 1;
+    float2 cs_new[FU ? 2 : 1];                      // (cos, sin) of the new token's position for this thread's pairs
+    if (FU) {
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+            cs_new[sl] = a.rope[(int64_t)max(ctx - 1, 0) * HALF + min((int)threadIdx.x + sl * 256, (G + 2) * HALF - 1) % HALF];
+    }
     const int npages = (ctx + PT - 1) / PT;
     const int chunk = (npages + (int)gridDim.z - 1) / (int)gridDim.z;
     const int pbeg = split * chunk, pend = min(npages, pbeg + chunk);
@@ -52,14 +91,16 @@ __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttn
 
     // Q^T operand: lane (head col, k-group g4) holds q[head][s*32 + g4*8 .. +8)
     half8 qf[KS], ql[SP ? KS : 1];
+    if (!FU) {
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        const f16_t* qp = a.q + (int64_t)b * qrow + (g * G + col) * HD + s * 32 + g4 * 8;
-        if (col < G) qf[s] = *reinterpret_cast<const half8*>(qp);
-        else qf[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (SP) {
-            if (col < G) ql[s] = *reinterpret_cast<const half8*>(qp + a.Hq * HD);
-            else ql[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int s = 0; s < KS; ++s) {
+            const f16_t* qp = a.q + (int64_t)b * qrow + (g * G + col) * HD + s * 32 + g4 * 8;
+            if (col < G) qf[s] = *reinterpret_cast<const half8*>(qp);
+            else qf[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (SP) {
+                if (col < G) ql[s] = *reinterpret_cast<const half8*>(qp + a.Hq * HD);
+                else ql[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
         }
     }
     const float scale = a.scale * LOG2E;       // softmax in base 2
@@ -88,11 +129,66 @@ __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttn
         const int64_t pg = bt[p];
         AD_FETCH(pg)
     }
+    const int p_new = (ctx - 1) / PT, st_new = (ctx - 1) % PT;   // page and slot of the new token
+    if (FU) {
+        if (ctx > 0) {   // uniform over the workgroup; a parked row has no keys and no query
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                const int i = threadIdx.x + sl * 256;
+                if (i < (G + 2) * HALF) {
+                    const int hh = i / HALF, j = i % HALF;
+                    const float2 cs = cs_new[sl];
+                    float x0 = 0.f, x1 = 0.f;       // summed in split order
+#pragma unroll
+                    for (int sp = 0; sp < NE; ++sp) {
+                        x0 = sp < a.qkv_nsplit ? x0 + pe0[sl][sp] : x0;
+                        x1 = sp < a.qkv_nsplit ? x1 + pe1[sl][sp] : x1;
+                    }
+                    for (int sp = NE; sp < a.qkv_nsplit; ++sp) {
+                        x0 += prow[sl][sp * a.qkv_split_stride];
+                        x1 += prow[sl][sp * a.qkv_split_stride + HALF];
+                    }
+                    if (hh <= G) {
+                        const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
+                        x0 = r0; x1 = r1;
+                    }
+                    const f16_t h0 = (f16_t)x0, h1 = (f16_t)x1;
+                    if (hh < G) {
+                        sm_q[hh][j] = h0; sm_q[hh][j + HALF] = h1;
+                    } else if (hh == G) {
+                        sm_k[j] = h0; sm_k[j + HALF] = h1;
+                    } else {
+                        sm_v[j] = h0; sm_v[j + HALF] = h1;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            if (col < G && ctx > 0) qf[s] = *reinterpret_cast<const half8*>(&sm_q[col][s * 32 + g4 * 8]);
+            else qf[s] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
     for (; p < pend; p += 4) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) { kf[s] = kn[s]; if (SP) kfl[s] = knl[s]; }
 #pragma unroll
         for (int d = 0; d < DB; ++d) { vf[d] = vn[d]; if (SP) vfl[d] = vnl[d]; }
+        if (FU && p == p_new) {   // the new token's key row and value column come from LDS
+            if (col == st_new) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s) kf[s] = *reinterpret_cast<const half8*>(&sm_k[s * 32 + g4 * 8]);
+            }
+            if (g4 == (st_new >> 2)) {
+#pragma unroll
+                for (int d = 0; d < DB; ++d) {
+                    const f16_t v = sm_v[d * 16 + col];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vf[d][i] = i == (st_new & 3) ? v : vf[d][i];
+                }
+            }
+        }
         {
             const int pn = min(p + 4, pend - 1);          // the last iteration re-reads a valid page, unused
             const int64_t pg = bt[pn];
@@ -141,6 +237,15 @@ __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttn
         }
     }
 #undef AD_FETCH
+    // FU: the new token's key and value go to the cache only now -- stores count towards the same in-order
+    // completion counter as loads, so stores issued before the loop would hold back every page load behind them
+    if (FU && split == 0 && ctx > 0) {
+        const int64_t page = bt[p_new];
+        for (int i = threadIdx.x; i < HD; i += 256) {
+            a.pool_w[a.geo.k_off(a.layer, page, g, st_new, i)] = sm_k[i];
+            a.pool_w[a.geo.v_off(a.layer, page, g, st_new, i)] = sm_v[i];
+        }
+    }
     // wave totals: l over the four key groups
     l_run += __shfl_xor(l_run, 16, RL_WAVE);
     l_run += __shfl_xor(l_run, 32, RL_WAVE);
@@ -206,15 +311,26 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, con
     if (split) op[Hq * HD] = (f16_t)(r - (float)hi);
 }
 
+// The consumer form of the kernel gives each of its 256 threads at most two (column, column + hd/2) pairs of the
+// group's G query heads, key and value, and keeps the queries of at most 8 heads in LDS.
+bool k_attn_decode_consumes_qkv(int Hq, int Hkv, int hd) {
+    const int G = Hq / Hkv;
+    return (hd == 64 || hd == 128) && G <= 8 && (G + 2) * (hd / 2) <= 512;
+}
+
 void k_attn_decode(const DecodeAttnArgs& a, int B, int nsplit, hipStream_t s) {
     if (B <= 0) return;
+    if (a.qkv_part && (a.split || !k_attn_decode_consumes_qkv(a.Hq, a.Hkv, a.geo.hd))) return;   // callers check first
     dim3 grid(B, a.Hkv, nsplit);
     if (a.split) {
-        if (a.geo.hd == 128) attn_decode_kernel<128, 16, true><<<grid, 256, 0, s>>>(a);
-        else attn_decode_kernel<64, 16, true><<<grid, 256, 0, s>>>(a);
+        if (a.geo.hd == 128) attn_decode_kernel<128, 16, true, false><<<grid, 256, 0, s>>>(a);
+        else attn_decode_kernel<64, 16, true, false><<<grid, 256, 0, s>>>(a);
+    } else if (a.qkv_part) {
+        if (a.geo.hd == 128) attn_decode_kernel<128, 16, false, true><<<grid, 256, 0, s>>>(a);
+        else attn_decode_kernel<64, 16, false, true><<<grid, 256, 0, s>>>(a);
     } else {
-        if (a.geo.hd == 128) attn_decode_kernel<128, 16, false><<<grid, 256, 0, s>>>(a);
-        else attn_decode_kernel<64, 16, false><<<grid, 256, 0, s>>>(a);
+        if (a.geo.hd == 128) attn_decode_kernel<128, 16, false, false><<<grid, 256, 0, s>>>(a);
+        else attn_decode_kernel<64, 16, false, false><<<grid, 256, 0, s>>>(a);
     }
     if (nsplit > 1) {
         if (a.geo.hd == 128) attn_merge_kernel<128><<<B * a.Hq, 128, 0, s>>>(a.part_o, a.part_ml, a.out, nsplit, a.Hq, a.split);

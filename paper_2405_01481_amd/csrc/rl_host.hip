@@ -232,6 +232,7 @@ struct rl_ctx {
     hipGraphExec_t gexec = nullptr;
     bool use_graph = true;
     bool fused_sample = true;        // decode LM head emits block statistics instead of logits (tuned path)
+    bool fused_qkv = true;           // decode attention sums, rotates and appends the QKV projection's partial rows itself
     // captured steps that may still be running when the policy is swapped without waiting: destroyed once the
     // event recorded behind their last launch has completed
     struct Retired { hipGraphExec_t g; hipEvent_t ev; };
@@ -318,7 +319,10 @@ static void gemm(rl_ctx* c, int cls, int epi, const void* A, int lda, const void
 // paged = attention reads the paged cache (decode); else the chunk's own contiguous K/V.
 // write_pages = append K/V of these tokens to the paged cache.
 // Returns true when h already holds RMSNorm(x; final_norm) (the tuned decode path fuses it).
-static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblocks, hipStream_t s) {
+// qkv_part (decode, tuned kernels, plain layers): the QKV projection's split-K partial rows, which the attention
+// kernel then consumes itself instead of reading rotated queries and an already appended cache.
+static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblocks, hipStream_t s,
+                      const float* qkv_part = nullptr, int qkv_nsplit = 0, int64_t qkv_split_stride = 0) {
     const rl_model_cfg& m = c->cfg;
     const Layout& L = c->L;
     ProfScope ps(c, paged ? RL_K_ATTN_DECODE : RL_K_ATTN_PREFILL, s);
@@ -330,6 +334,10 @@ static void attention(rl_ctx* c, int l, int n, bool paged, int max_ctx, int nblo
         a.part_ml = c->at<float>(L.attn_ml); a.mpps = L.mpps; a.layer = l; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads;
         a.scale = 1.0f / sqrtf((float)m.head_dim); a.geo = c->geo;
         a.split = sp; a.layer_lo = m.n_layers + l;
+        if (qkv_part) {
+            a.qkv_part = qkv_part; a.qkv_nsplit = qkv_nsplit; a.qkv_split_stride = qkv_split_stride;
+            a.rope = c->at<float2>(L.rope); a.pool_w = (f16_t*)c->pool;
+        }
         // the split count is a property of the context (most sequences, longest sequence), never of the live batch:
         // a row's reduction order, and with it its bits, must not depend on its batch-mates
         int nsplit = (1024 + m.max_batch * m.n_kv_heads - 1) / (m.max_batch * m.n_kv_heads);
@@ -455,9 +463,14 @@ static bool run_layers_fast(rl_ctx* c, const WeightsHost& W, int n, bool paged, 
             g.outF = part; g.ldc = L.nqkv; g.split_stride = (int64_t)n * L.nqkv;
             int ks = decode_splits(n, L.nqkv, g.K);
             mfma(c, gcls, MG_STORE_F32, g, ks, s);
-            k_rope_append_split(1, part, ks, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
-                                m.n_q_heads, s, sp, m.n_layers + l);
-            attention(c, l, n, true, max_ctx, 0, s);
+            // plain layers on the tuned kernels: attention is the consumer of the partial sums (a decode row's cache
+            // slot is its row index, which is what that kernel assumes)
+            const bool fuse = c->fused_qkv && c->impl == 1 && !sp &&
+                              k_attn_decode_consumes_qkv(m.n_q_heads, m.n_kv_heads, m.head_dim);
+            if (!fuse)
+                k_rope_append_split(1, part, ks, g.split_stride, n, tpos, tslot, rope, q, c->pool, l, c->geo, bt, L.mpps,
+                                    m.n_q_heads, s, sp, m.n_layers + l);
+            attention(c, l, n, true, max_ctx, 0, s, fuse ? part : nullptr, ks, g.split_stride);
             g = GemmArgs();
             g.M = n; g.A = att; pair_in(g, qd, sp); g.W = (const bf16_t*)W.wo[l]; g.N = m.d_model;
             g.outF = part; g.ldc = m.d_model; g.split_stride = (int64_t)n * m.d_model;
@@ -929,6 +942,13 @@ int rollout_set_precise_layers(rl_ctx* c, int32_t n) {
 int rollout_set_fused_sampling(rl_ctx* c, int32_t on) {
     if (!c) return fail(RL_EINVAL, "ctx is NULL");
     c->fused_sample = on != 0;
+    if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    return RL_OK;
+}
+
+int rollout_set_fused_qkv_consumer(rl_ctx* c, int32_t on) {
+    if (!c) return fail(RL_EINVAL, "ctx is NULL");
+    c->fused_qkv = on != 0;
     if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
     return RL_OK;
 }

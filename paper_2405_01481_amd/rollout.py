@@ -89,6 +89,7 @@ def lib():
         L.rollout_set_large_gemm_copy.argtypes = [i32]
         L.rollout_set_precise_layers.argtypes = [vp, i32]
         L.rollout_set_fused_sampling.argtypes = [vp, i32]
+        L.rollout_set_fused_qkv_consumer.argtypes = [vp, i32]
         L.rollout_forget_fp16_copies.argtypes = [vp]
         L.rollout_profile_enable.argtypes = [vp, i32, i32]
         L.rollout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -298,6 +299,9 @@ class Rollout:
 
     def rollout_set_fused_sampling(self, on: bool):
         _chk(lib().rollout_set_fused_sampling(self.h, 1 if on else 0))
+
+    def rollout_set_fused_qkv_consumer(self, on: bool):
+        _chk(lib().rollout_set_fused_qkv_consumer(self.h, 1 if on else 0))
 
     def rollout_profile_enable(self, kernel_class: int, every: int):
         _chk(lib().rollout_profile_enable(self.h, kernel_class, int(every)))

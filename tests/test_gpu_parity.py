@@ -790,6 +790,33 @@ def test_sampling_from_block_statistics(shape):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("shape,max_seq,plen", [(MINI64, 80, 48), (MINI128, 640, 600)], ids=["one-split", "kv-splits"])
+def test_attention_consumes_qkv_partials(shape, max_seq, plen):
+    """Decode attention as the consumer of the QKV projection's split-K partial sums (the default on the tuned path:
+    it sums, rotates and appends the new token's q, k, v itself) against the oracle along its own trajectory, and
+    against the same context with the separate consumer kernel: the same arithmetic, so the same tokens and
+    log-probs.  Ragged prompts put the new token at every slot of a page; the long case splits a sequence's keys
+    over several workgroups, each of which forms q, k, v for itself."""
+    B, G = 5, 20
+    ro, Wp, Wr, mp, mr = _setup(shape, B, max_seq)
+    ids, lens = synth.make_prompts(shape.vocab, B, plen, plen // 3, 31)
+    prompts = [ids[b, :lens[b]] for b in range(B)]
+    lt, cd = _tol(shape)
+    for temp, seed in ((1.0, 11), (0.0, 12)):
+        ro.rollout_set_fused_qkv_consumer(True)
+        f_ids, f_len, f_lp = _generate(ro, ids, lens, G, temp, seed=seed, base=2)
+        verify_rollout(mp, prompts, f_ids, f_lp, temp, seed, 2, cd, lt, rows=[0, B - 1] if plen > 100 else None)
+        torch.cuda.synchronize()
+        ro.rollout_set_fused_qkv_consumer(False)
+        s_ids, s_len, s_lp = _generate(ro, ids, lens, G, temp, seed=seed, base=2)
+        torch.cuda.synchronize()
+        assert np.array_equal(f_ids, s_ids) and np.array_equal(f_len, s_len)
+        assert np.array_equal(f_lp, s_lp)
+    ro.rollout_set_fused_qkv_consumer(True)
+    ro.close()
+
+
+@pytest.mark.gpu
 def test_measurement_instruments():
     """The two instruments bench.py leans on: the cost of an empty event pair (microseconds, not zero, not
     milliseconds) and the matrix cores' sustained rate (zeros at least as fast as random operands, both below the
