@@ -359,9 +359,10 @@ int rollout_profile_read(rl_ctx* ctx, int32_t kernel_class, double* total_ms, in
  * overhead_ms: host. */
 int rollout_profile_event_overhead(rl_ctx* ctx, int32_t pairs, double* overhead_ms, void* stream);
 /* Instrument for reading the MFMA roofline: the rate (TFLOP/s) at which the matrix cores of this GPU sustain
- * back-to-back fp16 32x32x16 MFMAs on operands held in registers -- no memory traffic, one workgroup of four waves per
- * compute unit, about 0.2 s -- on random operands (random_operands != 0) or on zeros.  Power management makes the two
- * differ by a third; a GEMM on real data cannot run faster than the first figure.  Uses the context's workspace
+ * back-to-back fp16 16x16x32 MFMAs (the shape the large-M GEMMs run) on operands held in registers -- no memory
+ * traffic, one workgroup of four waves per compute unit, about 0.2 s -- on random operands (random_operands != 0) or
+ * on zeros.  Power management makes the two differ by a third; a GEMM on real data cannot run faster than the first
+ * figure.  Uses the context's workspace
  * between calls (live sequences are not touched); synchronises `stream`.  tflops: host.
  * Errors: RL_EINVAL, RL_ENOSPACE, RL_EHIP. */
 int rollout_probe_mfma_rate(rl_ctx* ctx, int32_t random_operands, double* tflops, void* stream);

@@ -1185,39 +1185,38 @@ void k_lse_reduce(const float2* part, int nparts, const float* z_tgt, int nrows,
 }
 
 // ---------------------------------------------------------------- instrument: sustained rate of the matrix cores
-// Nothing but v_mfma_f32_32x32x16_f16 on operands held in registers (16 independent accumulator tiles per wave, four
-// waves per CU, no memory traffic inside the loop): what the matrix cores sustain under the chip's power management on
-// operands of the given kind.  Random operands (uniform in [-1, 1)) draw far more power than zeros, and the clock
-// follows.  The accumulators are written out once at the end so that the loop cannot be removed.
+// Nothing but v_mfma_f32_16x16x32_f16 -- the shape the large-M GEMMs run -- on operands held in registers (64
+// independent accumulator tiles per wave, four waves per CU, no memory traffic inside the loop): what the matrix cores
+// sustain under the chip's power management on operands of the given kind.  Random operands (uniform in [-1, 1)) draw
+// far more power than zeros, and the clock follows.  The accumulators are written out once at the end so that the loop
+// cannot be removed.
 __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(const f16_t* in, float* out, int iters) {
     typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-    typedef float floatx16_t __attribute__((ext_vector_type(16)));
+    typedef float floatx4_t __attribute__((ext_vector_type(4)));
     const int l = threadIdx.x;
-    half8_t a[4], b[4];
+    half8_t a[8], b[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 8; ++i) {
         a[i] = *reinterpret_cast<const half8_t*>(in + (size_t)(l + 256 * i) * 8);
-        b[i] = *reinterpret_cast<const half8_t*>(in + (size_t)(l + 256 * (4 + i)) * 8);
+        b[i] = *reinterpret_cast<const half8_t*>(in + (size_t)(l + 256 * (8 + i)) * 8);
     }
-    floatx16_t acc[4][4];
+    floatx4_t acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < 8; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         asm volatile("" : "+v"(a[0]), "+v"(b[0]));
     }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s += acc[i][j][3] + acc[i][j][11];
+        for (int j = 0; j < 8; ++j) s += acc[i][j][1] + acc[i][j][2];
     out[blockIdx.x * 256 + l] = s;
 }
 __global__ void mfma_rate_fill_kernel(f16_t* p, int n, int random) {
@@ -1227,10 +1226,10 @@ __global__ void mfma_rate_fill_kernel(f16_t* p, int n, int random) {
     h ^= h >> 13; h *= 0x5bd1e995u; h ^= h >> 15;
     p[i] = random ? (f16_t)(((h & 0xffff) / 65536.0f) * 2.f - 1.f) : (f16_t)0.f;
 }
-// scratch: at least 64 KB + n_wg * 1 KB of device memory.  One launch of n_wg workgroups x iters x 16 MFMAs per wave.
+// scratch: at least 64 KB + n_wg * 1 KB of device memory.  One launch of n_wg workgroups x iters x 64 MFMAs per wave.
 void k_mfma_rate(void* scratch, int n_wg, int iters, int random, hipStream_t s) {
     f16_t* in = reinterpret_cast<f16_t*>(scratch);
     float* out = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + 65536);
-    mfma_rate_fill_kernel<<<(8 * 256 * 8 + 255) / 256, 256, 0, s>>>(in, 8 * 256 * 8, random);
+    mfma_rate_fill_kernel<<<(16 * 256 * 8 + 255) / 256, 256, 0, s>>>(in, 16 * 256 * 8, random);
     mfma_rate_kernel<<<n_wg, 256, 0, s>>>(in, out, iters);
 }

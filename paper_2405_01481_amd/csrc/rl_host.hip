@@ -1803,7 +1803,7 @@ int rollout_probe_mfma_rate(rl_ctx* c, int32_t random_operands, double* tflops, 
     hipEvent_t a = nullptr, b = nullptr;
     HIP_TRY(hipEventCreate(&a));
     if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(RL_EHIP, "hipEventCreate failed"); }
-    const int iters = 200000;                      // about 0.1 s: long enough for the clock to settle
+    const int iters = 100000;                      // about 0.1 s: long enough for the clock to settle
     k_mfma_rate(scratch, n_cu, iters, random_operands != 0, s);   // warm
     int rc = RL_OK;
     float ms = 0.f;
@@ -1814,7 +1814,7 @@ int rollout_probe_mfma_rate(rl_ctx* c, int32_t random_operands, double* tflops, 
         rc = fail(RL_EHIP, "event timing failed");
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
-    if (rc == RL_OK) *tflops = (double)n_cu * 4 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12;
+    if (rc == RL_OK) *tflops = (double)n_cu * 4 * iters * 64 * 16384.0 / (ms * 1e-3) / 1e12;   // 64 MFMAs of 16 x 16 x 32 per wave and trip
     return rc;
 }
 
