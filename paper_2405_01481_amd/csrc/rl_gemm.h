@@ -68,9 +68,6 @@ bool k_gemm_mfma_reads_f16_copy(int epi, GemmArgs a, int splits);
 void k_gemm_big_reads_copy(int on);
 // splits > 1 only with MG_STORE_F32: partial sums of split s go to outF + s * split_stride.
 void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s);
-// Measurement switch for the 256 x 256 kernel: 1 (default) = five LDS stages with the staging loads of two k-tiles
-// issued together (whole cache lines per request pair), 0 = four stages, one k-tile per request group.
-void k_gemm_big_pairs(int on);
 int k_gemm_mfma_splits_used(int K, int splits);
 // Number of column groups per row that an MG_LSE launch of this shape writes (at most N / 64).
 int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode);

@@ -1,17 +1,21 @@
 // MFMA GEMMs for gfx950:  C[M,N] = A[M,K] (fp16, row-major) * W[N,K]^T (bf16, row-major).
 //
 // Weights stay bf16 in HBM and are converted to fp16 on their way to the MFMA operand registers
-// (exact for every weight of normal fp16 magnitude); the contraction runs on
-// v_mfma_f32_32x32x16_f16 with fp32 accumulation.  Three kernels share one set of epilogues:
+// (exact for every weight of normal fp16 magnitude) -- or are read from an fp16 copy where a weight set
+// has one; the contraction runs on fp16 MFMAs (v_mfma_f32_16x16x32_f16 in the large-M kernel,
+// v_mfma_f32_32x32x16_f16 in the others) with fp32 accumulation.  Four kernels share one set of epilogues:
 //   * gemm_mfma_kernel: 128 x 128 tiles staged through registers, two workgroups per CU -- small and
 //     medium M, and split-K for decode batches above 128 rows;
-//   * gemm_dma_kernel:  256 x 256 tiles staged by global -> LDS loads -- the large-M GEMMs of prefill
-//     and scoring once the grid fills the chip;
+//   * gemm_dma8_kernel: 256 x 256 tiles, eight waves, operands staged by global -> LDS loads -- the
+//     large-M GEMMs of prefill and scoring once the grid fills the chip;
+//   * gemm_dma_kernel:  128 x 128 tiles staged the same way, two GEMMs on one tile -- the exact
+//     full-vocabulary KL, which needs the policy's and the reference's logits of a tile together;
 //   * gemm_ring_kernel: the weight-streaming GEMMs of a decode step (M <= 128 rows), split over K so
 //     that all 256 CUs stream a slice of W; partial sums go to a [split][M][N] fp32 buffer and are
 //     reduced, in a fixed order, by the consumer kernel.
 // Epilogues: fp32 store / split-K partial, fp16 store, residual add, SwiGLU, RoPE + q/k/v split for
-// the QKV projection, and log-sum-exp + target gather for the scoring LM head.
+// the QKV projection, log-sum-exp + target gather for the scoring LM head, and per-block sampling
+// statistics for the decode LM head.
 #include "rl_common.h"
 #include "rl_gemm.h"
 
@@ -1110,18 +1114,14 @@ static void launch_dma8(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     dim3 grid(8 * ((n_blocks_n * ((a.M + 255) / 256) + 7) / 8), 1, 1);
     gemm_dma8_kernel<EPI, WF16><<<grid, 512, lds, s>>>(b);
 }
-// 256 x 256 kernel: 1 = eight waves, five stages, paired staging loads; 0 = four waves, four stages (measurement switch)
-static int g_big_pairs = 1;
-void k_gemm_big_pairs(int on) { g_big_pairs = on; }
 static int g_big_reads_copy = 1;   // measurement switch: 0 = the large-M GEMMs convert bf16 weights even where an fp16 copy exists
 void k_gemm_big_reads_copy(int on) { g_big_reads_copy = on; }
 template <int EPI>
 static void launch_big(const GemmArgs& a, int n_blocks_n, hipStream_t s) {
     GemmArgs b = a;
     b.k_per_split = a.K;
-    if (g_big_pairs && a.w_f16) launch_dma8<EPI, true>(b, n_blocks_n, s);
-    else if (g_big_pairs) launch_dma8<EPI>(b, n_blocks_n, s);
-    else launch_dma<EPI, 256, 256, 2, 2, 1>(b, n_blocks_n, 1, s);
+    if (a.w_f16) launch_dma8<EPI, true>(b, n_blocks_n, s);
+    else launch_dma8<EPI>(b, n_blocks_n, s);
 }
 
 bool k_gemm_mfma_supported(int epi, int N, int K, int hd) {
@@ -1143,16 +1143,14 @@ static bool use_big(int epi, const GemmArgs& a, int splits) {
 }
 
 int k_gemm_mfma_lse_parts(int M, int N, int K, int big_mode) {
-    GemmArgs a;
-    a.M = M; a.N = N; a.K = K; a.Kw = K; a.lda = K; a.Wrows = N; a.big_mode = big_mode;
-    // column groups are as wide as a wave's share of the tile: 128 columns on the four-wave 256 x 256 kernels, 64 on the
-    // eight-wave one and on the 128 x 128 kernel
-    return use_big(MG_LSE, a, 1) && !g_big_pairs ? N / 128 : N / 64;
+    // column groups are as wide as a wave's share of the tile: 64 columns on the 256 x 256 and on the 128 x 128 kernel
+    (void)M; (void)K; (void)big_mode;
+    return N / 64;
 }
 
 // Whether k_gemm_mfma will run this GEMM on the kernel that can read an fp16 copy of W (GemmArgs.w_f16).
 bool k_gemm_mfma_reads_f16_copy(int epi, GemmArgs a, int splits) {
-    if (a.M <= 0 || a.N <= 0 || epi == MG_KLFULL || !g_big_pairs || !g_big_reads_copy) return false;
+    if (a.M <= 0 || a.N <= 0 || epi == MG_KLFULL || !g_big_reads_copy) return false;
     if (a.Kw <= 0) a.Kw = a.K;
     if (splits < 1) splits = 1;
     const int kt = a.K / BK, per = (kt + splits - 1) / splits;
@@ -1171,7 +1169,7 @@ void k_gemm_mfma(int epi, GemmArgs a, int splits, hipStream_t s) {
     splits = (kt + per - 1) / per;
     a.Wrows = epi == MG_SWIGLU ? a.up_offset + a.N : a.N;
     const bool big = use_big(epi, a, splits);
-    if (a.w_f16 && !(big && g_big_pairs && epi != MG_KLFULL)) return;   // callers check k_gemm_mfma_reads_f16_copy first
+    if (a.w_f16 && !(big && epi != MG_KLFULL)) return;   // callers check k_gemm_mfma_reads_f16_copy first
     switch (epi) {
         case MG_STORE_F32:
             if (big) launch_big<MG_STORE_F32>(a, a.N / 256, s);
