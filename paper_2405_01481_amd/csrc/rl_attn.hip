@@ -19,6 +19,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #define LOG2E 1.4426950408889634f
 
+// 2^x as the hardware instruction alone.  The library's exp2f wraps it in a rescaling for results in the denormal
+// range (six instructions per value); softmax weights that small are zero for every purpose here.  2^-inf = 0.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ------------------------------------------------------------------ decode: one new query per sequence
 // Workgroup = (sequence b, kv head g, split).  Its 4 waves take page pairs round-robin
 // from the split's page range; query heads g*G .. g*G+G-1 are the MFMA columns 0..G-1
@@ -214,12 +218,12 @@ __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttn
         mx = fmaxf(mx, __shfl_xor(mx, 16, RL_WAVE));
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
         const float m_new = fmaxf(m_run, mx);       // finite: the first key of page p is always valid
-        const float alpha = exp2f(m_run - m_new);
+        const float alpha = fast_exp2(m_run - m_new);
         half4 pf0, pl0;
         float ps = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float e0 = exp2f(s0[i] - m_new);
+            float e0 = fast_exp2(s0[i] - m_new);
             ps += e0;
             pf0[i] = (f16_t)e0;
             if (SP) pl0[i] = (f16_t)(e0 - (float)pf0[i]);
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(256, SP ? 2 : 4) void attn_decode_kernel(DecodeAttn
         if (mt > -INFINITY) {
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                float wt = exp2f(sm_m[w][hh] - mt);
+                float wt = fast_exp2(sm_m[w][hh] - mt);
                 o += wt * sm_o[w][hh][d];
                 l += wt * sm_l[w][hh];
             }
@@ -300,7 +304,7 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(const float* part_o, con
     for (int s = 0; s < nsplit; ++s) {
         float m = part_ml[(head * nsplit + s) * 2];
         if (m == -INFINITY) continue;
-        float wt = exp2f(m - mt);
+        float wt = fast_exp2(m - mt);
         o += wt * part_o[(head * nsplit + s) * HD + d];
         l += wt * part_ml[(head * nsplit + s) * 2 + 1];
     }
@@ -472,13 +476,13 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(PrefillAttnArgs a) {
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, stt[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, RL_WAVE));
         const float m_new = fmaxf(m_run, mx);        // finite: key kb*32 <= qi for every kb <= qb
-        const float alpha = exp2f((m_run - m_new) * scale);
+        const float alpha = fast_exp2((m_run - m_new) * scale);
         const float nms = -m_new * scale;
         half8 pf[2], pl[SP ? 2 : 1];
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float e = exp2f(fmaf(stt[r], scale, nms));
+            float e = fast_exp2(fmaf(stt[r], scale, nms));
             ps += e;
             const f16_t eh = (f16_t)e;
             pf[r >> 3][r & 7] = eh;
