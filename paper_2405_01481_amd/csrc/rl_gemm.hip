@@ -106,6 +106,12 @@ __device__ __forceinline__ float row32_sum(float v) {
     return v + __shfl_xor(v, 16, RL_WAVE);
 }
 
+// SiLU(g) * u.  The quotient is g times a reciprocal (1 ulp) instead of a division (ten instructions): the result is
+// rounded to fp16 right after.  Very negative g: exp overflows to +inf, its reciprocal is 0, the product -0.
+__device__ __forceinline__ float swiglu_act(float g, float u) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
+
 // Epilogue shared by the tile kernels, for one 32-row band of a wave's accumulators: acc[j][r] of the
 // wave in tile-column position wn is C(row, col) with
 //   row = m_base + 8*(r/4) + 4*(lane/32) + r%4,   col(tile-local) = wn*TN*32 + j*32 + lane%32
@@ -346,6 +352,27 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
         }
         return;
     }
+    if constexpr (EPI == MG_SWIGLU || EPI == MG_STORE_F16) {
+        // A band that lies wholly inside the matrix (the rule on the large-M path) and leaves as plain fp16: no
+        // per-element bounds checks or branches, one row pointer per register row.  Same values as the general path.
+        constexpr int OUT_COLS = EPI == MG_SWIGLU ? TN * 16 : TN * 32;       // output columns of this wave
+        const int n_first = (EPI == MG_SWIGLU ? nb * (BN / 2) : nb * BN) + wn * OUT_COLS;
+        if (m_base + 32 <= a.M && n_first + OUT_COLS <= a.N && !a.split_out) {   // wave-uniform
+            f16_t* o = a.outH + (int64_t)(m_base + 4 * lg) * a.ldc + n_first + lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                f16_t* orow = o + (int64_t)(8 * (r >> 2) + (r & 3)) * a.ldc;
+                if constexpr (EPI == MG_SWIGLU) {
+#pragma unroll
+                    for (int j = 0; j < TN; j += 2) orow[(j / 2) * 32] = (f16_t)swiglu_act(acc[j][r], acc[j + 1][r]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) orow[j * 32] = (f16_t)acc[j][r];
+                }
+            }
+            return;
+        }
+    }
     {
         // the targets of the lane's 16 rows, fetched before the first store (a load behind a store that may alias it
         // waits for the store)
@@ -374,8 +401,7 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
 #pragma unroll
                 for (int j = 0; j < TN; j += 2) {
                     int n = nb * (BN / 2) + (wn * TN + j) / 2 * 32 + lrow;
-                    float g = acc[j][r], u = acc[j + 1][r];
-                    const float act = g / (1.0f + __expf(-g)) * u;
+                    const float act = swiglu_act(acc[j][r], acc[j + 1][r]);
                     if (n < a.N) {
                         if (a.split_out) {
                             f16_t hi, lo;
