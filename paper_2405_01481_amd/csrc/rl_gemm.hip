@@ -98,6 +98,41 @@ __device__ __forceinline__ float row32_max(float v) {
     v = fmaxf(v, dpp_move<0x140>(v));   // row_mirror
     return fmaxf(v, __shfl_xor(v, 16, RL_WAVE));
 }
+// The same two reductions for the 16 register rows of a band at once, level by level: the 16 chains are independent,
+// so consecutive instructions never wait on one another (a data-parallel-primitive move needs two idle slots after
+// the instruction that wrote its source).  Same operations per row, in the same order, as row32_max / row32_sum.
+template <int CTRL>
+__device__ __forceinline__ void rows16_max_step(float (&v)[16]) {
+    float t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = dpp_move<CTRL>(v[r]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], t[r]);
+}
+template <int CTRL>
+__device__ __forceinline__ void rows16_sum_step(float (&v)[16]) {
+    float t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = dpp_move<CTRL>(v[r]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] += t[r];
+}
+__device__ __forceinline__ void rows16_max(float (&v)[16]) {
+    rows16_max_step<0xB1>(v); rows16_max_step<0x4E>(v); rows16_max_step<0x141>(v); rows16_max_step<0x140>(v);
+    float t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = __shfl_xor(v[r], 16, RL_WAVE);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], t[r]);
+}
+__device__ __forceinline__ void rows16_sum(float (&v)[16]) {
+    rows16_sum_step<0xB1>(v); rows16_sum_step<0x4E>(v); rows16_sum_step<0x141>(v); rows16_sum_step<0x140>(v);
+    float t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = __shfl_xor(v[r], 16, RL_WAVE);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] += t[r];
+}
 __device__ __forceinline__ float row32_sum(float v) {
     v += dpp_move<0xB1>(v);
     v += dpp_move<0x4E>(v);
@@ -369,6 +404,44 @@ __device__ __forceinline__ void mg_epilogue(floatx16 (&acc)[TN], const GemmArgs&
 #pragma unroll
                     for (int j = 0; j < TN; ++j) orow[j * 32] = (f16_t)acc[j][r];
                 }
+            }
+            return;
+        }
+    }
+    if constexpr (EPI == MG_LSE) {
+        // A band that lies wholly inside the matrix: the 16 rows' reductions run level by level, then the stores.  Same
+        // values as the row-by-row form below.
+        if (m_base + 32 <= a.M) {                               // wave-uniform
+            int tg[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tg[r] = a.tgt[m_base + 8 * (r >> 2) + 4 * lg + (r & 3)];
+            float mx[16], se[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                mx[r] = acc[0][r];
+#pragma unroll
+                for (int j = 1; j < TN; ++j) mx[r] = fmaxf(mx[r], acc[j][r]);
+            }
+            rows16_max(mx);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                se[r] = 0.f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) se[r] += __expf(acc[j][r] - mx[r]);
+            }
+            rows16_sum(se);
+            const int nparts = (a.N / BN) * WGN;
+            const int c_first = nb * BN + wn * TN * 32 + lrow;   // this lane's column of acc[0]
+            float2* part = a.lse_part + (int64_t)(m_base + 4 * lg) * nparts + nb * WGN + wn;
+            float* zt = a.z_tgt + m_base + 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ro = 8 * (r >> 2) + (r & 3);
+                if (lrow == 0) part[(int64_t)ro * nparts] = make_float2(mx[r], se[r]);
+                const int d = tg[r] - c_first;                  // 0, 32, ..: the target is this lane's column of acc[d / 32]
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (d == j * 32) zt[ro] = acc[j][r];
             }
             return;
         }
